@@ -1,0 +1,414 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these re-types the oracle's own formulas on the same path: each is a
+closed form, a law of the combinators (paper section 2), a special case that
+collapses to another routine, or a pure-Python brute force on tiny inputs.
+A planted mistake in the oracle (dropped term, wrong index or sign, swapped
+gather operands, inclusive instead of exclusive scan, unclamped border) makes at
+least one of them fail.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle.interp import evaluate
+from workloads import Graph, build
+from workloads import configs as C
+
+F32 = np.float32
+
+
+def run(g, inputs):
+    return evaluate(g, inputs)
+
+
+# ---------------------------------------------------------------- map / generate / gather laws
+def test_identity_gather_is_noop():
+    rng = np.random.default_rng(1)
+    a = rng.standard_normal(1000).astype(F32)
+    g = Graph()
+    g.add("a", "input", "f32", (1000,))
+    g.add("i", "generate", "i32", (1000,), fn="iota")
+    g.add("b", "gather", "f32", (1000,), args=("i", "a"))
+    assert np.array_equal(run(g, {"a": a})["b"], a)
+
+
+def test_reverse_twice_is_identity_and_reverse_matches_slice():
+    # reverse = gather over generate(n-1-i)  (section 2, `reverse`)
+    a = np.arange(17, dtype=np.int32) * 3 + 1
+    g = Graph()
+    g.add("a", "input", "i32", (17,))
+    g.add("i", "generate", "i32", (17,), fn="iota_rev")
+    g.add("b", "gather", "i32", (17,), args=("i", "a"))
+    g.add("c", "gather", "i32", (17,), args=("i", "b"))
+    env = run(g, {"a": a})
+    assert np.array_equal(env["b"], a[::-1])
+    assert np.array_equal(env["c"], a)
+    assert env["i"][0] == 16 and env["i"][16] == 0
+
+
+def test_gather_argument_roles():
+    # gather(is, as)[j] = as[is[j]]: the first argument indexes, the second is read
+    src = np.array([10, 20, 30, 40], dtype=np.int32)
+    idx = np.array([3, 3, 0], dtype=np.int32)
+    g = Graph()
+    g.add("src", "input", "i32", (4,))
+    g.add("idx", "input", "i32", (3,))
+    g.add("b", "gather", "i32", (3,), args=("idx", "src"))
+    assert run(g, {"src": src, "idx": idx})["b"].tolist() == [40, 40, 10]
+
+
+def test_gather_out_of_range_is_an_error():
+    g = Graph()
+    g.add("src", "input", "i32", (4,))
+    g.add("idx", "input", "i32", (1,))
+    g.add("b", "gather", "i32", (1,), args=("idx", "src"))
+    with pytest.raises(IndexError):
+        run(g, {"src": np.zeros(4, np.int32), "idx": np.array([4], np.int32)})
+
+
+def test_permutation_gather_preserves_multiset_and_commutes_with_map():
+    # `simple1`: gather(is, map f xs) == map f (gather(is, xs)), bit for bit
+    rng = np.random.default_rng(2)
+    n = 4099
+    xs = rng.standard_normal(n).astype(F32)
+    idx = rng.permutation(n).astype(np.int32)
+    g = Graph()
+    g.add("xs", "input", "f32", (n,))
+    g.add("idx", "input", "i32", (n,))
+    g.add("a", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("xs",))
+    g.add("b", "gather", "f32", (n,), args=("idx", "a"))
+    g.add("gx", "gather", "f32", (n,), args=("idx", "xs"))
+    g.add("b2", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("gx",))
+    env = run(g, {"xs": xs, "idx": idx})
+    assert np.array_equal(env["b"], env["b2"])
+    assert np.array_equal(np.sort(env["gx"]), np.sort(xs))
+
+
+def test_gather_of_gather_composes():
+    # `simple2`: gather(is2, gather(is1, xs)) == gather(gather(is2, is1), xs)
+    rng = np.random.default_rng(3)
+    xs = rng.integers(0, 1000, 50, dtype=np.int32)
+    is1 = rng.integers(0, 50, 70, dtype=np.int32)
+    is2 = rng.integers(0, 70, 31, dtype=np.int32)
+    g = Graph()
+    g.add("xs", "input", "i32", (50,))
+    g.add("is1", "input", "i32", (70,))
+    g.add("is2", "input", "i32", (31,))
+    g.add("a", "gather", "i32", (70,), args=("is1", "xs"))
+    g.add("b", "gather", "i32", (31,), args=("is2", "a"))
+    g.add("ii", "gather", "i32", (31,), args=("is2", "is1"))
+    g.add("b2", "gather", "i32", (31,), args=("ii", "xs"))
+    env = run(g, {"xs": xs, "is1": is1, "is2": is2})
+    assert np.array_equal(env["b"], env["b2"])
+
+
+def test_affine_rounds_twice_not_fused():
+    # 2x+1 with separate roundings differs from the single rounding of a fused
+    # multiply-add for some x; pick one by search and pin the two-rounding value
+    a, b = F32(1.0000001), F32(1.0)
+    found = None
+    for k in range(1, 4000):
+        x = F32(1.0) + F32(k) * F32(2.0 ** -23)
+        two = F32(F32(a * x) + b)
+        one = F32(np.float64(a) * np.float64(x) + np.float64(b))
+        if two != one:
+            found = (x, two)
+            break
+    assert found is not None
+    x, two = found
+    g = Graph()
+    g.add("x", "input", "f32", (1,))
+    g.add("y", "map", "f32", (1,), fn="affine", fparam=(float(a), float(b)), args=("x",))
+    assert run(g, {"x": np.array([x], F32)})["y"][0] == two
+
+
+def test_transcendental_maps_against_math_module():
+    xs = np.array([0.0, 0.5, -1.25, 3.0, 1e-3], dtype=F32)
+    g = Graph()
+    g.add("x", "input", "f32", (5,))
+    g.add("s", "map", "f32", (5,), fn="sin_x_mul_x", args=("x",))
+    g.add("e", "map", "f32", (5,), fn="exp_neg", args=("x",))
+    g.add("q", "map", "f32", (5,), fn="sq_plus_one", args=("x",))
+    env = run(g, {"x": xs})
+    for i, x in enumerate(xs.tolist()):
+        assert env["s"][i] == F32(F32(math.sin(x)) * F32(x))
+        assert env["e"][i] == F32(math.exp(-x))
+        assert env["q"][i] == F32(F32(F32(x) * F32(x)) + F32(1))
+    assert env["s"][0] == 0 and env["e"][0] == 1 and env["q"][0] == 1
+
+
+# ---------------------------------------------------------------- fold
+def _fold_graph(n, fn="add", dtype="f32"):
+    g = Graph()
+    g.add("a", "input", dtype, (n,))
+    g.add("r", "fold", dtype, (1,), fn=fn, args=("a",))
+    return g
+
+
+def test_fold_closed_forms():
+    n = 100000
+    c = F32(0.1)
+    env = run(_fold_graph(n), {"a": np.full(n, c, F32)})
+    assert env["r"][0] == pytest.approx(n * float(c), rel=1e-13)
+    env = run(_fold_graph(n, dtype="i32"), {"a": np.arange(n, dtype=np.int32) % 7})
+    assert int(env["r"][0]) == (n // 7) * 21 + sum(range(n % 7))
+    with pytest.raises(OverflowError):                        # int32 results are checked, not wrapped
+        run(_fold_graph(3, dtype="i32"), {"a": np.full(3, 2 ** 30, np.int32)})
+    env = run(_fold_graph(1000, dtype="i32"), {"a": np.arange(1000, dtype=np.int32)})
+    assert int(env["r"][0]) == 1000 * 999 // 2
+    # empty fold = identity of the operator
+    assert run(_fold_graph(0), {"a": np.zeros(0, F32)})["r"][0] == 0.0
+    assert run(_fold_graph(0, "max"), {"a": np.zeros(0, F32)})["r"][0] == -np.inf
+
+
+def test_fold_accumulates_in_fp64_not_fp32():
+    # 2^24 + 1 + 1 ... in fp32 would stall at 2^24
+    a = np.ones(5, F32)
+    a[0] = F32(2.0 ** 24)
+    assert run(_fold_graph(5), {"a": a})["r"][0] == 2.0 ** 24 + 4
+
+
+def test_fold_of_affine_map_is_linear():
+    # fold(+)(map(2x+1) xs) = 2*sum(xs) + n up to the fp32 rounding of each element
+    rng = np.random.default_rng(4)
+    n = 5000
+    xs = (rng.integers(-512, 512, n) / 1024.0).astype(F32)   # 2x+1 exact in fp32
+    g = Graph()
+    g.add("xs", "input", "f32", (n,))
+    g.add("ys", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("xs",))
+    g.add("r", "fold", "f32", (1,), fn="add", args=("ys",))
+    assert run(g, {"xs": xs})["r"][0] == 2.0 * float(np.sum(xs.astype(np.float64))) + n
+
+
+def test_fold_brute_force_tiny():
+    rng = np.random.default_rng(5)
+    for n in range(1, 9):
+        a = rng.standard_normal(n).astype(F32)
+        acc = 0.0
+        mx = -math.inf
+        for v in a.tolist():
+            acc += v
+            mx = max(mx, v)
+        assert run(_fold_graph(n), {"a": a})["r"][0] == pytest.approx(acc, rel=1e-15, abs=1e-15)
+        assert run(_fold_graph(n, "max"), {"a": a})["r"][0] == mx
+
+
+def test_row_fold_reduces_innermost_dimension():
+    a = np.arange(12, dtype=np.int32).reshape(3, 4)
+    g = Graph()
+    g.add("a", "input", "i32", (3, 4))
+    g.add("r", "fold", "i32", (3,), fn="add", args=("a",))
+    assert run(g, {"a": a})["r"].tolist() == [6, 22, 38]
+
+
+def test_cfg1_closed_form_and_reversal_invariance():
+    n = 4096
+    c = F32(0.375)
+    w = C.reverse_dot(xs=np.full(n, c, F32))
+    assert evaluate(w.graph, w.inputs)["r"][0] == n * (2 * 0.375 + 1) ** 2
+    rng = np.random.default_rng(6)
+    xs = rng.uniform(-1, 1, n).astype(F32)
+    r1 = evaluate(C.reverse_dot(xs=xs).graph, {"xs": xs})["r"][0]
+    r2 = evaluate(C.reverse_dot(xs=xs[::-1].copy()).graph, {"xs": xs[::-1].copy()})["r"][0]
+    assert r1 == pytest.approx(r2, rel=1e-13)
+    # brute force
+    ys = [float(F32(F32(2) * x + F32(1))) for x in xs]
+    acc = 0.0
+    for i in range(n):
+        acc += float(F32(F32(ys[i]) * F32(ys[n - 1 - i])))
+    assert r1 == pytest.approx(acc, rel=1e-13)
+
+
+def test_cfg2_identity_vs_random_permutation():
+    rng = np.random.default_rng(7)
+    n = 20000
+    xs = rng.standard_normal(n).astype(F32)
+    ident = np.arange(n, dtype=np.int32)
+    perm = rng.permutation(n).astype(np.int32)
+    r_id = evaluate(C.perm_gather_fold(xs=xs, idx=ident).graph, {"xs": xs, "idx": ident})["r"][0]
+    r_pm = evaluate(C.perm_gather_fold(xs=xs, idx=perm).graph, {"xs": xs, "idx": perm})["r"][0]
+    assert r_id == pytest.approx(r_pm, rel=1e-12)
+    # direct evaluation without any gather
+    z = (np.sin(xs.astype(np.float64)).astype(F32) * xs)
+    wz = (z * z + F32(1)).astype(np.float64)
+    assert r_id == pytest.approx(math.fsum(wz.tolist()), rel=1e-13)
+
+
+# ---------------------------------------------------------------- foldSeg / SpMV
+def test_spmv_unit_values_give_row_lengths():
+    w = C.spmv(rows=3000, seed=11)
+    ins = dict(w.inputs)
+    ins["vals"] = np.ones_like(ins["vals"])
+    ins["x"] = np.ones_like(ins["x"])
+    y = evaluate(w.graph, ins)["y"]
+    assert np.array_equal(y, np.diff(ins["off"]).astype(np.float64))
+
+
+def test_spmv_diagonal_is_elementwise_product():
+    n = 1000
+    rng = np.random.default_rng(12)
+    w = C.spmv(lengths=np.ones(n, np.int64), seed=12)
+    ins = dict(w.inputs)
+    ins["col"] = np.arange(n, dtype=np.int32)
+    y = evaluate(w.graph, ins)["y"]
+    assert np.array_equal(y.astype(F32), ins["vals"] * ins["x"])
+
+
+def test_spmv_vs_dense_and_empty_rows():
+    lengths = np.array([0, 3, 0, 0, 5, 1, 0, 40, 2, 0], dtype=np.int64)
+    w = C.spmv(lengths=lengths, seed=13, ncols=10)
+    ins = w.inputs
+    rows = len(lengths)
+    dense = np.zeros((rows, 10), dtype=np.float64)
+    for r in range(rows):
+        for k in range(ins["off"][r], ins["off"][r + 1]):
+            dense[r, ins["col"][k]] += float(F32(ins["vals"][k] * ins["x"][ins["col"][k]]))
+    y = evaluate(w.graph, ins)["y"]
+    assert y.shape == (rows,)
+    assert np.allclose(y, dense.sum(axis=1), rtol=1e-14, atol=1e-15)
+    assert all(y[r] == 0.0 for r in range(rows) if lengths[r] == 0)
+
+
+def test_spmv_row_sums_total_and_single_row():
+    w = C.spmv(rows=2000, seed=14)
+    env = evaluate(w.graph, w.inputs)
+    assert math.fsum(env["y"].tolist()) == pytest.approx(
+        math.fsum(env["p"].astype(np.float64).tolist()), rel=1e-12)
+    # all elements in one row = a plain fold
+    nnz = int(w.inputs["off"][-1])
+    w1 = C.spmv(lengths=np.array([nnz], np.int64), seed=14, ncols=2000)
+    y1 = evaluate(w1.graph, w1.inputs)
+    assert y1["y"][0] == pytest.approx(math.fsum(y1["p"].astype(np.float64).tolist()), rel=1e-13)
+
+
+def test_foldseg_max_and_leading_trailing_empty():
+    vals = np.array([1, 5, 2, 9, 4], dtype=np.int32)
+    off = np.array([0, 0, 2, 2, 5, 5], dtype=np.int32)
+    g = Graph()
+    g.add("v", "input", "i32", (5,))
+    g.add("off", "input", "i32", (6,))
+    g.add("y", "foldseg", "i32", (5,), fn="max", args=("v", "off"))
+    y = run(g, {"v": vals, "off": off})["y"]
+    lo = np.iinfo(np.int32).min
+    assert y.tolist() == [lo, 5, lo, 9, lo]
+    g2 = Graph()
+    g2.add("v", "input", "i32", (5,))
+    g2.add("off", "input", "i32", (6,))
+    g2.add("y", "foldseg", "i32", (5,), fn="add", args=("v", "off"))
+    assert run(g2, {"v": vals, "off": off})["y"].tolist() == [0, 6, 0, 15, 0]
+
+
+# ---------------------------------------------------------------- scan / scatter / compaction
+def test_scan_is_exclusive():
+    a = np.array([3, 1, 4, 1, 5, 9, 2, 6], dtype=np.int32)
+    g = Graph()
+    g.add("a", "input", "i32", (8,))
+    g.add("l", "scanl", "i32", (8,), fn="add", args=("a",))
+    g.add("r", "scanr", "i32", (8,), fn="add", args=("a",))
+    env = run(g, {"a": a})
+    run_sum, expect = 0, []
+    for v in a.tolist():
+        expect.append(run_sum)
+        run_sum += v
+    assert env["l"].tolist() == expect
+    # scanr: everything later
+    assert env["r"].tolist() == [sum(a.tolist()[i + 1:]) for i in range(8)]
+    ones = np.ones(1000, np.int32)
+    g1 = Graph()
+    g1.add("a", "input", "i32", (1000,))
+    g1.add("l", "scanl", "i32", (1000,), fn="add", args=("a",))
+    assert np.array_equal(run(g1, {"a": ones})["l"], np.arange(1000, dtype=np.int32))
+
+
+def test_compaction_invariants():
+    w = C.compaction(n=50021, seed=21)
+    env = evaluate(w.graph, w.inputs)
+    v, flags, offs, out = w.inputs["v"], env["flags"], env["offs"], env["out"]
+    count = int(env["count"][0])
+    assert offs[0] == 0
+    assert np.array_equal(np.diff(offs), flags[:-1])
+    assert count == int(offs[-1] + flags[-1]) == w.extra["kept"]          # count = scan total
+    keep = [int(x) for x in v.tolist() if x % 3 == 0]                    # stable filtered subsequence
+    assert out[:count].tolist() == keep
+    assert np.all(out[count:] == -1)                                      # untouched part of dest
+    # statistical pin on the generator + predicate: p = 715827883 / 2^31
+    p = 715827883 / 2 ** 31
+    assert abs(count - 50021 * p) < 4 * math.sqrt(50021 * p * (1 - p))
+
+
+def test_compaction_closed_form_iota():
+    n = 1000
+    w = C.compaction(v=np.arange(n, dtype=np.int32))
+    env = evaluate(w.graph, w.inputs)
+    count = int(env["count"][0])
+    assert count == (n + 2) // 3
+    assert env["out"][:count].tolist() == [3 * k for k in range(count)]
+
+
+def test_scatter_semantics():
+    g = Graph()
+    g.add("dest", "input", "i32", (6,))
+    g.add("i", "input", "i32", (4,))
+    g.add("x", "input", "i32", (4,))
+    g.add("f", "input", "i32", (4,))
+    g.add("o", "scatter", "i32", (6,), fn="overwrite", args=("dest", "i", "x", "f"))
+    g.add("a", "scatter", "i32", (6,), fn="add", args=("dest", "i", "x"))
+    ins = {"dest": np.arange(6, dtype=np.int32) * 100,
+           "i": np.array([5, 0, 5, 2], np.int32), "x": np.array([1, 2, 3, 4], np.int32),
+           "f": np.array([1, 1, 0, 1], np.int32)}
+    env = run(g, ins)
+    assert env["o"].tolist() == [2, 100, 4, 300, 400, 1]
+    assert env["a"].tolist() == [2, 100, 204, 300, 400, 504]       # colliding (+) combines
+    assert ins["dest"].tolist() == [0, 100, 200, 300, 400, 500]    # the oracle works on a copy
+    ins2 = dict(ins, f=np.ones(4, np.int32))
+    with pytest.raises(ValueError):
+        run(g, ins2)                                                # colliding overwrite is rejected
+    with pytest.raises(IndexError):
+        run(g, dict(ins, i=np.array([6, 0, 5, 2], np.int32)))
+
+
+# ---------------------------------------------------------------- stencil + max
+def test_stencil_constant_grid_pins_clamping():
+    c = F32(0.3)
+    w = C.stencil_max(grid=np.full((7, 9), c, F32))
+    env = evaluate(w.graph, w.inputs)
+    e = F32(math.exp(-float(c)))
+    assert np.all(env["out"] == F32(F32(F32(F32(e + e) + e) + e) + e))   # borders included
+    assert env["m"][0] == float(e)
+
+
+def test_stencil_brute_force_and_max_monotone():
+    rng = np.random.default_rng(31)
+    for (h, w_) in ((3, 3), (1, 8), (5, 1), (4, 6)):
+        grid = rng.uniform(0, 1, (h, w_)).astype(F32)
+        wk = C.stencil_max(grid=grid)
+        env = evaluate(wk.graph, wk.inputs)
+        p = [[F32(math.exp(-float(grid[i, j]))) for j in range(w_)] for i in range(h)]
+        for i in range(h):
+            for j in range(w_):
+                n_, s_ = p[max(i - 1, 0)][j], p[min(i + 1, h - 1)][j]
+                w__, e_ = p[i][max(j - 1, 0)], p[i][min(j + 1, w_ - 1)]
+                want = F32(F32(F32(F32(p[i][j] + n_) + s_) + w__) + e_)
+                assert env["out"][i, j] == want, (h, w_, i, j)
+        assert env["m"][0] == float(F32(math.exp(-float(grid.min()))))
+
+
+def test_stencil_row_only_grid():
+    # a grid that depends on the row only: west and east terms equal the centre
+    h, w_ = 6, 5
+    grid = np.repeat(np.linspace(0, 1, h, dtype=F32)[:, None], w_, axis=1)
+    wk = C.stencil_max(grid=grid)
+    env = evaluate(wk.graph, wk.inputs)
+    assert np.array_equal(env["pW"], env["p"]) and np.array_equal(env["pE"], env["p"])
+    assert np.array_equal(env["pN"][1:], env["p"][:-1]) and np.array_equal(env["pN"][0], env["p"][0])
+    assert np.array_equal(env["pS"][:-1], env["p"][1:]) and np.array_equal(env["pS"][-1], env["p"][-1])
+
+
+def test_all_small_configs_evaluate():
+    for c in (1, 2, 3, 4, 5):
+        w = build(c, small=True)
+        env = evaluate(w.graph, w.inputs)
+        for o in w.graph.outputs():
+            assert env[o].shape == tuple(w.graph[o].shape)

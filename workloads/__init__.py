@@ -1,0 +1,8 @@
+"""Program descriptions and seeded inputs shared by the oracle, the HIP binding, the tests and the bench.
+
+Data only: no combinator is evaluated and no partition is chosen in this package.
+"""
+from .graph import Graph, Node
+from .configs import Workload, build, BUILDERS, SMALL, SEED0
+
+__all__ = ["Graph", "Node", "Workload", "build", "BUILDERS", "SMALL", "SEED0"]
