@@ -1,0 +1,214 @@
+/*
+ * fc.h -- C ABI of the fused-combinator library for AMD MI355X (gfx950).
+ *
+ * The library executes array-combinator programs (paper section 2, "Language")
+ * as fused clusters (section 3, "Fusion"): map / zipWith / generate producers
+ * are evaluated in registers, pushed through gathers, and consumed by a fold, a
+ * segmented fold, a single-pass scan or a scatter, so that no intermediate
+ * array reaches memory.  Which combinators share a loop is described by a
+ * clustering (section 4.1: pi, x, m; section 4.2: traversal orders) that
+ * fc_plan() chooses by solving the paper's integer linear program exactly.
+ *
+ * Everything here is plain C: POD structs, raw pointers, sizes.  No exception
+ * crosses the boundary; every function returns FC_OK (0) or a negative error
+ * code and leaves a message for fc_last_error().
+ *
+ * Pointers are HOST pointers unless a comment says DEVICE.
+ */
+#ifndef FC_H
+#define FC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---------------------------------------------------------------- error codes */
+#define FC_OK                   0
+#define FC_E_BADGRAPH          -1  /* cycle / arity / dtype / shape mismatch, unknown function  */
+#define FC_E_ILLEGAL_PARTITION -2  /* breaks a rule of section 3.4 or a constraint of Fig. "Total ILP formulation" */
+#define FC_E_UNSUPPORTED       -3  /* legal cluster, but no kernel instance is built for its shape */
+#define FC_E_UNBOUND           -4  /* an input or manifest array has no device buffer, or it is too small / misaligned */
+#define FC_E_SCRATCH           -5  /* scratch missing, misaligned or smaller than fc_scratch_bytes() */
+#define FC_E_HIP               -6  /* a HIP runtime call failed (message holds hipGetErrorString) */
+#define FC_E_ARG               -7  /* NULL / out-of-range argument, capacity too small */
+#define FC_E_LIMIT             -8  /* graph too large for the exact chooser, or a size above 2^31-1 elements */
+
+/* ---------------------------------------------------------------- vocabulary */
+/* Combinators of the language (section 2; Table 1 gives their cluster signatures).
+ * One node = one combinator = the array it produces. */
+typedef enum fc_kind {
+  FC_INPUT    = 0,  /* array handed in by the caller; every edge out of it is infusible (section 3.4) */
+  FC_MAP      = 1,  /* n-ary map: zipWith after the SoA transformation (section 2, last paragraph) */
+  FC_GENERATE = 2,  /* ys[i] = f(i) */
+  FC_GATHER   = 3,  /* ys[j] = src[idx[j]]; arg0 = idx (read in output order), arg1 = src (read in the gather's own order) */
+  FC_FOLD     = 4,  /* shape (1): fold of the flattened argument; else fold of the innermost dimension */
+  FC_FOLDSEG  = 5,  /* arg0 = flat values, arg1 = offsets[R+1] (infusible); y[r] = fold of values[off[r], off[r+1]) */
+  FC_SCANL    = 6,  /* exclusive prefix combine, identity seeded; traversal order 0 */
+  FC_SCANR    = 7,  /* exclusive suffix combine; traversal order 1 */
+  FC_SCATTER  = 8,  /* arg0 = dest (infusible, updated in place), arg1 = index, arg2 = value, arg3 = flag (optional) */
+  FC_FORCE    = 9   /* identity; every edge out of it is infusible */
+} fc_kind;
+
+typedef enum fc_dtype { FC_F32 = 0, FC_I32 = 1 } fc_dtype;
+
+/* Element functions (the paper allows arbitrary lambdas; the kernels here are
+ * hand written, so the lambdas form a closed vocabulary). */
+typedef enum fc_fn {
+  FC_FN_NONE = 0,
+  /* map functions; fp32 arithmetic is rounded operation by operation (never contracted) */
+  FC_FN_IDENT = 1,        /* x                                           */
+  FC_FN_AFFINE = 2,       /* fparam[0]*x + fparam[1]                     */
+  FC_FN_SIN_X_MUL_X = 3,  /* sin(x)*x                                    */
+  FC_FN_SQ_PLUS_ONE = 4,  /* x*x + 1                                     */
+  FC_FN_MUL2 = 5,         /* a*b                                         */
+  FC_FN_ADD2 = 6,         /* a+b                                         */
+  FC_FN_ADD3 = 7,         /* (a+b)+c                                     */
+  FC_FN_ADD5 = 8,         /* (((a+b)+c)+d)+e                             */
+  FC_FN_EXP_NEG = 9,      /* exp(-x)                                     */
+  FC_FN_MOD_EQ = 10,      /* i32 -> i32: (x mod iparam[0] == iparam[1]) ? 1 : 0, x >= 0 */
+  /* generate functions (index -> i32) */
+  FC_FN_IOTA = 32,            /* i                                                       */
+  FC_FN_IOTA_REV = 33,        /* n-1-i                                                   */
+  FC_FN_CLAMP_SHIFT_2D = 34,  /* (i,j) -> clamp(i+iparam[0],0,H-1)*W + clamp(j+iparam[1],0,W-1) */
+  FC_FN_ROW_OF_2D = 35,       /* (i,j) -> i                                              */
+  FC_FN_CONST_I32 = 36,       /* iparam[0]                                               */
+  /* reducers of fold / foldSeg / scan and combination functions of scatter */
+  FC_OP_ADD = 64,
+  FC_OP_MAX = 65,
+  FC_OP_MUL = 66,
+  FC_OP_OVERWRITE = 67        /* scatter only: the new value wins (section 2.1) */
+} fc_fn;
+
+#define FC_MAX_ARGS 6
+
+/* node flags */
+#define FC_NODE_OUTPUT 1u   /* a result of the program: must be manifest (m = 0) */
+
+typedef struct fc_node {
+  int32_t  kind;              /* fc_kind  */
+  int32_t  dtype;             /* fc_dtype of the produced array */
+  int32_t  fn;                /* fc_fn    */
+  float    fparam[2];
+  int32_t  iparam[4];
+  int32_t  nargs;
+  int32_t  arg[FC_MAX_ARGS];  /* indices of the producing nodes; each < own index (topological order) */
+  int32_t  rank;              /* 1 or 2 */
+  int64_t  shape[2];          /* row-major extents; unused extents are 1 */
+  uint32_t flags;
+} fc_node;
+
+/* The data dependence graph (n, N, F, I) of section 4.1.  Edges are implied by
+ * the argument lists; edge e is the e-th (consumer ascending, slot ascending)
+ * argument reference.  Fusible / infusible follows from the kinds (inputs,
+ * force, scatter destination and scatter result, foldSeg offsets are infusible). */
+typedef struct fc_graph {
+  int32_t        n;
+  const fc_node *nodes;
+} fc_graph;
+
+/* A clustering in the variables of Fig. "Total ILP formulation".  All arrays are
+ * caller allocated: n_nodes entries for the per-node arrays, n_edges for the
+ * per-edge array. */
+typedef struct fc_partition {
+  int32_t  n_nodes;       /* capacity of pi / fused_away / order_out (in) */
+  int32_t  n_edges;       /* capacity of edge_unfused (in)                */
+  int32_t *pi;            /* cluster number; clusters run in ascending order           */
+  uint8_t *fused_away;    /* m_a: 1 = the array never reaches memory, 0 = manifest      */
+  int32_t *order_out;     /* d^o_a: 0, 1 or the label (2 + ordinal) of a gather         */
+  uint8_t *edge_unfused;  /* x_ab: 0 = fused over, 1 = not                              */
+  int32_t  n_clusters;    /* (out) clusters after the connected-component split         */
+  double   cost;          /* (out) value of the requested cost function                 */
+} fc_partition;
+
+/* cost functions of section 4.1 ("Cost function"), evaluated on the ILP solution */
+typedef enum fc_cost {
+  FC_COST_CLUSTERS    = 0,  /* (a) largest cluster number + 1                                  */
+  FC_COST_FUSED_EDGES = 1,  /* (b) sum of x over fusible edges                                 */
+  FC_COST_ARRAYS      = 2,  /* (c) number of manifest non-input arrays                         */
+  FC_COST_READS       = 3,  /* (d) array reads: one per (array, consuming cluster, order)      */
+  FC_COST_READS_WRITES= 4,  /* (e) reads + manifest arrays                                     */
+  FC_COST_BYTES       = 5   /* (e) with every read / write weighted by the array's bytes       */
+} fc_cost;
+
+/* plan flags */
+#define FC_PLAN_NO_SPLIT 1u  /* keep the raw ILP solution (skip the connected-component split) */
+
+typedef struct fc_buffer {
+  void   *ptr;    /* DEVICE pointer, 16-byte aligned; NULL = not bound */
+  int64_t bytes;
+} fc_buffer;
+
+/* ---------------------------------------------------------------- planning (host only) */
+
+/* Number of edges of the graph (length of fc_partition.edge_unfused). */
+int fc_num_edges(const fc_graph *g, int32_t *n_edges);
+
+/* Choose the clustering that minimises `cost_fn` subject to the constraints of
+ * Fig. "Total ILP formulation" (sections 4.1, 4.2), by exact branch and bound over
+ * the edge variables x, then split clusters into connected components (section
+ * 4.1, "Performance and correctness").  Fills every array of *out, n_clusters and
+ * cost.  Graphs of more than 64 non-input nodes are refused (FC_E_LIMIT). */
+int fc_plan(const fc_graph *g, int cost_fn, uint32_t flags, fc_partition *out);
+
+/* The clustering with every combinator in a cluster of its own (no fusion). */
+int fc_partition_trivial(const fc_graph *g, fc_partition *out);
+
+/* Check a clustering against the rules of section 3.4 and the ILP constraints;
+ * only pi is read, the other arrays and n_clusters are (re)derived and written.
+ * *cost receives the value of cost_fn for it (may be NULL). */
+int fc_partition_check(const fc_graph *g, fc_partition *p, int cost_fn, double *cost);
+
+/* Work duplication (named in sections 1 and 6, outside the paper's ILP): clone
+ * every map / generate node that a gather reads as its source and that has other
+ * consumers, once per such gather, so that each clone has a single traversal
+ * order.  Writes the rewritten graph to out_nodes (capacity entries), its size to
+ * *out_n, and for each new node the index of the node it came from to origin. */
+int fc_duplicate(const fc_graph *g, fc_node *out_nodes, int32_t capacity, int32_t *out_n, int32_t *origin);
+
+/* ---------------------------------------------------------------- execution (device work) */
+
+/* Bytes of device scratch fc_run_* needs for this graph and clustering
+ * (p == NULL: the unfused clustering). */
+int fc_scratch_bytes(const fc_graph *g, const fc_partition *p, size_t *bytes);
+
+/* Execute the program cluster by cluster, one kernel launch per cluster, on
+ * `hip_stream` (a hipStream_t; NULL = the default stream).  The call only
+ * enqueues work and returns; results are valid after the stream is synchronised.
+ *
+ * bufs[i] is the DEVICE buffer of node i.  Inputs and manifest arrays (m = 0) of
+ * the clustering must be bound, fused-away arrays are ignored.  Arrays made
+ * manifest by the clustering but not bound by the caller are placed in scratch.
+ * A scatter updates its destination buffer in place (section 2, scatter), its own
+ * buffer must be NULL or equal to the destination's.  Scalar results (fold of
+ * shape (1)) are 4-byte device buffers.  Gather and scatter indices out of range
+ * are undefined behaviour, as in the paper.
+ *
+ * scratch: DEVICE, 256-byte aligned, at least fc_scratch_bytes().  Its first
+ * FC_SCRATCH_CONTROL_BYTES must be zero the first time a buffer is used; every
+ * call leaves them ready for the next one.  Two calls that overlap in time must
+ * not share a scratch buffer. */
+int fc_run_fused(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs,
+                 void *scratch, size_t scratch_bytes, void *hip_stream);
+
+/* Same program, no fusion: one kernel per combinator, every intermediate array
+ * (generated index arrays included) materialised in scratch unless bound. */
+int fc_run_unfused(const fc_graph *g, const fc_buffer *bufs,
+                   void *scratch, size_t scratch_bytes, void *hip_stream);
+
+/* Name of the kernel instance chosen for cluster `cluster` of the clustering
+ * (p == NULL: the unfused clustering), for reports and profiles. */
+int fc_cluster_kernel(const fc_graph *g, const fc_partition *p, int32_t cluster,
+                      char *name, size_t capacity);
+
+#define FC_SCRATCH_CONTROL_BYTES (1u << 23)
+
+/* Message of the last error on the calling thread; valid until the next call. */
+const char *fc_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FC_H */

@@ -1,0 +1,209 @@
+// extern "C" entry points (include/fc.h).  Argument checking and marshalling
+// only; no exception leaves this file.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <exception>
+#include <string>
+
+#include "model.hpp"
+#include "plan.hpp"
+#include "run.hpp"
+
+namespace {
+
+thread_local std::string g_error;
+
+int fail(int code, const std::string &msg) {
+  g_error = msg;
+  return code;
+}
+
+template <class F> int guarded(F &&f) {
+  try {
+    g_error.clear();
+    return f();
+  } catch (const std::exception &e) {
+    return fail(FC_E_ARG, std::string("internal error: ") + e.what());
+  } catch (...) {
+    return fail(FC_E_ARG, "internal error");
+  }
+}
+
+int fill_partition(const fc::Model &m, const fc::Clustering &c, int n_clusters, double cost, fc_partition *out) {
+  if (!out || out->n_nodes < m.n || out->n_edges < (int)m.edges.size())
+    return fail(FC_E_ARG, "partition arrays are too small");
+  if (m.n && (!out->pi || !out->fused_away || !out->order_out)) return fail(FC_E_ARG, "null partition array");
+  if (!m.edges.empty() && !out->edge_unfused) return fail(FC_E_ARG, "null partition array");
+  for (int a = 0; a < m.n; ++a) {
+    out->pi[a] = c.pi[a];
+    out->fused_away[a] = c.fused_away[a];
+    out->order_out[a] = c.order_out[a];
+  }
+  for (size_t e = 0; e < m.edges.size(); ++e) out->edge_unfused[e] = c.x[e];
+  out->n_clusters = n_clusters;
+  out->cost = cost;
+  return FC_OK;
+}
+
+int load_clustering(const fc::Model &m, const fc_partition *p, fc::Clustering &c, std::string &err) {
+  std::vector<int> pi(m.n);
+  if (p) {
+    if (p->n_nodes < m.n || (m.n && !p->pi)) { err = "partition does not cover the graph"; return FC_E_ARG; }
+    for (int a = 0; a < m.n; ++a) pi[a] = p->pi[a];
+  } else {
+    for (int a = 0; a < m.n; ++a) pi[a] = a;   // every combinator on its own, in program order
+  }
+  return fc::derive_and_check(m, pi, c, err);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *fc_last_error(void) { return g_error.c_str(); }
+
+int fc_num_edges(const fc_graph *g, int32_t *n_edges) {
+  return guarded([&]() {
+    fc::Model m;
+    std::string err;
+    int rc = fc::build_model(g, m, err);
+    if (rc != FC_OK) return fail(rc, err);
+    if (!n_edges) return fail(FC_E_ARG, "null result pointer");
+    *n_edges = (int32_t)m.edges.size();
+    return FC_OK;
+  });
+}
+
+int fc_plan(const fc_graph *g, int cost_fn, uint32_t flags, fc_partition *out) {
+  return guarded([&]() {
+    fc::Model m;
+    std::string err;
+    int rc = fc::build_model(g, m, err);
+    if (rc != FC_OK) return fail(rc, err);
+    fc::Clustering c;
+    int n_clusters = 0;
+    double cost = 0;
+    rc = fc::choose_clustering(m, cost_fn, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err);
+    if (rc != FC_OK) return fail(rc, err);
+    return fill_partition(m, c, n_clusters, cost, out);
+  });
+}
+
+int fc_partition_trivial(const fc_graph *g, fc_partition *out) {
+  return guarded([&]() {
+    fc::Model m;
+    std::string err;
+    int rc = fc::build_model(g, m, err);
+    if (rc != FC_OK) return fail(rc, err);
+    fc::Clustering c;
+    rc = load_clustering(m, nullptr, c, err);
+    if (rc != FC_OK) return fail(rc, err);
+    int k = fc::renumber_levels(m, c);
+    return fill_partition(m, c, k, fc::evaluate_cost(m, c, FC_COST_READS_WRITES), out);
+  });
+}
+
+int fc_partition_check(const fc_graph *g, fc_partition *p, int cost_fn, double *cost) {
+  return guarded([&]() {
+    fc::Model m;
+    std::string err;
+    int rc = fc::build_model(g, m, err);
+    if (rc != FC_OK) return fail(rc, err);
+    if (!p) return fail(FC_E_ARG, "null partition");
+    fc::Clustering c;
+    rc = load_clustering(m, p, c, err);
+    if (rc != FC_OK) return fail(rc, err);
+    double v = fc::evaluate_cost(m, c, cost_fn);
+    if (v < 0) return fail(FC_E_ARG, "unknown cost function");
+    if (cost) *cost = v;
+    int k = (int)fc::clusters_of(m, c).size();
+    return fill_partition(m, c, k, v, p);
+  });
+}
+
+int fc_duplicate(const fc_graph *g, fc_node *out_nodes, int32_t capacity, int32_t *out_n, int32_t *origin) {
+  return guarded([&]() {
+    fc::Model m;
+    std::string err;
+    int rc = fc::build_model(g, m, err);
+    if (rc != FC_OK) return fail(rc, err);
+    std::vector<fc_node> nodes;
+    std::vector<int> org;
+    rc = fc::duplicate_producers(m, nodes, org);
+    if (rc != FC_OK) return fail(rc, "duplication failed");
+    if (!out_n) return fail(FC_E_ARG, "null result pointer");
+    *out_n = (int32_t)nodes.size();
+    if ((int)nodes.size() > capacity || !out_nodes) return fail(FC_E_ARG, "node capacity too small");
+    for (size_t i = 0; i < nodes.size(); ++i) {
+      out_nodes[i] = nodes[i];
+      if (origin) origin[i] = org[i];
+    }
+    return FC_OK;
+  });
+}
+
+int fc_scratch_bytes(const fc_graph *g, const fc_partition *p, size_t *bytes) {
+  return guarded([&]() {
+    fc::Model m;
+    std::string err;
+    int rc = fc::build_model(g, m, err);
+    if (rc != FC_OK) return fail(rc, err);
+    fc::Clustering c;
+    rc = load_clustering(m, p, c, err);
+    if (rc != FC_OK) return fail(rc, err);
+    if (!bytes) return fail(FC_E_ARG, "null result pointer");
+    *bytes = fc::scratch_bytes_for(m, c);
+    return FC_OK;
+  });
+}
+
+static int run_common(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs, void *scratch,
+                      size_t scratch_bytes, void *hip_stream) {
+  fc::Model m;
+  std::string err;
+  int rc = fc::build_model(g, m, err);
+  if (rc != FC_OK) return fail(rc, err);
+  fc::Clustering c;
+  rc = load_clustering(m, p, c, err);
+  if (rc != FC_OK) return fail(rc, err);
+  rc = fc::run_clustering(m, c, bufs, scratch, scratch_bytes, static_cast<hipStream_t>(hip_stream), err);
+  if (rc != FC_OK) return fail(rc, err);
+  return FC_OK;
+}
+
+int fc_run_fused(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs, void *scratch, size_t scratch_bytes,
+                 void *hip_stream) {
+  return guarded([&]() {
+    if (!p) return fail(FC_E_ARG, "null partition");
+    return run_common(g, p, bufs, scratch, scratch_bytes, hip_stream);
+  });
+}
+
+int fc_run_unfused(const fc_graph *g, const fc_buffer *bufs, void *scratch, size_t scratch_bytes, void *hip_stream) {
+  return guarded([&]() { return run_common(g, nullptr, bufs, scratch, scratch_bytes, hip_stream); });
+}
+
+int fc_cluster_kernel(const fc_graph *g, const fc_partition *p, int32_t cluster, char *name, size_t capacity) {
+  return guarded([&]() {
+    fc::Model m;
+    std::string err;
+    int rc = fc::build_model(g, m, err);
+    if (rc != FC_OK) return fail(rc, err);
+    fc::Clustering c;
+    rc = load_clustering(m, p, c, err);
+    if (rc != FC_OK) return fail(rc, err);
+    auto cl = fc::clusters_of(m, c);
+    if (cluster < 0 || cluster >= (int)cl.size()) return fail(FC_E_ARG, "cluster index out of range");
+    fc::ClusterLaunch launch;
+    rc = fc::plan_cluster(m, c, cl[cluster], launch, err);
+    if (rc != FC_OK) return fail(rc, err);
+    std::string s = launch.sig;
+    if (launch.instance && launch.instance->variant[0]) s += std::string(" {") + launch.instance->variant + "}";
+    if (!name || capacity < s.size() + 1) return fail(FC_E_ARG, "name buffer too small");
+    std::memcpy(name, s.c_str(), s.size() + 1);
+    return FC_OK;
+  });
+}
+
+}  // extern "C"

@@ -1,0 +1,190 @@
+// Element-level programs of a fused cluster as expression types.
+//
+// A cluster's producers (map / zipWith, generate, gather; Table 1) form a tree
+// that is evaluated in registers for one iteration index.  A gather pushes its
+// index through the producers of its source (section 3.3, `simple1`,
+// `simple2`): Gather<EI, ES> evaluates ES at the index EI yields, so a producer
+// below a gather is recomputed at the gathered position and never stored.
+//
+// Every expression type offers
+//   eval(args, i)     value at iteration index i
+//   eval4(args, i)    values at i .. i+3 (i a multiple of 4), 128-bit loads on leaves
+//   sig(std::string&) the textual signature the host matcher compares against
+//   kNodes            number of combinator nodes in the tree (parameter slots)
+// Parameter slots are numbered in pre-order, leaves included.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <tuple>
+#include <utility>
+
+#include "prim.hpp"
+
+namespace fc {
+
+constexpr int kMaxIn = 8;
+constexpr int kMaxOut = 4;
+constexpr int kMaxSlots = 24;
+
+struct Slot {     // parameters of one combinator node
+  float f[2];
+  int i[2];       // the node's own integer parameters
+  int ext[2];     // the node's own extents (outer, inner); inner is 1 for 1-D arrays
+};
+
+struct KArgs {    // arguments of one cluster launch
+  const void *in[kMaxIn];   // external arrays read by the cluster
+  void *out[kMaxOut];       // arrays the cluster writes
+  int n;                    // iteration size
+  int w;                    // inner extent of 2-D index functions (1 for 1-D)
+  int h;                    // outer extent
+  int aux;                  // skeleton specific (rows of a segmented fold, ...)
+  Slot p[kMaxSlots];
+};
+
+template <class T> struct Vec4 { T v[4]; };
+
+template <class T> struct DtypeName;
+template <> struct DtypeName<float> { static const char *s() { return "f32"; } };
+template <> struct DtypeName<int> { static const char *s() { return "i32"; } };
+
+// ------------------------------------------------------------------ element functions
+struct FnIdentF { using R = float; static constexpr int kFn = FC_FN_IDENT;
+  static __device__ __forceinline__ R apply(const Slot &, float x) { return x; } };
+struct FnIdentI { using R = int; static constexpr int kFn = FC_FN_IDENT;
+  static __device__ __forceinline__ R apply(const Slot &, int x) { return x; } };
+struct FnAffine { using R = float; static constexpr int kFn = FC_FN_AFFINE;
+  static __device__ __forceinline__ R apply(const Slot &s, float x) { float t = s.f[0] * x; return t + s.f[1]; } };
+struct FnSinXMulX { using R = float; static constexpr int kFn = FC_FN_SIN_X_MUL_X;
+  static __device__ __forceinline__ R apply(const Slot &, float x) { return sinf(x) * x; } };
+struct FnSqPlusOne { using R = float; static constexpr int kFn = FC_FN_SQ_PLUS_ONE;
+  static __device__ __forceinline__ R apply(const Slot &, float x) { float t = x * x; return t + 1.0f; } };
+struct FnMul2 { using R = float; static constexpr int kFn = FC_FN_MUL2;
+  static __device__ __forceinline__ R apply(const Slot &, float a, float b) { return a * b; } };
+struct FnAdd2 { using R = float; static constexpr int kFn = FC_FN_ADD2;
+  static __device__ __forceinline__ R apply(const Slot &, float a, float b) { return a + b; } };
+struct FnAdd3 { using R = float; static constexpr int kFn = FC_FN_ADD3;
+  static __device__ __forceinline__ R apply(const Slot &, float a, float b, float c) { return (a + b) + c; } };
+struct FnAdd5 { using R = float; static constexpr int kFn = FC_FN_ADD5;
+  static __device__ __forceinline__ R apply(const Slot &, float a, float b, float c, float d, float e) {
+    return (((a + b) + c) + d) + e; } };
+struct FnExpNeg { using R = float; static constexpr int kFn = FC_FN_EXP_NEG;
+  static __device__ __forceinline__ R apply(const Slot &, float x) { return expf(-x); } };
+struct FnModEq { using R = int; static constexpr int kFn = FC_FN_MOD_EQ;
+  static __device__ __forceinline__ R apply(const Slot &s, int x) {
+    return ((unsigned)x % (unsigned)s.i[0]) == (unsigned)s.i[1] ? 1 : 0; } };
+
+// index functions of generate
+struct GenIota { static constexpr int kFn = FC_FN_IOTA;
+  static __device__ __forceinline__ int apply(const Slot &, const KArgs &, int i) { return i; } };
+struct GenIotaRev { static constexpr int kFn = FC_FN_IOTA_REV;
+  static __device__ __forceinline__ int apply(const Slot &s, const KArgs &, int i) { return s.ext[0] * s.ext[1] - 1 - i; } };
+struct GenClampShift2D { static constexpr int kFn = FC_FN_CLAMP_SHIFT_2D;
+  static __device__ __forceinline__ int apply(const Slot &s, const KArgs &, int i) {
+    const int h = s.ext[0], w = s.ext[1];
+    int r = i / w, c = i - r * w;
+    r = min(max(r + s.i[0], 0), h - 1);
+    c = min(max(c + s.i[1], 0), w - 1);
+    return r * w + c; } };
+struct GenRowOf2D { static constexpr int kFn = FC_FN_ROW_OF_2D;
+  static __device__ __forceinline__ int apply(const Slot &s, const KArgs &, int i) { return i / s.ext[1]; } };
+struct GenConst { static constexpr int kFn = FC_FN_CONST_I32;
+  static __device__ __forceinline__ int apply(const Slot &s, const KArgs &, int) { return s.i[0]; } };
+
+// ------------------------------------------------------------------ expression nodes
+// external array number K of the cluster, element type T
+template <int K, class T>
+struct In {
+  using R = T;
+  static constexpr int kNodes = 1;
+  template <int Base> static __device__ __forceinline__ T eval(const KArgs &a, int i) {
+    return static_cast<const T *>(a.in[K])[i];
+  }
+  template <int Base> static __device__ __forceinline__ Vec4<T> eval4(const KArgs &a, int i) {
+    using V = T __attribute__((ext_vector_type(4)));
+    V v = __builtin_nontemporal_load(reinterpret_cast<const V *>(static_cast<const T *>(a.in[K]) + i));
+    return Vec4<T>{{v.x, v.y, v.z, v.w}};
+  }
+  static void sig(std::string &s) { s += "in" + std::to_string(K) + ":" + DtypeName<T>::s(); }
+};
+
+template <int Base, int K, class... E> struct ChildBase;
+template <int Base, class E0, class... E> struct ChildBase<Base, 0, E0, E...> { static constexpr int value = Base; };
+template <int Base, int K, class E0, class... E> struct ChildBase<Base, K, E0, E...> {
+  static constexpr int value = ChildBase<Base + E0::kNodes, K - 1, E...>::value;
+};
+
+template <class F, class... E>
+struct Map {
+  using R = typename F::R;
+  static constexpr int kNodes = 1 + (E::kNodes + ... + 0);
+  template <int Base, int... K>
+  static __device__ __forceinline__ R eval_(const KArgs &a, int i, std::integer_sequence<int, K...>) {
+    return F::apply(a.p[Base], E::template eval<ChildBase<Base + 1, K, E...>::value>(a, i)...);
+  }
+  template <int Base> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
+    return eval_<Base>(a, i, std::make_integer_sequence<int, sizeof...(E)>());
+  }
+  template <int Base, int... K>
+  static __device__ __forceinline__ Vec4<R> eval4_(const KArgs &a, int i, std::integer_sequence<int, K...>) {
+    auto t = std::make_tuple(E::template eval4<ChildBase<Base + 1, K, E...>::value>(a, i)...);
+    Vec4<R> r;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) r.v[c] = F::apply(a.p[Base], std::get<K>(t).v[c]...);
+    return r;
+  }
+  template <int Base> static __device__ __forceinline__ Vec4<R> eval4(const KArgs &a, int i) {
+    return eval4_<Base>(a, i, std::make_integer_sequence<int, sizeof...(E)>());
+  }
+  static void sig(std::string &s) {
+    s += "map" + std::to_string(F::kFn) + "(";
+    bool first = true;
+    ((s += (first ? "" : ","), first = false, E::sig(s)), ...);
+    s += ")";
+  }
+};
+
+template <class G>
+struct Gen {
+  using R = int;
+  static constexpr int kNodes = 1;
+  template <int Base> static __device__ __forceinline__ int eval(const KArgs &a, int i) {
+    return G::apply(a.p[Base], a, i);
+  }
+  template <int Base> static __device__ __forceinline__ Vec4<int> eval4(const KArgs &a, int i) {
+    Vec4<int> r;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) r.v[c] = G::apply(a.p[Base], a, i + c);
+    return r;
+  }
+  static void sig(std::string &s) { s += "gen" + std::to_string(G::kFn); }
+};
+
+// EI yields the index, ES is evaluated there
+template <class EI, class ES>
+struct Gather {
+  using R = typename ES::R;
+  static constexpr int kNodes = 1 + EI::kNodes + ES::kNodes;
+  template <int Base> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
+    int j = EI::template eval<Base + 1>(a, i);
+    return ES::template eval<Base + 1 + EI::kNodes>(a, j);
+  }
+  template <int Base> static __device__ __forceinline__ Vec4<R> eval4(const KArgs &a, int i) {
+    Vec4<int> j = EI::template eval4<Base + 1>(a, i);
+    Vec4<R> r;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) r.v[c] = ES::template eval<Base + 1 + EI::kNodes>(a, j.v[c]);
+    return r;
+  }
+  static void sig(std::string &s) {
+    s += "gather(";
+    EI::sig(s);
+    s += ",";
+    ES::sig(s);
+    s += ")";
+  }
+};
+
+}  // namespace fc

@@ -1,0 +1,201 @@
+// Kernel instances: the cluster shapes the library can execute, each a skeleton
+// (kernels.hpp) specialised with an element program (expr.hpp).  The unfused arm
+// runs one singleton cluster per combinator through the same skeletons, so fused
+// and unfused execution share every primitive.
+#include "kernels.hpp"
+#include "registry.hpp"
+#include "stencil.hpp"
+
+#include <algorithm>
+
+namespace fc {
+
+namespace {
+
+constexpr unsigned kMaxGrid = 2048;   // 256 CUs x 8 workgroups
+
+unsigned grid_for(int n, int tile, unsigned cap) {
+  long long g = ((long long)n + tile - 1) / tile;
+  return (unsigned)std::max<long long>(1, std::min<long long>(g, cap));
+}
+
+// ---- launchers ------------------------------------------------------------
+// Launch through hipLaunchKernel so that the status returned is that of this
+// launch (hipGetLastError would also report an error an earlier, unrelated call
+// left behind on the thread).
+template <class... P, size_t... I>
+hipError_t launch_impl(void (*k)(P...), dim3 grid, hipStream_t s, std::tuple<P...> &vals, std::index_sequence<I...>) {
+  void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))...};
+  return hipLaunchKernel(reinterpret_cast<const void *>(k), grid, dim3(kBlock), ptrs, 0, s);
+}
+template <class... P, class... A>
+hipError_t launch_k(void (*k)(P...), unsigned grid, hipStream_t s, A... a) {
+  std::tuple<P...> vals(a...);
+  return launch_impl(k, dim3(grid), s, vals, std::index_sequence_for<P...>());
+}
+template <class E> hipError_t launch_store(const KArgs &a, const LaunchCtx &c) {
+  if (a.n == 0) return hipSuccess;
+  return launch_k(&store_kernel<E>, grid_for(a.n, kTile, kMaxGrid), c.stream, a);
+}
+template <class Op, class E> hipError_t launch_fold(const KArgs &a, const LaunchCtx &c) {
+  return launch_k(&fold_kernel<Op, E>, grid_for(a.n, kTile, kMaxGrid), c.stream, a, c.ctl, c.partials);
+}
+template <class ES, class Op, class EF> hipError_t launch_store_fold(const KArgs &a, const LaunchCtx &c) {
+  return launch_k(&store_fold_kernel<ES, Op, EF>, grid_for(a.n, kTile, kMaxGrid), c.stream, a, c.ctl, c.partials);
+}
+template <class Op, class E> hipError_t launch_foldseg(const KArgs &a, const LaunchCtx &c) {
+  if (a.aux == 0) return hipSuccess;
+  return launch_k(&foldseg_kernel<Op, E>, grid_for(a.aux, kBlock / 16, kMaxGrid * 8), c.stream, a);
+}
+template <class EX, class EV, int Mode> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {
+  long long tiles = std::max<long long>(1, ((long long)a.n + kScanTile - 1) / kScanTile);
+  if ((size_t)tiles > c.max_tiles) return hipErrorInvalidValue;
+  return launch_k(&scan_kernel<EX, EV, Mode>, (unsigned)tiles, c.stream, a, c.ctl, c.status);
+}
+template <class EI, class EV, class EF> hipError_t launch_scatter(const KArgs &a, const LaunchCtx &c) {
+  if (a.n == 0) return hipSuccess;
+  return launch_k(&scatter_kernel<EI, EV, EF>, grid_for(a.n, kTile, kMaxGrid), c.stream, a);
+}
+
+// ---- signatures -----------------------------------------------------------
+template <class E> std::string sig_of() { std::string s; E::sig(s); return s; }
+template <class E> Instance store_() { return {"store[" + sig_of<E>() + "]", &launch_store<E>}; }
+template <class Op, class E> Instance fold_() {
+  return {std::string("fold.") + Op::name() + "[" + sig_of<E>() + "]", &launch_fold<Op, E>};
+}
+template <class ES, class Op, class EF> Instance store_fold_() {
+  return {"store[" + sig_of<ES>() + "]+fold." + Op::name() + "[" + sig_of<EF>() + "]", &launch_store_fold<ES, Op, EF>};
+}
+template <class Op, class E> Instance foldseg_() {
+  return {std::string("foldseg.") + Op::name() + "[" + sig_of<E>() + "]", &launch_foldseg<Op, E>};
+}
+template <class EX, class EV, int Mode> Instance scan_() {
+  std::string s = "scan[" + sig_of<EX>() + "]";
+  if (Mode & kOffs) s += "+offs";
+  if (Mode & kScatter) s += "+scatter[" + sig_of<EV>() + "]";
+  if (Mode & kCount) s += "+count";
+  return {s, &launch_scan<EX, EV, Mode>};
+}
+template <class EI, class EV, class EF> Instance scatter_() {
+  return {"scatter[" + sig_of<EI>() + "," + sig_of<EV>() + "," + sig_of<EF>() + "]", &launch_scatter<EI, EV, EF>};
+}
+
+using F0 = In<0, float>;
+using F1 = In<1, float>;
+using F2 = In<2, float>;
+using F3 = In<3, float>;
+using F4 = In<4, float>;
+using I0 = In<0, int>;
+using I1 = In<1, int>;
+using I2 = In<2, int>;
+
+// element programs of the fused pipelines
+// r = fold(+)(zipWith(*) (map(ax+b) xs) (gather(reverse, map(ax+b) xs)))      [map duplicated per order]
+using ReverseDot = Map<FnMul2, Map<FnAffine, F0>, Gather<Gen<GenIotaRev>, Map<FnAffine, F0>>>;
+// r = fold(+)(map(z*z+1)(gather(idx, map(sin x * x) xs)))                      [`simple1` shape]
+using PermGather = Map<FnSqPlusOne, Gather<I0, Map<FnSinXMulX, F1>>>;
+// y = foldSeg(+)(zipWith(*) vals (gather(col, x)))
+using SpmvTerm = Map<FnMul2, F0, Gather<I1, F2>>;
+// compaction: flags = map(v mod k == r) v, value = v
+using ModFlag = Map<FnModEq, I0>;
+// stencil with the producer recomputed at every gathered position
+using ExpNeg0 = Map<FnExpNeg, F0>;
+using ShiftedExp = Gather<Gen<GenClampShift2D>, ExpNeg0>;
+using Stencil5 = Map<FnAdd5, ExpNeg0, ShiftedExp, ShiftedExp, ShiftedExp, ShiftedExp>;
+// the same stencil reading a materialised p
+using ShiftedIn = Gather<Gen<GenClampShift2D>, F0>;
+using Stencil5Mat = Map<FnAdd5, F0, ShiftedIn, ShiftedIn, ShiftedIn, ShiftedIn>;
+
+// specialised instances come first: they share the signature of a generic one
+// and take over when their accept() passes
+void append_stencil_instances(std::vector<Instance> &r) {
+  // pre-order slots of Stencil5: 0 add5, 1 exp, 2 in, then (gather, gen, exp, in) x 4
+  static_assert(Stencil5::kNodes == 19 && Stencil5Mat::kNodes == 14, "slot numbering");
+  Instance a = store_fold_<Stencil5, MaxF32, ExpNeg0>();
+  a.launch = &launch_stencil5<FnExpNeg, 1, true>;
+  a.accept = &stencil5_accept<FnExpNeg, 1, true, 4, 4>;
+  a.variant = "rows-in-registers";
+  r.push_back(a);
+  Instance b = store_<Stencil5>();
+  b.launch = &launch_stencil5<FnExpNeg, 1, false>;
+  b.accept = &stencil5_accept<FnExpNeg, 1, false, 4, 4>;
+  b.variant = "rows-in-registers";
+  r.push_back(b);
+  // pre-order slots of Stencil5Mat: 0 add5, 1 in, then (gather, gen, in) x 4
+  Instance c = store_<Stencil5Mat>();
+  c.launch = &launch_stencil5<FnIdentF, 0, false>;
+  c.accept = &stencil5_accept<FnIdentF, 0, false, 3, 3>;
+  c.variant = "rows-in-registers";
+  r.push_back(c);
+}
+
+std::vector<Instance> build_registry() {
+  std::vector<Instance> r;
+  append_stencil_instances(r);
+  // ---- singleton clusters (the unfused arm) ----
+  r.push_back(store_<Map<FnIdentF, F0>>());
+  r.push_back(store_<Map<FnIdentI, I0>>());
+  r.push_back(store_<Map<FnAffine, F0>>());
+  r.push_back(store_<Map<FnSinXMulX, F0>>());
+  r.push_back(store_<Map<FnSqPlusOne, F0>>());
+  r.push_back(store_<Map<FnExpNeg, F0>>());
+  r.push_back(store_<Map<FnMul2, F0, F1>>());
+  r.push_back(store_<Map<FnAdd2, F0, F1>>());
+  r.push_back(store_<Map<FnAdd3, F0, F1, F2>>());
+  r.push_back(store_<Map<FnAdd5, F0, F1, F2, F3, F4>>());
+  r.push_back(store_<Map<FnModEq, I0>>());
+  r.push_back(store_<Gen<GenIota>>());
+  r.push_back(store_<Gen<GenIotaRev>>());
+  r.push_back(store_<Gen<GenClampShift2D>>());
+  r.push_back(store_<Gen<GenRowOf2D>>());
+  r.push_back(store_<Gen<GenConst>>());
+  r.push_back(store_<Gather<I0, F1>>());
+  r.push_back(store_<Gather<I0, I1>>());
+  r.push_back(fold_<AddF32, F0>());
+  r.push_back(fold_<MaxF32, F0>());
+  r.push_back(fold_<MulF32, F0>());
+  r.push_back(fold_<AddI32, I0>());
+  r.push_back(fold_<MaxI32, I0>());
+  r.push_back(foldseg_<AddF32, F0>());
+  r.push_back(foldseg_<MaxF32, F0>());
+  r.push_back(foldseg_<AddI32, I0>());
+  r.push_back(scan_<I0, I0, kOffs>());
+  r.push_back(scatter_<I0, I1, I2>());
+  r.push_back(scatter_<I0, F1, I2>());
+  // ---- fused clusters ----
+  r.push_back(fold_<AddF32, ReverseDot>());
+  r.push_back(fold_<AddF32, PermGather>());
+  r.push_back(foldseg_<AddF32, SpmvTerm>());
+  r.push_back(scan_<ModFlag, I0, kScatter | kCount>());
+  r.push_back(scan_<ModFlag, I0, kScatter>());
+  r.push_back(scan_<ModFlag, I0, kOffs | kCount>());
+  r.push_back(store_fold_<Stencil5, MaxF32, ExpNeg0>());
+  r.push_back(store_fold_<ExpNeg0, MaxF32, ExpNeg0>());       // diagonal: p stored and folded
+  r.push_back(store_<Stencil5Mat>());
+  r.push_back(store_<Stencil5>());
+  // clusters of the strict (no duplication) optimum of the reverse-dot pipeline
+  r.push_back(fold_<AddF32, Map<FnMul2, F0, Gather<Gen<GenIotaRev>, F0>>>());
+  // partial fusions used by tests of the fusion rules
+  r.push_back(store_<Gather<I0, Map<FnAffine, F1>>>());       // `simple1`
+  r.push_back(store_<Gather<I0, Gather<I1, F2>>>());          // `simple2`
+  r.push_back(store_<Gather<Gen<GenIotaRev>, F0>>());         // reverse / backpermute
+  r.push_back(store_<Map<FnSqPlusOne, Gather<I0, Map<FnSinXMulX, F1>>>>());
+  r.push_back(fold_<AddF32, Map<FnSqPlusOne, F0>>());
+  r.push_back(store_<Map<FnMul2, F0, Gather<I1, F2>>>());
+  return r;
+}
+
+}  // namespace
+
+const std::vector<Instance> &registry() {
+  static const std::vector<Instance> r = build_registry();
+  return r;
+}
+
+const Instance *find_instance(const std::string &sig, const KArgs &a) {
+  for (const Instance &i : registry())
+    if (i.sig == sig && (!i.accept || i.accept(a))) return &i;
+  return nullptr;
+}
+
+}  // namespace fc

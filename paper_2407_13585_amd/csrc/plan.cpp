@@ -1,0 +1,255 @@
+// The chooser: exact solution of the clustering ILP (Fig. "Total ILP
+// formulation") by branch and bound, and the work-duplication rewrite.
+//
+// A feasible point of the ILP is fixed by pi alone: x_ab = [pi_a != pi_b],
+// m_a = 1 exactly when every edge out of a is fused over (any other choice is
+// never better for the cost functions of section 4.1), and the traversal orders
+// follow from the equalities over fused edges.  The search therefore enumerates
+// the level sets of pi -- set partitions of the non-input nodes, built in
+// program order -- and prunes with a lower bound of the cost that holds for every
+// completion.  The numerical values of pi are irrelevant beyond their order
+// (section 5.2), so blocks are numbered by a topological order of the quotient
+// graph at the leaves.
+#include "plan.hpp"
+
+#include <algorithm>
+#include <map>
+#include <set>
+
+namespace fc {
+
+namespace {
+
+struct Search {
+  const Model &m;
+  int cost_fn;
+  std::vector<int> order;          // non-input nodes in program order
+  std::vector<int> block;          // per node, -1 = unassigned (inputs: -2)
+  int n_blocks = 0;
+  double best = 1e300;
+  std::vector<int> best_pi;
+  long long visited = 0;
+  long long limit;
+  bool aborted = false;
+  // block graph: adj[b] = bitmask of blocks that must run strictly after b
+  std::vector<uint64_t> adj;
+
+  Search(const Model &m_, int cf, long long lim) : m(m_), cost_fn(cf), block(m_.n, -1), limit(lim), adj(64, 0) {
+    for (int a = 0; a < m.n; ++a) {
+      if (m.is_input(a)) block[a] = -2; else order.push_back(a);
+    }
+  }
+
+  bool reaches(int from, int to) const {
+    uint64_t seen = 0, frontier = 1ull << from;
+    while (frontier) {
+      int b = __builtin_ctzll(frontier);
+      frontier &= frontier - 1;
+      if (seen >> b & 1) continue;
+      seen |= 1ull << b;
+      if (adj[b] >> to & 1) return true;
+      frontier |= adj[b] & ~seen;
+    }
+    return false;
+  }
+
+  // cost of the decisions taken so far; never above the cost of any completion
+  double lower_bound() const {
+    const bool weighted = cost_fn == FC_COST_BYTES;
+    double reads = 0, writes = 0, unfused = 0;
+    for (int a = 0; a < m.n; ++a) {
+      if (block[a] == -1) continue;
+      uint64_t readers = 0;
+      bool manifest = !m.is_input(a) && (m.out_edges[a].empty() || (m.nodes[a].flags & FC_NODE_OUTPUT));
+      for (int e : m.out_edges[a]) {
+        int b = m.edges[e].b;
+        if (block[b] < 0) continue;
+        if (block[b] != block[a]) {
+          readers |= 1ull << block[b];
+          if (!m.is_input(a)) manifest = true;
+          if (m.edges[e].fusible) unfused += 1;
+        }
+      }
+      double wgt = weighted ? (double)m.bytes(a) : 1.0;
+      reads += wgt * __builtin_popcountll(readers);
+      if (manifest) writes += wgt;
+    }
+    switch (cost_fn) {
+      case FC_COST_CLUSTERS: return n_blocks;
+      case FC_COST_FUSED_EDGES: return unfused;
+      case FC_COST_ARRAYS: return writes;
+      case FC_COST_READS: return reads;
+      default: return reads + writes;
+    }
+  }
+
+  void leaf() {
+    // number the blocks in a topological order of the block graph
+    std::vector<int> indeg(n_blocks, 0), topo;
+    for (int b = 0; b < n_blocks; ++b)
+      for (int d = 0; d < n_blocks; ++d) if (adj[b] >> d & 1) ++indeg[d];
+    std::vector<int> ready;
+    for (int b = n_blocks - 1; b >= 0; --b) if (!indeg[b]) ready.push_back(b);
+    while (!ready.empty()) {
+      int b = ready.back();
+      ready.pop_back();
+      topo.push_back(b);
+      for (int d = n_blocks - 1; d >= 0; --d) if ((adj[b] >> d & 1) && --indeg[d] == 0) ready.push_back(d);
+    }
+    if ((int)topo.size() != n_blocks) return;   // cyclic: not a valid cluster order
+    std::vector<int> level(n_blocks);
+    for (int k = 0; k < n_blocks; ++k) level[topo[k]] = k + 1;
+    std::vector<int> pi(m.n, 0);
+    for (int a : order) pi[a] = level[block[a]];
+    Clustering c;
+    std::string err;
+    if (derive_and_check(m, pi, c, err) != FC_OK) return;
+    double cost = evaluate_cost(m, c, cost_fn);
+    if (cost < best) { best = cost; best_pi = pi; }
+  }
+
+  void go(size_t k) {
+    if (aborted) return;
+    if (++visited > limit) { aborted = true; return; }
+    if (k == order.size()) { leaf(); return; }
+    const int a = order[k];
+    // candidate blocks: those holding a producer of `a` first, then the others, then a new one
+    std::vector<int> cand;
+    for (int e : m.in_edges[a]) {
+      int b = block[m.edges[e].a];
+      if (b >= 0 && std::find(cand.begin(), cand.end(), b) == cand.end()) cand.push_back(b);
+    }
+    for (int b = 0; b < n_blocks; ++b) if (std::find(cand.begin(), cand.end(), b) == cand.end()) cand.push_back(b);
+    if (n_blocks < 64) cand.push_back(n_blocks);
+    for (int b : cand) {
+      const bool fresh = b == n_blocks;
+      // edges into `a`: infusible ones need another block; all of them order the blocks
+      bool ok = true;
+      std::vector<std::pair<int, int>> added;   // (from block, to block) bits set here
+      auto order_blocks = [&](int from, int to) {
+        if (from == to) { ok = false; return; }
+        if (!(adj[from] >> to & 1)) {
+          if (reaches(to, from)) { ok = false; return; }
+          adj[from] |= 1ull << to;
+          added.push_back({from, to});
+        }
+      };
+      for (int e : m.in_edges[a]) {
+        if (!ok) break;
+        const Edge &ed = m.edges[e];
+        int pb = block[ed.a];
+        if (pb < 0) continue;   // producer is a program input
+        if (pb == b) { if (!ed.fusible) ok = false; continue; }
+        order_blocks(pb, b);
+      }
+      // temporal uniqueness of scatter, in both roles `a` can play
+      if (ok && m.nodes[a].kind == FC_SCATTER) {
+        int d = m.nodes[a].arg[0];
+        for (int e : m.out_edges[d]) {
+          int i = m.edges[e].b;
+          if (i != a && block[i] >= 0 && ok) order_blocks(block[i], b);
+        }
+      }
+      if (ok) {
+        for (int e : m.in_edges[a]) {
+          int d = m.edges[e].a;
+          for (int e2 : m.out_edges[d]) {
+            int j = m.edges[e2].b;
+            if (j != a && m.nodes[j].kind == FC_SCATTER && m.nodes[j].arg[0] == d && block[j] >= 0 && ok)
+              order_blocks(b, block[j]);
+          }
+        }
+      }
+      if (ok) {
+        block[a] = b;
+        if (fresh) ++n_blocks;
+        if (lower_bound() < best) go(k + 1);
+        if (fresh) --n_blocks;
+        block[a] = -1;
+      }
+      for (auto &p : added) adj[p.first] &= ~(1ull << p.second);
+    }
+  }
+};
+
+}  // namespace
+
+int choose_clustering(const Model &m, int cost_fn, bool split, Clustering &out, int &n_clusters, double &cost,
+                      std::string &err) {
+  if (cost_fn < FC_COST_CLUSTERS || cost_fn > FC_COST_BYTES) { err = "unknown cost function"; return FC_E_ARG; }
+  int non_input = 0;
+  for (int a = 0; a < m.n; ++a) non_input += !m.is_input(a);
+  if (non_input > 64) { err = "the exact chooser handles at most 64 combinators"; return FC_E_LIMIT; }
+  Search s(m, cost_fn, 200000000LL);
+  s.go(0);
+  if (s.aborted) { err = "search limit reached before optimality was proven"; return FC_E_LIMIT; }
+  if (s.best_pi.empty() && non_input > 0) { err = "no feasible clustering"; return FC_E_ILLEGAL_PARTITION; }
+  std::vector<int> pi = s.best_pi.empty() ? std::vector<int>(m.n, 0) : s.best_pi;
+  int rc = derive_and_check(m, pi, out, err);
+  if (rc != FC_OK) return rc;
+  cost = evaluate_cost(m, out, cost_fn);
+  n_clusters = split ? split_components(m, out) : renumber_levels(m, out);
+  // the split changes cluster numbers only; re-derive the per-edge and per-node variables
+  Clustering again;
+  rc = derive_and_check(m, out.pi, again, err);
+  if (rc != FC_OK) return rc;
+  out = again;
+  return FC_OK;
+}
+
+// --------------------------------------------------------------------------- duplication
+int duplicate_producers(const Model &m, std::vector<fc_node> &out_nodes, std::vector<int> &origin) {
+  const int n = m.n;
+  // versions[a]: order classes in which a copy of node a is needed.  Class 0 is the
+  // natural order; class g+1 is "read as the source of gather g".
+  std::vector<std::vector<int>> versions(n);
+  auto cloneable = [&](int a) { return m.nodes[a].kind == FC_MAP || m.nodes[a].kind == FC_GENERATE; };
+  for (int a = n - 1; a >= 0; --a) {
+    std::set<int> classes;
+    if (m.out_edges[a].empty() || (m.nodes[a].flags & FC_NODE_OUTPUT)) classes.insert(0);
+    for (int e : m.out_edges[a]) {
+      const Edge &ed = m.edges[e];
+      switch (m.in_order(ed.b, ed.slot)) {
+        case InOrder::Label: classes.insert(ed.b + 1); break;
+        case InOrder::SameAsOut: for (int t : versions[ed.b]) classes.insert(t); break;
+        default: classes.insert(0);
+      }
+    }
+    if (!cloneable(a) && classes.size() > 1) classes = {0};
+    versions[a].assign(classes.begin(), classes.end());
+  }
+  // emit in program order; version (a, t) takes the version of each argument that matches its class
+  std::map<std::pair<int, int>, int> id;
+  out_nodes.clear();
+  origin.clear();
+  auto version_of = [&](int p, int cls) {
+    auto it = id.find({p, cls});
+    if (it != id.end()) return it->second;
+    it = id.find({p, 0});
+    if (it != id.end()) return it->second;
+    return id.lower_bound({p, -1})->second;   // the only version there is
+  };
+  for (int a = 0; a < n; ++a) {
+    for (size_t v = 0; v < versions[a].size(); ++v) {
+      int t = versions[a][v];
+      fc_node nd = m.nodes[a];
+      if (t != 0 && versions[a].size() > 1 && std::find(versions[a].begin(), versions[a].end(), 0) != versions[a].end())
+        nd.flags &= ~FC_NODE_OUTPUT;
+      for (int k = 0; k < nd.nargs; ++k) {
+        int cls = 0;
+        switch (m.in_order(a, k)) {
+          case InOrder::Label: cls = a + 1; break;
+          case InOrder::SameAsOut: cls = t; break;
+          default: cls = 0;
+        }
+        nd.arg[k] = version_of(m.nodes[a].arg[k], cls);
+      }
+      id[{a, t}] = (int)out_nodes.size();
+      out_nodes.push_back(nd);
+      origin.push_back(a);
+    }
+  }
+  return FC_OK;
+}
+
+}  // namespace fc

@@ -1,0 +1,319 @@
+// Runner: maps every cluster of a clustering onto a kernel instance and
+// launches it.  One launch per cluster; no host synchronisation.
+#include "run.hpp"
+
+#include <algorithm>
+#include <cstring>
+#include <map>
+#include <set>
+
+#include "registry.hpp"
+
+namespace fc {
+
+namespace {
+
+struct Builder {
+  const Model &m;
+  const Clustering &c;
+  const std::vector<int> &members;   // nodes of the cluster
+  std::set<int> in_cluster;
+  std::vector<int> externals;        // node ids, in order of first appearance
+  KArgs args;
+  int slots = 0;
+  std::string err;
+
+  Builder(const Model &m_, const Clustering &c_, const std::vector<int> &mem)
+      : m(m_), c(c_), members(mem), in_cluster(mem.begin(), mem.end()) {
+    std::memset(&args, 0, sizeof(args));
+  }
+
+  bool fail(const std::string &s) { if (err.empty()) err = s; return false; }
+
+  int external(int a) {
+    for (size_t k = 0; k < externals.size(); ++k) if (externals[k] == a) return (int)k;
+    externals.push_back(a);
+    return (int)externals.size() - 1;
+  }
+
+  bool slot_for(int a) {
+    if (slots >= kMaxSlots) return fail("element program too large");
+    Slot &s = args.p[slots++];
+    const fc_node &nd = m.nodes[a];
+    s.f[0] = nd.fparam[0]; s.f[1] = nd.fparam[1];
+    s.i[0] = nd.iparam[0]; s.i[1] = nd.iparam[1];
+    s.ext[0] = (int)nd.shape[0]; s.ext[1] = (int)nd.shape[1];
+    return true;
+  }
+
+  // element program that yields array `a` at the current iteration index
+  bool expr(int a, std::string &sig) {
+    const fc_node &nd = m.nodes[a];
+    if (!slot_for(a)) return false;
+    if (!in_cluster.count(a)) {
+      int k = external(a);
+      if (k >= kMaxIn - 1) return fail("too many external arrays");
+      sig += "in" + std::to_string(k) + (nd.dtype == FC_F32 ? ":f32" : ":i32");
+      return true;
+    }
+    switch (nd.kind) {
+      case FC_MAP:
+        sig += "map" + std::to_string(nd.fn) + "(";
+        for (int k = 0; k < nd.nargs; ++k) {
+          if (k) sig += ",";
+          if (!expr(nd.arg[k], sig)) return false;
+        }
+        sig += ")";
+        return true;
+      case FC_GENERATE:
+        sig += "gen" + std::to_string(nd.fn);
+        return true;
+      case FC_GATHER:
+        sig += "gather(";
+        if (!expr(nd.arg[0], sig)) return false;
+        sig += ",";
+        if (!expr(nd.arg[1], sig)) return false;
+        sig += ")";
+        return true;
+      default:
+        return fail("node " + std::to_string(a) + " cannot be evaluated inside an element program");
+    }
+  }
+};
+
+const char *op_name(int fn, int dtype) {
+  if (dtype == FC_F32) return fn == FC_OP_ADD ? "add.f32" : fn == FC_OP_MAX ? "max.f32" : "mul.f32";
+  return fn == FC_OP_ADD ? "add.i32" : fn == FC_OP_MAX ? "max.i32" : "mul.i32";
+}
+
+}  // namespace
+
+int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &members, ClusterLaunch &out,
+                 std::string &err) {
+  Builder b(m, c, members);
+  out = ClusterLaunch();
+  auto unsupported = [&](const std::string &s) { err = s + (b.err.empty() ? "" : ": " + b.err); return FC_E_UNSUPPORTED; };
+
+  std::vector<int> scans, scatters, folds, foldsegs, stores, forces;
+  for (int a : members) {
+    const fc_node &nd = m.nodes[a];
+    switch (nd.kind) {
+      case FC_SCANL: scans.push_back(a); break;
+      case FC_SCANR: return unsupported("scanr has no kernel instance yet");
+      case FC_SCATTER: scatters.push_back(a); break;
+      case FC_FOLD: folds.push_back(a); break;
+      case FC_FOLDSEG: foldsegs.push_back(a); break;
+      case FC_FORCE: forces.push_back(a); break;
+      default:
+        if (!c.fused_away[a]) stores.push_back(a);
+    }
+  }
+  std::string sig;
+  int n = -1;
+  auto set_n = [&](int64_t v) { if (n >= 0 && n != (int)v) return false; n = (int)v; return true; };
+  auto shape_from = [&](int a) { out.h = (int)m.nodes[a].shape[0]; out.w = (int)m.nodes[a].shape[1]; };
+
+  if (!forces.empty()) {
+    if (members.size() != 1) return unsupported("force shares a cluster");
+    out.kind = ClusterLaunch::Alias;
+    out.alias_of = m.nodes[forces[0]].arg[0];
+    out.alias_node = forces[0];
+    out.sig = "alias";
+    return FC_OK;
+  }
+  if (!scans.empty()) {
+    if (scans.size() != 1 || scatters.size() > 1 || folds.size() > 1 || !foldsegs.empty() || !stores.empty())
+      return unsupported("scan cluster shape");
+    const int sc = scans[0];
+    const int x = m.nodes[sc].arg[0];
+    if (m.nodes[sc].dtype != FC_I32) return unsupported("scan of f32");
+    sig = "scan[";
+    if (!b.expr(x, sig)) return unsupported("scan input");
+    sig += "]";
+    set_n(m.size(sc));
+    shape_from(sc);
+    if (!c.fused_away[sc]) { sig += "+offs"; out.out_nodes[1] = sc; }
+    if (!scatters.empty()) {
+      const fc_node &st = m.nodes[scatters[0]];
+      if (st.fn != FC_OP_OVERWRITE || st.arg[1] != sc || st.nargs != 4 || st.arg[3] != x)
+        return unsupported("scatter fused with a scan must take the scan as index and the scanned flags as flag");
+      sig += "+scatter[";
+      if (!b.expr(st.arg[2], sig)) return unsupported("scatter value");
+      sig += "]";
+      out.out_nodes[0] = scatters[0];
+    }
+    if (!folds.empty()) {
+      const fc_node &f = m.nodes[folds[0]];
+      if (f.fn != FC_OP_ADD || f.arg[0] != x || f.shape[0] != 1) return unsupported("fold beside a scan must be (+) over the scanned array");
+      sig += "+count";
+      out.out_nodes[2] = folds[0];
+    }
+  } else if (!scatters.empty()) {
+    if (scatters.size() != 1 || !folds.empty() || !foldsegs.empty() || !stores.empty())
+      return unsupported("scatter cluster shape");
+    const fc_node &st = m.nodes[scatters[0]];
+    if (st.fn != FC_OP_OVERWRITE) return unsupported("combining scatter has no kernel instance yet");
+    if (st.nargs != 4) return unsupported("scatter without flag");
+    sig = "scatter[";
+    if (!b.expr(st.arg[1], sig)) return unsupported("scatter index");
+    sig += ",";
+    if (!b.expr(st.arg[2], sig)) return unsupported("scatter value");
+    sig += ",";
+    if (!b.expr(st.arg[3], sig)) return unsupported("scatter flag");
+    sig += "]";
+    set_n(m.size(st.arg[1]));
+    shape_from(st.arg[1]);
+    out.out_nodes[0] = scatters[0];
+  } else if (!foldsegs.empty()) {
+    if (foldsegs.size() != 1 || !folds.empty() || !stores.empty()) return unsupported("foldSeg cluster shape");
+    const fc_node &f = m.nodes[foldsegs[0]];
+    sig = std::string("foldseg.") + op_name(f.fn, f.dtype) + "[";
+    if (!b.expr(f.arg[0], sig)) return unsupported("foldSeg values");
+    sig += "]";
+    set_n(m.size(f.arg[0]));
+    shape_from(f.arg[0]);
+    out.aux = (int)f.shape[0];
+    out.offsets_node = f.arg[1];
+    out.out_nodes[0] = foldsegs[0];
+  } else {
+    if (stores.size() > 1 || folds.size() > 1 || (stores.empty() && folds.empty()))
+      return unsupported("cluster with " + std::to_string(stores.size()) + " stored arrays and " + std::to_string(folds.size()) + " folds");
+    if (!stores.empty()) {
+      sig = "store[";
+      if (!b.expr(stores[0], sig)) return unsupported("stored array");
+      sig += "]";
+      set_n(m.size(stores[0]));
+      shape_from(stores[0]);
+      out.out_nodes[0] = stores[0];
+    }
+    if (!folds.empty()) {
+      const fc_node &f = m.nodes[folds[0]];
+      if (!(f.rank == 1 && f.shape[0] == 1)) return unsupported("row fold has no kernel instance yet");
+      if (!stores.empty()) sig += "+";
+      sig += std::string("fold.") + op_name(f.fn, f.dtype) + "[";
+      if (!b.expr(f.arg[0], sig)) return unsupported("fold argument");
+      sig += "]";
+      if (!set_n(m.size(f.arg[0]))) return unsupported("iteration sizes differ inside a cluster");
+      if (stores.empty()) shape_from(f.arg[0]);
+      out.out_nodes[stores.empty() ? 0 : 1] = folds[0];
+    }
+  }
+  // every member must have been reached by an element program or be a root
+  out.kind = ClusterLaunch::Kernel;
+  out.sig = sig;
+  out.args = b.args;
+  out.args.n = n;
+  out.args.h = out.h;
+  out.args.w = out.w;
+  out.args.aux = out.aux;
+  out.externals = b.externals;
+  const Instance *inst = find_instance(sig, out.args);
+  if (!inst) return unsupported("no kernel instance for cluster " + sig);
+  out.instance = inst;
+  return FC_OK;
+}
+
+std::vector<std::vector<int>> clusters_of(const Model &m, const Clustering &c) {
+  std::map<int, std::vector<int>> by_pi;
+  for (int a = 0; a < m.n; ++a) if (!m.is_input(a)) by_pi[c.pi[a]].push_back(a);
+  std::vector<std::vector<int>> r;
+  for (auto &kv : by_pi) r.push_back(kv.second);
+  return r;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+size_t scratch_bytes_for(const Model &m, const Clustering &c) {
+  size_t total = FC_SCRATCH_CONTROL_BYTES;
+  for (int a = 0; a < m.n; ++a)
+    if (!m.is_input(a) && !c.fused_away[a] && m.nodes[a].kind != FC_SCATTER && m.nodes[a].kind != FC_FORCE)
+      total += align_up(std::max<size_t>((size_t)m.bytes(a), 4), 256);
+  return total;
+}
+
+int run_clustering(const Model &m, const Clustering &c, const fc_buffer *bufs, void *scratch, size_t scratch_bytes,
+                   hipStream_t stream, std::string &err) {
+  if (!bufs) { err = "null buffer table"; return FC_E_ARG; }
+  if (!scratch || ((uintptr_t)scratch & 255u) || scratch_bytes < FC_SCRATCH_CONTROL_BYTES) {
+    err = "scratch must be 256-byte aligned and at least FC_SCRATCH_CONTROL_BYTES";
+    return FC_E_SCRATCH;
+  }
+  // resolve the device buffer of every array that reaches memory
+  std::vector<void *> ptr(m.n, nullptr);
+  size_t cursor = FC_SCRATCH_CONTROL_BYTES;
+  for (int a = 0; a < m.n; ++a) {
+    const fc_node &nd = m.nodes[a];
+    const size_t need = std::max<size_t>((size_t)m.bytes(a), nd.kind == FC_FOLD ? 4 : 0);
+    if (nd.kind == FC_SCATTER) {
+      ptr[a] = ptr[nd.arg[0]];
+      if (bufs[a].ptr && bufs[a].ptr != ptr[a]) { err = "scatter " + std::to_string(a) + " must share the buffer of its destination"; return FC_E_UNBOUND; }
+      continue;
+    }
+    if (!m.is_input(a) && c.fused_away[a]) continue;
+    if (bufs[a].ptr) {
+      if ((size_t)bufs[a].bytes < need) { err = "buffer of node " + std::to_string(a) + " is too small"; return FC_E_UNBOUND; }
+      if ((uintptr_t)bufs[a].ptr & 15u) { err = "buffer of node " + std::to_string(a) + " is not 16-byte aligned"; return FC_E_UNBOUND; }
+      ptr[a] = bufs[a].ptr;
+    } else if (m.is_input(a)) {
+      if (need == 0) { ptr[a] = scratch; continue; }   // empty array: any valid pointer
+      err = "input " + std::to_string(a) + " is not bound";
+      return FC_E_UNBOUND;
+    } else if (nd.kind == FC_FORCE) {
+      ptr[a] = ptr[nd.arg[0]];
+    } else {
+      size_t sz = align_up(std::max<size_t>(need, 4), 256);
+      if (cursor + sz > scratch_bytes) { err = "scratch too small for the manifest intermediates"; return FC_E_SCRATCH; }
+      ptr[a] = static_cast<char *>(scratch) + cursor;
+      cursor += sz;
+    }
+  }
+  LaunchCtx ctx;
+  ctx.stream = stream;
+  ctx.ctl = static_cast<Control *>(scratch);
+  ctx.partials = reinterpret_cast<unsigned *>(static_cast<char *>(scratch) + kPartialsOffset);
+  ctx.status = reinterpret_cast<unsigned long long *>(static_cast<char *>(scratch) + kStatusOffset);
+  ctx.max_tiles = kMaxTiles;
+
+  // plan every cluster before the first launch, so that an unsupported cluster
+  // leaves no partial results behind
+  std::vector<ClusterLaunch> launches;
+  for (const auto &members : clusters_of(m, c)) {
+    ClusterLaunch cl;
+    int rc = plan_cluster(m, c, members, cl, err);
+    if (rc != FC_OK) return rc;
+    launches.push_back(cl);
+  }
+  for (ClusterLaunch &cl : launches) {
+    if (cl.kind == ClusterLaunch::Alias) {
+      if (bufs[cl.alias_node].ptr && bufs[cl.alias_node].ptr != ptr[cl.alias_of]) {
+        hipError_t e = hipMemcpyAsync(bufs[cl.alias_node].ptr, ptr[cl.alias_of], (size_t)m.bytes(cl.alias_node),
+                                      hipMemcpyDeviceToDevice, stream);
+        if (e != hipSuccess) { err = hipGetErrorString(e); return FC_E_HIP; }
+      }
+      continue;
+    }
+    for (size_t k = 0; k < cl.externals.size(); ++k) {
+      cl.args.in[k] = ptr[cl.externals[k]];
+      if (!cl.args.in[k]) { err = "array " + std::to_string(cl.externals[k]) + " read before it exists"; return FC_E_UNBOUND; }
+    }
+    if (cl.offsets_node >= 0) cl.args.in[kMaxIn - 1] = ptr[cl.offsets_node];
+    for (int k = 0; k < kMaxOut; ++k)
+      if (cl.out_nodes[k] >= 0) {
+        cl.args.out[k] = ptr[cl.out_nodes[k]];
+        if (!cl.args.out[k]) { err = "array " + std::to_string(cl.out_nodes[k]) + " has no buffer"; return FC_E_UNBOUND; }
+      }
+    hipError_t e = cl.instance->launch(cl.args, ctx);
+    if (e != hipSuccess) {
+      int count = -1, dev = -1;
+      hipError_t e2 = hipGetDeviceCount(&count);
+      hipError_t e3 = hipGetDevice(&dev);
+      err = std::string("launch of ") + cl.sig + ": " + hipGetErrorString(e) + " (devices visible to the library: " +
+            std::to_string(count) + ", current " + std::to_string(dev) + ", status " + std::to_string((int)e2) + "/" +
+            std::to_string((int)e3) + ")";
+      return FC_E_HIP;
+    }
+  }
+  return FC_OK;
+}
+
+}  // namespace fc

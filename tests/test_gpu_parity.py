@@ -1,0 +1,234 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, on the GPU.
+
+Every case runs the same seeded inputs through oracle.interp.evaluate and through
+fc_run_fused / fc_run_unfused and compares element by element under the rules of
+tests/parity.py.
+"""
+import numpy as np
+import pytest
+
+import parity as P
+from oracle.interp import evaluate
+from workloads import Graph, build
+from workloads import configs as C
+
+pytestmark = pytest.mark.gpu
+
+F32 = np.float32
+
+# comparison rule per node of the five pipelines
+RULES = {
+    1: {"ys": "exact", "idx": "exact", "zs": "exact", "ps": "exact", "r": "fold"},
+    2: {"ys": ("ulp", 4), "zs": ("ulp", 4), "ws": ("rel", 2e-6), "r": "fold"},
+    3: {"g": "exact", "p": "exact", "y": "segmented"},
+    4: {"flags": "exact", "offs": "exact", "count": "exact", "out": "exact"},
+    5: {"p": ("ulp", 4), "iN": "exact", "iS": "exact", "iW": "exact", "iE": "exact",
+        "pN": ("ulp", 4), "pS": ("ulp", 4), "pW": ("ulp", 4), "pE": ("ulp", 4),
+        "out": ("rel", 1e-6), "m": ("ulp", 4)},
+}
+
+
+def fc():
+    import paper_2407_13585_amd as fc_
+    return fc_
+
+
+def device_program(*a, **kw):
+    from paper_2407_13585_amd.device import DeviceProgram
+    return DeviceProgram(*a, **kw)
+
+
+def compare(cfg, w, env, prog, names, tag):
+    for name in names:
+        rule = RULES[cfg][name]
+        got, ref = prog.fetch(name), env[name]
+        what = f"{w.name}/{tag}/{name}"
+        if rule == "exact":
+            P.assert_bit_exact(got, ref, what)
+        elif rule == "fold":
+            P.assert_fold(got, ref, what)
+        elif rule == "segmented":
+            P.assert_segmented(got, ref, env["p"], w.inputs["off"], what)
+        elif rule[0] == "ulp":
+            P.assert_ulp(got, np.asarray(ref, dtype=np.float64).astype(F32), rule[1], what)
+        elif rule[0] == "rel":
+            P.assert_close(got, ref, rule[1], what)
+
+
+def plan(graph, duplicate):
+    if duplicate:
+        graph, _ = fc().fc_duplicate(graph)
+    return graph, fc().fc_plan(graph, "bytes")
+
+
+def run_all_modes(cfg, w, env=None):
+    env = env or evaluate(w.graph, w.inputs)
+    outs = w.graph.outputs()
+    results = {}
+    for dup in (True, False):
+        g, part = plan(w.graph, dup)
+        prog = device_program(g, w.inputs, part)
+        prog.run()
+        compare(cfg, w, env, prog, outs, "fused-dup" if dup else "fused-strict")
+        results["dup" if dup else "strict"] = {o: prog.fetch(o) for o in outs}
+        assert prog.control_words()[:2].tolist() == [0, 0] and prog.control_words()[3] == 0
+    inter = [n.name for n in w.graph.nodes if n.kind != "input"]
+    prog = device_program(w.graph, w.inputs, None, bind=inter)
+    prog.run()
+    compare(cfg, w, env, prog, inter, "unfused")
+    results["unfused"] = {o: prog.fetch(o) for o in outs}
+    return results
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_small_configs_match_oracle(cfg):
+    w = build(cfg, small=True)
+    res = run_all_modes(cfg, w)
+    # fusion never changes element values: stored arrays agree bit for bit across arms
+    for o in w.graph.outputs():
+        if RULES[cfg][o] in ("exact",) or o == "out":
+            P.assert_bit_exact(res["dup"][o], res["unfused"][o], f"{w.name}: fused vs unfused {o}")
+            P.assert_bit_exact(res["strict"][o], res["unfused"][o], f"{w.name}: strict vs unfused {o}")
+
+
+def test_plans_have_the_expected_shape():
+    k = {}
+    for cfg in (1, 2, 3, 4, 5):
+        w = build(cfg, small=True)
+        _, strict = plan(w.graph, False)
+        _, dup = plan(w.graph, True)
+        k[cfg] = (strict.n_clusters, dup.n_clusters)
+    # without duplication a producer read in two orders stays manifest (cfg 1, cfg 5)
+    assert k == {1: (2, 1), 2: (1, 1), 3: (1, 1), 4: (1, 1), 5: (2, 1)}
+
+
+# ------------------------------------------------------------------ ragged sizes, tiles, edges
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 255, 4095, 4096, 4097, 8191, 12289, 1 << 20])
+def test_fold_sizes(n):
+    w = C.reverse_dot(n=n, seed=100 + n)
+    run_all_modes(1, w)
+    w = C.perm_gather_fold(n=n, seed=200 + n)
+    run_all_modes(2, w)
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 4095, 4096, 4097, 65536 + 17, 3 * 4096, (1 << 20) + 5])
+def test_compaction_sizes(n):
+    run_all_modes(4, C.compaction(n=n, seed=300 + n))
+
+
+def test_compaction_degenerate_flags():
+    n = 50000
+    for v in (np.zeros(n, np.int32) + 3, np.zeros(n, np.int32) + 1, np.arange(n, dtype=np.int32)):
+        run_all_modes(4, C.compaction(v=v))
+
+
+def test_empty_inputs():
+    w = C.reverse_dot(xs=np.zeros(0, F32))
+    env = evaluate(w.graph, w.inputs)
+    for part in (plan(w.graph, True), (w.graph, None)):
+        prog = device_program(part[0], w.inputs, part[1])
+        prog.run()
+        assert prog.fetch("r")[0] == 0.0 == env["r"][0]
+    w = C.compaction(v=np.zeros(0, np.int32))
+    g, part = plan(w.graph, True)
+    prog = device_program(g, w.inputs, part)
+    prog.run()
+    assert prog.fetch("count")[0] == 0
+    w = C.spmv(lengths=np.zeros(0, np.int64), ncols=4, seed=1)
+    g, part = plan(w.graph, True)
+    prog = device_program(g, w.inputs, part)
+    prog.run()
+    assert prog.fetch("y").shape == (0,)
+
+
+@pytest.mark.parametrize("lengths", [
+    [0, 0, 0], [1], [5000], [0, 17, 0, 16, 15, 33, 1, 0], [16] * 1000, [0] * 100 + [3] + [0] * 100,
+    list(range(0, 70)), [100000, 0, 1, 0, 100000],
+])
+def test_spmv_row_shapes(lengths):
+    lengths = np.asarray(lengths, dtype=np.int64)
+    w = C.spmv(lengths=lengths, seed=int(lengths.sum()) % 1000 + 400, ncols=max(int(lengths.max()), 8))
+    run_all_modes(3, w)
+
+
+def test_spmv_skewed_rows():
+    rng = np.random.default_rng(77)
+    lengths = np.minimum(rng.zipf(1.5, size=5000), 20000).astype(np.int64)
+    run_all_modes(3, C.spmv(lengths=lengths, seed=78, ncols=5000))
+
+
+@pytest.mark.parametrize("hw", [(1, 4), (1, 8), (2, 4), (3, 3), (1, 1), (5, 7), (33, 248), (34, 252), (64, 256),
+                                (65, 1000), (7, 1004), (100, 2048), (31, 996)])
+def test_stencil_shapes(hw):
+    run_all_modes(5, C.stencil_max(h=hw[0], w=hw[1], seed=500 + hw[0] * 7 + hw[1]))
+
+
+def test_stencil_constant_grid_borders():
+    w = C.stencil_max(grid=np.full((40, 500), F32(0.25)))
+    res = run_all_modes(5, w)
+    assert np.all(res["dup"]["out"] == res["dup"]["out"][0, 0])
+
+
+# ------------------------------------------------------------------ scratch reuse
+def test_repeated_runs_share_scratch():
+    for cfg in (2, 4, 5):
+        w = build(cfg, small=True)
+        env = evaluate(w.graph, w.inputs)
+        g, part = plan(w.graph, True)
+        prog = device_program(g, w.inputs, part)
+        for rep in range(4):
+            if cfg == 4:
+                prog.upload("dest", w.inputs["dest"])
+            prog.run()
+            compare(cfg, w, env, prog, w.graph.outputs(), f"rep{rep}")
+        words = prog.control_words()
+        assert words[0] == 0 and words[1] == 0 and words[3] == 0
+        if cfg == 4:
+            assert words[2] == 4        # one look-back launch per run
+
+
+def test_fusion_rule_clusters_execute():
+    """`simple1`, `simple2`, reverse and a diagonal cluster, each as one kernel."""
+    rng = np.random.default_rng(9)
+    n, m = 5003, 3001
+    xs = rng.standard_normal(n).astype(F32)
+    is1 = rng.integers(0, n, m, dtype=np.int32)
+    is2 = rng.integers(0, m, 777, dtype=np.int32)
+    g = Graph()
+    g.add("xs", "input", "f32", (n,))
+    g.add("is", "input", "i32", (m,))
+    g.add("as", "map", "f32", (n,), fn="affine", fparam=(3.0, -0.5), args=("xs",))
+    g.add("bs", "gather", "f32", (m,), args=("is", "as"), output=True)
+    part = fc().fc_plan(g, "bytes")
+    assert part.n_clusters == 1 and part.fused_away[2] == 1
+    prog = device_program(g, {"xs": xs, "is": is1}, part)
+    prog.run()
+    P.assert_bit_exact(prog.fetch("bs"), evaluate(g, {"xs": xs, "is": is1})["bs"], "simple1")
+
+    g = Graph()
+    g.add("is1", "input", "i32", (m,))
+    g.add("is2", "input", "i32", (777,))
+    g.add("xs", "input", "f32", (n,))
+    g.add("as", "gather", "f32", (m,), args=("is1", "xs"))
+    g.add("bs", "gather", "f32", (777,), args=("is2", "as"), output=True)
+    part = fc().fc_plan(g, "bytes")
+    assert part.n_clusters == 1
+    ins = {"xs": xs, "is1": is1, "is2": is2}
+    prog = device_program(g, ins, part)
+    prog.run()
+    P.assert_bit_exact(prog.fetch("bs"), evaluate(g, ins)["bs"], "simple2")
+
+
+# ------------------------------------------------------------------ full sizes (the launch shapes the bench times)
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_configs_match_oracle(cfg):
+    w = build(cfg)
+    env = evaluate(w.graph, w.inputs)
+    g, part = plan(w.graph, True)
+    prog = device_program(g, w.inputs, part)
+    prog.run()
+    compare(cfg, w, env, prog, w.graph.outputs(), "full-fused")
+    del prog
+    prog = device_program(w.graph, w.inputs, None)
+    prog.run()
+    compare(cfg, w, env, prog, w.graph.outputs(), "full-unfused")
