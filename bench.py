@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Throughput of the fused pipelines on one MI355X.
+
+A step is one pass of the whole hot path: the five synthetic pipelines, each
+executed as its fused clusters (fc_run_fused), inputs resident in HBM.  The
+reported value is the fused-traffic lower bound of a step (every external input
+byte once + every output byte once) divided by the time of a step.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--configs 1,2,3,4,5]
+
+One JSON line goes to stdout; a table per pipeline goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published peak
+ROTATE_BYTES = 1 << 30       # cycle through input sets until at least this much is touched between
+#                              two uses of the same set (the 256 MiB memory-side cache must not serve a pipeline)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--configs", default="1,2,3,4,5")
+    ap.add_argument("--small", action="store_true", help="small sizes (debugging only; not a valid measurement)")
+    ap.add_argument("--no-unfused", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU; there is no multi-GPU path to measure (got --gpus %d)" % args.gpus)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2407_13585_amd as fc
+    from paper_2407_13585_amd.device import DeviceProgram, require_gpu
+    from workloads import build
+
+    dev = require_gpu()
+    cfgs = [int(c) for c in args.configs.split(",")]
+
+    # ---- build the workloads and the device programs --------------------------------------
+    t0 = time.time()
+    work, fused, unfused, kernels = {}, {}, {}, {}
+    for c in cfgs:
+        w = build(c, small=args.small)
+        g, _ = fc.fc_duplicate(w.graph)
+        part = fc.fc_plan(g, "bytes")
+        footprint = sum(a.nbytes for a in w.inputs.values()) + 4 * sum(w.graph[o].size for o in w.graph.outputs())
+        sets = max(2, min(8, -(-ROTATE_BYTES // max(footprint, 1))))
+        fused[c] = [DeviceProgram(g, w.inputs, part) for _ in range(sets)]
+        kernels[c] = fused[c][0].kernels()
+        if not args.no_unfused:
+            unfused[c] = DeviceProgram(w.graph, w.inputs, None)
+        work[c] = w
+        log(f"cfg{c}: {w.name} units={w.units} {w.unit_name}, LB={w.lb_bytes / 1e6:.1f} MB, "
+            f"{part.n_clusters} fused cluster(s), {sets} rotating input sets: {kernels[c]}")
+    log(f"setup {time.time() - t0:.1f}s")
+
+    def one_step(s, events=None):
+        for k, c in enumerate(cfgs):
+            if events is not None:
+                events[k].record()
+            fused[c][s % len(fused[c])].run()
+        if events is not None:
+            events[len(cfgs)].record()
+
+    # ---- timed region ----------------------------------------------------------------------
+    for s in range(args.warmup):
+        one_step(s)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(cfgs) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        one_step(args.warmup + s, ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    # per-pipeline kernel time from the HIP events on the launch stream
+    kt = {c: [] for c in cfgs}
+    for s in range(args.steps):
+        for k, c in enumerate(cfgs):
+            kt[c].append(ev[s][k].elapsed_time(ev[s][k + 1]))       # ms
+    gpu_ms = {c: float(np.mean(kt[c])) for c in cfgs}
+    gpu_med = {c: float(np.median(kt[c])) for c in cfgs}
+
+    # ---- unfused arm: one kernel per combinator ---------------------------------------------
+    unf_ms = {}
+    if not args.no_unfused:
+        for c in cfgs:
+            p = unfused[c]
+            reps = 3 if c == 5 else 5
+            p.run()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                p.run()
+            b.record()
+            torch.cuda.synchronize()
+            unf_ms[c] = a.elapsed_time(b) / reps
+
+    # ---- CPU baseline: the oracle as it stands, one step on the host ------------------------
+    cpu = None
+    if not args.no_cpu:
+        from oracle.interp import evaluate
+        t0 = time.perf_counter()
+        for c in cfgs:
+            evaluate(work[c].graph, work[c].inputs)
+        cpu_s = time.perf_counter() - t0
+        lb = sum(work[c].lb_bytes for c in cfgs)
+        cpu = {"value": lb / cpu_s / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": f"one step (pipelines {args.configs} at the benchmarked sizes), {cpu_s:.2f} s, "
+                         f"numpy single thread, host has {os.cpu_count()} logical cores"}
+
+    # ---- report ----------------------------------------------------------------------------
+    lb_total = sum(work[c].lb_bytes for c in cfgs)
+    per = {}
+    for c in cfgs:
+        w = work[c]
+        gbs = w.lb_bytes / (gpu_ms[c] * 1e-3) / 1e9
+        per[f"cfg{c}"] = {
+            "kernel_ms": round(gpu_ms[c], 5), "kernel_ms_median": round(gpu_med[c], 5),
+            "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+            f"{w.unit_name}/s": round(w.units / (gpu_ms[c] * 1e-3), 1), "lb_bytes": w.lb_bytes,
+            "unfused_ms": round(unf_ms[c], 5) if c in unf_ms else None,
+            "speedup_vs_unfused": round(unf_ms[c] / gpu_ms[c], 2) if c in unf_ms else None,
+            "kernels": kernels[c],
+        }
+        log(f"cfg{c}: {gpu_ms[c] * 1e3:9.1f} us  {gbs:8.1f} GB/s  {100 * gbs / HBM_PEAK_GBS:5.1f}% of HBM peak  "
+            + (f"unfused {unf_ms[c] * 1e3:10.1f} us  speedup {unf_ms[c] / gpu_ms[c]:6.2f}x" if c in unf_ms else ""))
+    dom = max(cfgs, key=lambda c: gpu_ms[c])
+    achieved = work[dom].lb_bytes / (gpu_ms[dom] * 1e-3) / 1e9
+    out = {
+        "metric": "fused pipeline GB/s (fused-traffic lower bound / time)",
+        "value": round(lb_total / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": ("SMALL DEBUG SIZES " if args.small else "") +
+                   "all five BASELINE pipelines, fused: " + ", ".join(work[c].name for c in cfgs)},
+        "gpu_sum_kernel_ms": round(sum(gpu_ms.values()), 5),
+        "frac_hbm_peak": round(lb_total / (sum(gpu_ms.values()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "per_config": per,
+        "roofline": {"bound": "hbm", "kernel": kernels[dom][0], "workload": work[dom].name,
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -52,25 +52,31 @@ __global__ __launch_bounds__(kBlock) void store_kernel(const KArgs a) {
 // scheduling.  fold is one stage of a multi-stage parallel reduction (section 2, fold).
 template <class Op>
 __device__ __forceinline__ void fold_finish(typename Op::T acc, const KArgs &a, int out_slot, Control *ctl,
-                                            unsigned *partials) {
+                                            unsigned long long *partials) {
   using T = typename Op::T;
   __shared__ T lds[kWavesPerBlock + 1];
-  __shared__ unsigned last;
+  const unsigned epoch = load_agent(&ctl->epoch);
+  const unsigned tag = tag_of_epoch(epoch);
   T r = block_reduce<Op>(acc, lds);
-  if (threadIdx.x == 0) store_agent(&partials[blockIdx.x], (unsigned)as_bits(r));
-  if (last_block_done(ctl, gridDim.x, &last)) {
+  if (threadIdx.x == 0) store_agent64(&partials[blockIdx.x], pack_word((unsigned)as_bits(r), tag, 1u));
+  // the workgroup with the highest index is dispatched last; it waits for the
+  // partials of all others and combines them in index order
+  if (blockIdx.x == gridDim.x - 1) {
     T s = Op::identity();
-    for (unsigned k = threadIdx.x; k < gridDim.x; k += kBlock) s = Op::apply(s, from_bits<T>((int)load_agent(&partials[k])));
+    for (unsigned k = threadIdx.x; k < gridDim.x; k += kBlock) {
+      unsigned long long w = wait_word(&partials[k], tag, ctl);
+      s = Op::apply(s, w ? from_bits<T>((int)(unsigned)(w >> 32)) : Op::identity());
+    }
     s = block_reduce<Op>(s, lds);
     if (threadIdx.x == 0) {
       *static_cast<T *>(a.out[out_slot]) = s;
-      store_agent(&ctl->done, 0u);
+      store_agent(&ctl->epoch, epoch + 1u);
     }
   }
 }
 
 template <class Op, class E>
-__global__ __launch_bounds__(kBlock) void fold_kernel(const KArgs a, Control *ctl, unsigned *partials) {
+__global__ __launch_bounds__(kBlock) void fold_kernel(const KArgs a, Control *ctl, unsigned long long *partials) {
   using T = typename Op::T;
   const unsigned n = (unsigned)a.n, n4 = n & ~3u;
   T acc = Op::identity();
@@ -97,7 +103,7 @@ __global__ __launch_bounds__(kBlock) void fold_kernel(const KArgs a, Control *ct
 
 // out[0][i] = ES(i) and out[1] = fold(Op, EF(i)) in one pass
 template <class ES, class Op, class EF>
-__global__ __launch_bounds__(kBlock) void store_fold_kernel(const KArgs a, Control *ctl, unsigned *partials) {
+__global__ __launch_bounds__(kBlock) void store_fold_kernel(const KArgs a, Control *ctl, unsigned long long *partials) {
   using T = typename Op::T;
   using S = typename ES::R;
   S *out = static_cast<S *>(a.out[0]);
@@ -153,38 +159,28 @@ __global__ __launch_bounds__(kBlock) void foldseg_kernel(const KArgs a) {
 // ------------------------------------------------------------------ single-pass scan / compaction
 // Exclusive (+) scan of the int32 stream EX in one pass over the data (section
 // 2: a scan inside a cluster must be a single pass; the chained scan is one of
-// the implementations named there).  Tiles are handed out by a ticket counter so
-// that every predecessor of a tile is already running; each tile publishes its
-// aggregate, then looks back over the status words of its predecessors until it
-// meets an inclusive prefix.  The scan result never reaches memory unless asked
-// for: kOffs stores it, kScatter writes EV(i) to dest[offs[i]] where EX(i) != 0
-// (scatter with collision-free indices: plain stores), kCount stores the total.
+// the implementations named there).  Tile t is processed by workgroup t; each
+// tile publishes its aggregate, then looks back over the status words of its
+// predecessors until it meets an inclusive prefix (decoupled look-back).
+// Workgroups are dispatched in index order, so the lowest unfinished tile is
+// always running and can always finish; every wait is bounded all the same.
+// The scan result never reaches memory unless asked for: kOffs stores it,
+// kScatter writes EV(i) to dest[offs[i]] where EX(i) != 0 (scatter with
+// collision-free indices: plain stores, no atomics), kCount stores the total.
 constexpr int kScanItems = 16;                        // per lane
 constexpr int kScanTile = kBlock * kScanItems;        // 4096
 constexpr int kOffs = 1, kScatter = 2, kCount = 4;
-constexpr unsigned kSpinLimit = 1u << 22;
-
-__device__ __forceinline__ unsigned long long pack_status(int value, unsigned tag, unsigned state) {
-  return ((unsigned long long)(unsigned)value << 32) | (unsigned long long)((tag << 2) | state);
-}
 
 template <class EX, class EV, int Mode>
 __global__ __launch_bounds__(kBlock) void scan_kernel(const KArgs a, Control *ctl, unsigned long long *status) {
   __shared__ int lds_wave[kWavesPerBlock];
-  __shared__ int lds_bcast[2];
-  __shared__ unsigned lds_last;
+  __shared__ int lds_prefix;
   const unsigned n = (unsigned)a.n;
   const unsigned n_tiles = gridDim.x;
+  const unsigned tile = blockIdx.x;
   const int lane = lane_id(), wave = wave_id();
-
-  if (threadIdx.x == 0) {
-    lds_bcast[0] = (int)__hip_atomic_fetch_add(&ctl->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    lds_bcast[1] = (int)load_agent(&ctl->epoch);
-  }
-  __syncthreads();
-  const unsigned tile = (unsigned)lds_bcast[0];
-  const unsigned tag = ((unsigned)lds_bcast[1] % 0x3ffffffeu) + 1u;   // never 0: a zeroed word is "not ready"
-  if (tile >= n_tiles) return;                                        // control block was not clean
+  const unsigned epoch = load_agent(&ctl->epoch);
+  const unsigned tag = tag_of_epoch(epoch);
 
   // wave-striped layout: wave w owns 1024 consecutive elements; access j of a
   // lane covers elements base + j*256 + lane*4 .. +3 (fully coalesced)
@@ -223,26 +219,19 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(const KArgs a, Control *ct
     aggregate += t;
   }
 
-  // publish, then look back (wave 0)
+  // publish, then look back (wave 0): lane l inspects tile - 1 - l
   if (wave == 0) {
-    if (lane == 0)
-      store_agent64(&status[tile], pack_status(aggregate, tag, tile == 0 ? 2u : 1u));
+    if (lane == 0) store_agent64(&status[tile], pack_word((unsigned)aggregate, tag, tile == 0 ? 2u : 1u));
     int prefix = 0;
     if (tile > 0) {
       int pred = (int)tile - 1 - lane;
-      bool ok = true;
       while (true) {
         int value = 0;
-        unsigned state = 2u;                 // tiles before the first: prefix 0
+        unsigned state = 2u;                 // before the first tile: prefix 0
         if (pred >= 0) {
-          unsigned spins = 0;
-          while (true) {
-            unsigned long long st = load_agent64(&status[pred]);
-            unsigned lo = (unsigned)st;
-            if ((lo >> 2) == tag && (lo & 3u) != 0u) { value = (int)(st >> 32); state = lo & 3u; break; }
-            if (++spins > kSpinLimit) { ok = false; state = 2u; break; }   // give up: never hang the device
-            __builtin_amdgcn_s_sleep(1);
-          }
+          unsigned long long w = wait_word(&status[pred], tag, ctl);
+          value = (int)(unsigned)(w >> 32);
+          state = w ? ((unsigned)w & 3u) : 2u;   // a wait that gave up ends the look-back
         }
         unsigned long long has_prefix = __ballot(state == 2u);
         int first = has_prefix ? (int)__builtin_ctzll(has_prefix) : kWave;
@@ -250,16 +239,19 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(const KArgs a, Control *ct
         if (has_prefix) break;
         pred -= kWave;
       }
-      if (__ballot(!ok) && lane == 0) store_agent(&ctl->pad[0], 1u);      // error word
-      if (lane == 0) store_agent64(&status[tile], pack_status(prefix + aggregate, tag, 2u));
+      if (lane == 0) store_agent64(&status[tile], pack_word((unsigned)(prefix + aggregate), tag, 2u));
     }
-    if (lane == 0) lds_bcast[0] = prefix;
+    if (lane == 0) lds_prefix = prefix;
   }
   __syncthreads();
-  const int tile_excl = lds_bcast[0];
+  const int tile_excl = lds_prefix;
 
-  if ((Mode & kCount) && tile == n_tiles - 1 && threadIdx.x == 0)
-    *static_cast<int *>(a.out[2]) = tile_excl + aggregate;
+  if (tile == n_tiles - 1 && threadIdx.x == 0) {
+    if (Mode & kCount) *static_cast<int *>(a.out[2]) = tile_excl + aggregate;
+    // the last tile has seen a prefix that covers every other tile, so all of them
+    // have taken their tag: the next launch may use the next one
+    store_agent(&ctl->epoch, epoch + 1u);
+  }
 
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -290,14 +282,6 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(const KArgs a, Control *ct
         for (int c = 0; c < 4; ++c)
           if (i + c < n && x[j][c] != 0) dest[o[c]] = EV::template eval<EX::kNodes>(a, (int)(i + c));
       }
-    }
-  }
-
-  if (last_block_done(ctl, n_tiles, &lds_last)) {
-    if (threadIdx.x == 0) {
-      store_agent(&ctl->ticket, 0u);
-      store_agent(&ctl->done, 0u);
-      store_agent(&ctl->epoch, (unsigned)lds_bcast[1] + 1u);
     }
   }
 }

@@ -139,31 +139,45 @@ __device__ __forceinline__ unsigned long long load_agent64(const unsigned long l
 }
 
 // ------------------------------------------------------------------ scratch control block
-// Layout of the first bytes of the caller's scratch buffer.  All words are zero
-// before the first use and are returned to the state the next launch expects by
-// the last workgroup of every kernel that uses them.
+// Layout of the first bytes of the caller's scratch buffer.  Cross-workgroup
+// steps use no read-modify-write atomics: device-scope atomics on one address
+// serialise (tens of nanoseconds each), which would dominate a kernel of a few
+// thousand workgroups.  Instead every launch takes a tag from `epoch`, results
+// that other workgroups wait for are published as 64-bit words carrying that tag
+// (one agent-scope store), and readers poll until the tag matches.  Words left by
+// earlier launches carry older tags and a zero-filled buffer carries tag 0, which
+// is never used, so nothing has to be cleared between launches.  The workgroup
+// that finishes the launch's protocol last by construction (it has seen the
+// words of all others) advances `epoch`.
 struct Control {
-  unsigned ticket;      // next tile to hand out (single-pass scan)
-  unsigned done;        // workgroups that have finished
-  unsigned epoch;       // launches of look-back kernels so far; tags tile status words
-  unsigned pad[61];
+  unsigned epoch;       // launches of tagged kernels so far
+  unsigned error;       // set to 1 when a bounded wait gave up (results of that launch are invalid)
+  unsigned pad[62];
 };
 constexpr int kMaxPartials = 8192;                 // workgroups of a fold launch
 constexpr size_t kPartialsOffset = sizeof(Control);
-constexpr size_t kStatusOffset = kPartialsOffset + kMaxPartials * 2 * sizeof(unsigned);
+constexpr size_t kStatusOffset = kPartialsOffset + kMaxPartials * sizeof(unsigned long long);
 constexpr size_t kMaxTiles = (FC_SCRATCH_CONTROL_BYTES - kStatusOffset) / sizeof(unsigned long long);
+constexpr unsigned kSpinLimit = 1u << 22;          // polls before a wait gives up: never hang the device
 
-// The calling workgroup reports completion; returns true (to all its threads) in
-// the one workgroup that reports last.  Writes made before the call by any
-// workgroup with store_agent() are visible to load_agent() in that workgroup.
-__device__ __forceinline__ bool last_block_done(Control *ctl, unsigned n_blocks, unsigned *lds_flag) {
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned prev = __hip_atomic_fetch_add(&ctl->done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    *lds_flag = (prev == n_blocks - 1);
+__device__ __forceinline__ unsigned tag_of_epoch(unsigned epoch) { return epoch % 0x3ffffffeu + 1u; }  // 30 bits, never 0
+
+// word = value (high 32 bits) | tag << 2 | state (low 2 bits, 0 = not ready)
+__device__ __forceinline__ unsigned long long pack_word(unsigned value, unsigned tag, unsigned state) {
+  return ((unsigned long long)value << 32) | (unsigned long long)((tag << 2) | state);
+}
+
+// Polls `p` until it carries `tag` with a non-zero state; returns the word, or 0
+// after kSpinLimit polls (and raises the error word).
+__device__ __forceinline__ unsigned long long wait_word(const unsigned long long *p, unsigned tag, Control *ctl) {
+  for (unsigned spins = 0; spins < kSpinLimit; ++spins) {
+    unsigned long long w = load_agent64(p);
+    unsigned lo = (unsigned)w;
+    if ((lo >> 2) == tag && (lo & 3u) != 0u) return w;
+    __builtin_amdgcn_s_sleep(1);
   }
-  __syncthreads();
-  return *lds_flag != 0;
+  store_agent(&ctl->error, 1u);
+  return 0ull;
 }
 
 }  // namespace fc

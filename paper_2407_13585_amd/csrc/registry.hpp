@@ -16,7 +16,7 @@ struct Control;
 struct LaunchCtx {
   hipStream_t stream;
   Control *ctl;                   // DEVICE: control block at the start of scratch
-  unsigned *partials;             // DEVICE: per-workgroup partial results of a fold
+  unsigned long long *partials;             // DEVICE: per-workgroup partial results of a fold
   unsigned long long *status;     // DEVICE: tile status words of the single-pass scan
   size_t max_tiles;
 };

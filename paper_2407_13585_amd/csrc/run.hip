@@ -270,7 +270,7 @@ int run_clustering(const Model &m, const Clustering &c, const fc_buffer *bufs, v
   LaunchCtx ctx;
   ctx.stream = stream;
   ctx.ctl = static_cast<Control *>(scratch);
-  ctx.partials = reinterpret_cast<unsigned *>(static_cast<char *>(scratch) + kPartialsOffset);
+  ctx.partials = reinterpret_cast<unsigned long long *>(static_cast<char *>(scratch) + kPartialsOffset);
   ctx.status = reinterpret_cast<unsigned long long *>(static_cast<char *>(scratch) + kStatusOffset);
   ctx.max_tiles = kMaxTiles;
 

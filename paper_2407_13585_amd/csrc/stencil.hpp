@@ -44,7 +44,7 @@ __device__ __forceinline__ Quad load_row(const float *g, const Slot &s, int r, i
 // F: element function of the shared producer (FnExpNeg, or FnIdentF when p is
 // read from memory).  WithMax: also fold(max) over p into out[1].
 template <class F, int FSlot, bool WithMax>
-__global__ __launch_bounds__(kBlock) void stencil5_kernel(const KArgs a, Control *ctl, unsigned *partials,
+__global__ __launch_bounds__(kBlock) void stencil5_kernel(const KArgs a, Control *ctl, unsigned long long *partials,
                                                           int n_groups, int n_bands, int band_rows) {
   const int H = a.h, W = a.w;
   const float *g = static_cast<const float *>(a.in[0]);
@@ -118,7 +118,7 @@ hipError_t launch_stencil5(const KArgs &a, const LaunchCtx &c) {
   const int blocks = ((groups * bands + 7) / 8) * 8;
   KArgs args = a;
   Control *ctl = c.ctl;
-  unsigned *partials = c.partials;
+  unsigned long long *partials = c.partials;
   int g = groups, b = bands, br = band_rows;
   void *ptrs[] = {&args, &ctl, &partials, &g, &b, &br};
   return hipLaunchKernel(reinterpret_cast<const void *>(&stencil5_kernel<F, FSlot, WithMax>), dim3(blocks),

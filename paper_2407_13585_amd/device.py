@@ -74,7 +74,7 @@ class DeviceProgram:
             self.buffers[name][:a.size].copy_(torch.from_numpy(a))
 
     def control_words(self) -> np.ndarray:
-        """First words of the scratch control block (ticket, done, epoch, error)."""
+        """First words of the scratch control block: launch epoch, error flag."""
         torch.cuda.synchronize(self.device)
         return self.scratch[:4].cpu().numpy().copy()
 

@@ -71,7 +71,7 @@ def run_all_modes(cfg, w, env=None):
         prog.run()
         compare(cfg, w, env, prog, outs, "fused-dup" if dup else "fused-strict")
         results["dup" if dup else "strict"] = {o: prog.fetch(o) for o in outs}
-        assert prog.control_words()[:2].tolist() == [0, 0] and prog.control_words()[3] == 0
+        assert prog.control_words()[1] == 0          # no bounded wait gave up
     inter = [n.name for n in w.graph.nodes if n.kind != "input"]
     prog = device_program(w.graph, w.inputs, None, bind=inter)
     prog.run()
@@ -182,9 +182,8 @@ def test_repeated_runs_share_scratch():
             prog.run()
             compare(cfg, w, env, prog, w.graph.outputs(), f"rep{rep}")
         words = prog.control_words()
-        assert words[0] == 0 and words[1] == 0 and words[3] == 0
-        if cfg == 4:
-            assert words[2] == 4        # one look-back launch per run
+        assert words[1] == 0
+        assert words[0] == 4            # one tagged launch per run
 
 
 def test_fusion_rule_clusters_execute():
