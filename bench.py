@@ -40,6 +40,9 @@ def main() -> int:
     ap.add_argument("--small", action="store_true", help="small sizes (debugging only; not a valid measurement)")
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain copy kernel of known size (256 MiB in, 256 MiB out): the reference "
+                         "that hardware counter readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU; there is no multi-GPU path to measure (got --gpus %d)" % args.gpus)
@@ -71,6 +74,18 @@ def main() -> int:
         log(f"cfg{c}: {w.name} units={w.units} {w.unit_name}, LB={w.lb_bytes / 1e6:.1f} MB, "
             f"{part.n_clusters} fused cluster(s), {sets} rotating input sets: {kernels[c]}")
     log(f"setup {time.time() - t0:.1f}s")
+
+    if args.calibrate:
+        from workloads import Graph
+        n = 1 << 26
+        cg = Graph()
+        cg.add("src", "input", "f32", (n,))
+        cg.add("dst", "map", "f32", (n,), fn="ident", args=("src",), output=True)
+        cal = DeviceProgram(cg, {"src": np.zeros(n, np.float32)}, fc.fc_plan(cg, "bytes"))
+        for _ in range(3):
+            cal.run()
+        torch.cuda.synchronize()
+        log(f"calibration copy: {cal.kernels()} moves {4 * n} B in and {4 * n} B out per launch")
 
     def one_step(s, events=None):
         for k, c in enumerate(cfgs):

@@ -98,6 +98,8 @@ typedef struct fc_node {
   int32_t  rank;              /* 1 or 2 */
   int64_t  shape[2];          /* row-major extents; unused extents are 1 */
   uint32_t flags;
+  uint32_t infusible_args;    /* bit k set: the edge from arg[k] is infusible whatever the kinds say
+                                 (the argument is indexed with `!`, wrapped in force, or passed to foreign code) */
 } fc_node;
 
 /* The data dependence graph (n, N, F, I) of section 4.1.  Edges are implied by

@@ -47,7 +47,8 @@ class fc_node(C.Structure):
     _fields_ = [("kind", C.c_int32), ("dtype", C.c_int32), ("fn", C.c_int32),
                 ("fparam", C.c_float * 2), ("iparam", C.c_int32 * 4),
                 ("nargs", C.c_int32), ("arg", C.c_int32 * FC_MAX_ARGS),
-                ("rank", C.c_int32), ("shape", C.c_int64 * 2), ("flags", C.c_uint32)]
+                ("rank", C.c_int32), ("shape", C.c_int64 * 2), ("flags", C.c_uint32),
+                ("infusible_args", C.c_uint32)]
 
 
 class fc_graph(C.Structure):
@@ -148,6 +149,7 @@ class CGraph:
             c.shape[0] = int(n.shape[0])
             c.shape[1] = int(n.shape[1]) if len(n.shape) == 2 else 1
             c.flags = FC_NODE_OUTPUT if n.output else 0
+            c.infusible_args = sum(1 << k for k in getattr(n, "infusible", ()))
         self.c = fc_graph(len(graph.nodes), self.nodes)
         self.n_edges = len(graph.edges())
 
@@ -247,7 +249,7 @@ def fc_duplicate(graph: Graph) -> Tuple[Graph, List[int]]:
         new.add(name, base.kind, base.dtype, base.shape,
                 fn=base.fn, fparam=base.fparam, iparam=base.iparam,
                 args=tuple(new_names[out[i].arg[j]] for j in range(out[i].nargs)),
-                output=bool(out[i].flags & FC_NODE_OUTPUT))
+                output=bool(out[i].flags & FC_NODE_OUTPUT), infusible=base.infusible)
     return new, [origin[i] for i in range(n.value)]
 
 

@@ -24,14 +24,19 @@ unsigned grid_for(int n, int tile, unsigned cap) {
 // launch (hipGetLastError would also report an error an earlier, unrelated call
 // left behind on the thread).
 template <class... P, size_t... I>
-hipError_t launch_impl(void (*k)(P...), dim3 grid, hipStream_t s, std::tuple<P...> &vals, std::index_sequence<I...>) {
+hipError_t launch_impl(void (*k)(P...), dim3 grid, dim3 block, hipStream_t s, std::tuple<P...> &vals,
+                       std::index_sequence<I...>) {
   void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))...};
-  return hipLaunchKernel(reinterpret_cast<const void *>(k), grid, dim3(kBlock), ptrs, 0, s);
+  return hipLaunchKernel(reinterpret_cast<const void *>(k), grid, block, ptrs, 0, s);
 }
-template <class... P, class... A>
-hipError_t launch_k(void (*k)(P...), unsigned grid, hipStream_t s, A... a) {
+template <class... P>
+hipError_t launch_k(void (*k)(P...), unsigned grid, hipStream_t s, int block, P... a) {
   std::tuple<P...> vals(a...);
-  return launch_impl(k, dim3(grid), s, vals, std::index_sequence_for<P...>());
+  return launch_impl(k, dim3(grid), dim3(block), s, vals, std::index_sequence_for<P...>());
+}
+template <class... P>
+hipError_t launch_k(void (*k)(P...), unsigned grid, hipStream_t s, P... a) {
+  return launch_k(k, grid, s, (int)kBlock, a...);
 }
 template <class E> hipError_t launch_store(const KArgs &a, const LaunchCtx &c) {
   if (a.n == 0) return hipSuccess;
@@ -50,7 +55,7 @@ template <class Op, class E> hipError_t launch_foldseg(const KArgs &a, const Lau
 template <class EX, class EV, int Mode> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {
   long long tiles = std::max<long long>(1, ((long long)a.n + kScanTile - 1) / kScanTile);
   if ((size_t)tiles > c.max_tiles) return hipErrorInvalidValue;
-  return launch_k(&scan_kernel<EX, EV, Mode>, (unsigned)tiles, c.stream, a, c.ctl, c.status);
+  return launch_k(&scan_kernel<EX, EV, Mode>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status);
 }
 template <class EI, class EV, class EF> hipError_t launch_scatter(const KArgs &a, const LaunchCtx &c) {
   if (a.n == 0) return hipSuccess;

@@ -167,14 +167,18 @@ __global__ __launch_bounds__(kBlock) void foldseg_kernel(const KArgs a) {
 // The scan result never reaches memory unless asked for: kOffs stores it,
 // kScatter writes EV(i) to dest[offs[i]] where EX(i) != 0 (scatter with
 // collision-free indices: plain stores, no atomics), kCount stores the total.
+constexpr int kScanBlock = 512;                       // threads per workgroup of the scan kernels
+constexpr int kScanWaves = kScanBlock / kWave;
 constexpr int kScanItems = 16;                        // per lane
-constexpr int kScanTile = kBlock * kScanItems;        // 4096
+constexpr int kScanTile = kScanBlock * kScanItems;    // 8192 elements
 constexpr int kOffs = 1, kScatter = 2, kCount = 4;
 
 template <class EX, class EV, int Mode>
-__global__ __launch_bounds__(kBlock) void scan_kernel(const KArgs a, Control *ctl, unsigned long long *status) {
-  __shared__ int lds_wave[kWavesPerBlock];
-  __shared__ int lds_prefix;
+__global__ __launch_bounds__(kScanBlock) void scan_kernel(const KArgs a, Control *ctl, unsigned long long *status) {
+  __shared__ int lds_wave[kScanWaves];
+  __shared__ int lds_part[kScanWaves];
+  __shared__ int lds_found[kScanWaves];
+  using V = typename EV::R;
   const unsigned n = (unsigned)a.n;
   const unsigned n_tiles = gridDim.x;
   const unsigned tile = blockIdx.x;
@@ -186,6 +190,7 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(const KArgs a, Control *ct
   // lane covers elements base + j*256 + lane*4 .. +3 (fully coalesced)
   const unsigned wbase = tile * kScanTile + wave * (kWave * kScanItems);
   int x[4][4];
+  V val[4][4];
   int s[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -194,9 +199,17 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(const KArgs a, Control *ct
       Vec4<int> v = EX::template eval4<0>(a, (int)i);
 #pragma unroll
       for (int c = 0; c < 4; ++c) x[j][c] = v.v[c];
+      if (Mode & kScatter) {
+        Vec4<V> u = EV::template eval4<EX::kNodes>(a, (int)i);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) val[j][c] = u.v[c];
+      }
     } else {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) x[j][c] = (i + c < n) ? EX::template eval<0>(a, (int)(i + c)) : 0;
+      for (int c = 0; c < 4; ++c) {
+        x[j][c] = (i + c < n) ? EX::template eval<0>(a, (int)(i + c)) : 0;
+        if (Mode & kScatter) val[j][c] = (i + c < n) ? EV::template eval<EX::kNodes>(a, (int)(i + c)) : V(0);
+      }
     }
     s[j] = (x[j][0] + x[j][1]) + (x[j][2] + x[j][3]);
   }
@@ -213,38 +226,45 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(const KArgs a, Control *ct
   __syncthreads();
   int wave_excl = 0, aggregate = 0;
 #pragma unroll
-  for (int k = 0; k < kWavesPerBlock; ++k) {
+  for (int k = 0; k < kScanWaves; ++k) {
     int t = lds_wave[k];
     if (k < wave) wave_excl += t;
     aggregate += t;
   }
 
-  // publish, then look back (wave 0): lane l inspects tile - 1 - l
-  if (wave == 0) {
-    if (lane == 0) store_agent64(&status[tile], pack_word((unsigned)aggregate, tag, tile == 0 ? 2u : 1u));
-    int prefix = 0;
-    if (tile > 0) {
-      int pred = (int)tile - 1 - lane;
-      while (true) {
-        int value = 0;
-        unsigned state = 2u;                 // before the first tile: prefix 0
-        if (pred >= 0) {
-          unsigned long long w = wait_word(&status[pred], tag, ctl);
-          value = (int)(unsigned)(w >> 32);
-          state = w ? ((unsigned)w & 3u) : 2u;   // a wait that gave up ends the look-back
-        }
-        unsigned long long has_prefix = __ballot(state == 2u);
-        int first = has_prefix ? (int)__builtin_ctzll(has_prefix) : kWave;
-        prefix += wave_reduce<AddI32>(lane <= first ? value : 0);
-        if (has_prefix) break;
-        pred -= kWave;
+  // publish the aggregate, then look back: thread t inspects tile - 1 - t, so one
+  // round covers the kScanBlock nearest predecessors.  The window has to be wide:
+  // the front of known prefixes advances by at most one window per memory round
+  // trip, and it must outrun the rate at which tiles stream through the chip.
+  if (threadIdx.x == 0) store_agent64(&status[tile], pack_word((unsigned)aggregate, tag, tile == 0 ? 2u : 1u));
+  int prefix = 0;
+  if (tile > 0) {
+    int pred = (int)tile - 1 - (int)threadIdx.x;
+    while (true) {
+      int value = 0;
+      unsigned state = 2u;                 // before the first tile: prefix 0
+      if (pred >= 0) {
+        unsigned long long w = wait_word(&status[pred], tag, ctl);
+        value = (int)(unsigned)(w >> 32);
+        state = w ? ((unsigned)w & 3u) : 2u;   // a wait that gave up ends the look-back
       }
-      if (lane == 0) store_agent64(&status[tile], pack_word((unsigned)(prefix + aggregate), tag, 2u));
+      unsigned long long has_prefix = __ballot(state == 2u);
+      int first = has_prefix ? (int)__builtin_ctzll(has_prefix) : kWave;
+      int part = wave_reduce<AddI32>(lane <= first ? value : 0);
+      if (lane == 0) { lds_part[wave] = part; lds_found[wave] = has_prefix != 0; }
+      __syncthreads();
+      bool found = false;
+#pragma unroll
+      for (int k = 0; k < kScanWaves; ++k) {
+        if (!found) { prefix += lds_part[k]; found = lds_found[k] != 0; }
+      }
+      __syncthreads();
+      if (found) break;
+      pred -= kScanBlock;
     }
-    if (lane == 0) lds_prefix = prefix;
+    if (threadIdx.x == 0) store_agent64(&status[tile], pack_word((unsigned)(prefix + aggregate), tag, 2u));
   }
-  __syncthreads();
-  const int tile_excl = lds_prefix;
+  const int tile_excl = prefix;
 
   if (tile == n_tiles - 1 && threadIdx.x == 0) {
     if (Mode & kCount) *static_cast<int *>(a.out[2]) = tile_excl + aggregate;
@@ -271,17 +291,9 @@ __global__ __launch_bounds__(kBlock) void scan_kernel(const KArgs a, Control *ct
       }
     }
     if (Mode & kScatter) {
-      using V = typename EV::R;
       V *dest = static_cast<V *>(a.out[0]);
-      if (i + 3 < n) {
-        Vec4<V> v = EV::template eval4<EX::kNodes>(a, (int)i);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) if (x[j][c] != 0) dest[o[c]] = v.v[c];
-      } else {
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (i + c < n && x[j][c] != 0) dest[o[c]] = EV::template eval<EX::kNodes>(a, (int)(i + c));
-      }
+      for (int c = 0; c < 4; ++c) if (i + c < n && x[j][c] != 0) dest[o[c]] = val[j][c];
     }
   }
 }

@@ -133,7 +133,8 @@ int build_model(const fc_graph *g, Model &m, std::string &err) {
       int a = nd.arg[k];
       int ka = m.nodes[a].kind;
       bool fusible = !(ka == FC_INPUT || ka == FC_FORCE || ka == FC_SCATTER) && nd.kind != FC_FORCE &&
-                     !(nd.kind == FC_SCATTER && k == 0) && !(nd.kind == FC_FOLDSEG && k == 1);
+                     !(nd.kind == FC_SCATTER && k == 0) && !(nd.kind == FC_FOLDSEG && k == 1) &&
+                     !((nd.infusible_args >> k) & 1u);
       int e = (int)m.edges.size();
       m.edges.push_back({a, i, k, fusible});
       m.out_edges[a].push_back(e);

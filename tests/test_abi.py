@@ -1,0 +1,139 @@
+"""The C ABI: every function include/fc.h declares is exported, and the host-side checks
+reject bad input with the documented error codes before any device work is enqueued."""
+import ctypes
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+import paper_2407_13585_amd as fc
+from paper_2407_13585_amd import binding as B
+from workloads import Graph, build
+from workloads import paper_graphs as PG
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"fc_plan", "fc_run_fused", "fc_run_unfused", "fc_last_error"} <= set(names)
+    lib = B.lib()
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_header_is_plain_c_and_struct_layout_matches_the_binding(tmp_path):
+    # fc.h must compile as C; the sizes and a few offsets gcc gives its PODs must equal ctypes' layout
+    src = tmp_path / "layout.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "fc.h"\n'
+        'int main(void){printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(fc_node), sizeof(fc_buffer), sizeof(fc_graph),'
+        ' sizeof(fc_partition), offsetof(fc_node, shape), offsetof(fc_node, infusible_args),'
+        ' offsetof(fc_partition, cost)); return 0;}\n')
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split()]
+    assert got == [ctypes.sizeof(B.fc_node), ctypes.sizeof(B.fc_buffer), ctypes.sizeof(B.fc_graph),
+                   ctypes.sizeof(B.fc_partition), B.fc_node.shape.offset, B.fc_node.infusible_args.offset,
+                   B.fc_partition.cost.offset]
+
+
+def expect(code, fn, *a, **kw):
+    with pytest.raises(fc.FcError) as e:
+        fn(*a, **kw)
+    assert e.value.name == code, str(e.value)
+    return str(e.value)
+
+
+def test_bad_graphs_are_rejected():
+    g = Graph()
+    g.add("a", "input", "f32", (8,))
+    g.add("b", "input", "f32", (9,))
+    g.add("c", "map", "f32", (8,), fn="add2", args=("a", "b"))        # zipWith of unequal sizes
+    expect("FC_E_BADGRAPH", fc.fc_plan, g)
+    g = Graph()
+    g.add("a", "input", "f32", (8,))
+    g.add("i", "input", "f32", (8,))
+    g.add("c", "gather", "f32", (8,), args=("i", "a"))                # float indices
+    expect("FC_E_BADGRAPH", fc.fc_plan, g)
+    g = Graph()
+    g.add("a", "input", "f32", (8,))
+    g.add("c", "map", "f32", (8,), fn="mul2", args=("a",))            # arity
+    expect("FC_E_BADGRAPH", fc.fc_plan, g)
+    g = Graph()
+    g.add("a", "input", "i32", (8,))
+    g.add("o", "input", "i32", (3,))
+    g.add("y", "foldseg", "i32", (3,), fn="add", args=("a", "o"))     # offsets need rows + 1 entries
+    expect("FC_E_BADGRAPH", fc.fc_plan, g)
+
+
+def test_run_checks_come_before_any_launch():
+    w = build(2, small=True)
+    g = w.graph
+    part = fc.fc_plan(g, "bytes")
+    fake = (0x10000000, 1 << 30)          # never dereferenced: every call below fails validation first
+    bufs = {n.name: fake for n in g.nodes if n.kind == "input" or n.output}
+    expect("FC_E_SCRATCH", fc.fc_run_fused, g, part, bufs, (0, 0))
+    expect("FC_E_SCRATCH", fc.fc_run_fused, g, part, bufs, (0x10000001, 1 << 30))
+    expect("FC_E_SCRATCH", fc.fc_run_fused, g, part, bufs, (0x10000000, 1024))
+    missing = dict(bufs)
+    del missing["idx"]
+    expect("FC_E_UNBOUND", fc.fc_run_fused, g, part, missing, fake)
+    small = dict(bufs, xs=(0x10000000, 16))
+    expect("FC_E_UNBOUND", fc.fc_run_fused, g, part, small, fake)
+    odd = dict(bufs, xs=(0x10000004, 1 << 30))
+    expect("FC_E_UNBOUND", fc.fc_run_fused, g, part, odd, fake)
+    bad = fc.Partition(part.pi.copy(), part.fused_away, part.order_out, part.edge_unfused)
+    bad.pi[2] = 5                          # ys after its consumer
+    expect("FC_E_ILLEGAL_PARTITION", fc.fc_run_fused, g, bad, bufs, fake)
+    # unfused needs room for every intermediate
+    expect("FC_E_SCRATCH", fc.fc_run_unfused, g, bufs, (0x10000000, B.FC_SCRATCH_CONTROL_BYTES))
+
+
+def test_unsupported_cluster_is_reported_not_executed():
+    # legal clustering, but no kernel instance: a gather of a row-fold (`simple4`)
+    g = PG.simple4()
+    part = fc.fc_plan(g, "bytes")
+    msg = expect("FC_E_UNSUPPORTED", fc.fc_cluster_kernel, g, part, 0)
+    assert "element program" in msg or "instance" in msg
+    fake = (0x10000000, 1 << 30)
+    bufs = {n.name: fake for n in g.nodes}
+    expect("FC_E_UNSUPPORTED", fc.fc_run_fused, g, part, bufs, fake)
+
+
+def test_scratch_bytes_and_kernel_names():
+    w = build(5, small=True)
+    g2, _ = fc.fc_duplicate(w.graph)
+    part = fc.fc_plan(g2, "bytes")
+    fused = fc.fc_scratch_bytes(g2, part)
+    unfused = fc.fc_scratch_bytes(w.graph, None)
+    pts = w.units
+    assert fused >= B.FC_SCRATCH_CONTROL_BYTES and unfused >= B.FC_SCRATCH_CONTROL_BYTES + 10 * 4 * pts
+    name = fc.fc_cluster_kernel(g2, part, 0)
+    assert name.startswith("store[") and "fold.max.f32" in name
+    assert fc.fc_num_edges(w.graph) == len(w.graph.edges())
+    trivial = fc.fc_partition_trivial(w.graph)
+    assert trivial.n_clusters == len([n for n in w.graph.nodes if n.kind != "input"])
+    assert not trivial.fused_away.any()
+
+
+def test_duplicate_keeps_program_meaning():
+    from oracle.interp import evaluate
+    for cfg in (1, 5):
+        w = build(cfg, small=True)
+        g2, origin = fc.fc_duplicate(w.graph)
+        assert len(g2.nodes) > len(w.graph.nodes)
+        a, b = evaluate(w.graph, w.inputs), evaluate(g2, w.inputs)
+        for o in w.graph.outputs():
+            assert np.array_equal(a[o], b[o])
+        for i, n in enumerate(g2.nodes):
+            assert n.kind == w.graph.nodes[origin[i]].kind

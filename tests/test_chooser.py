@@ -1,0 +1,353 @@
+"""fc_plan (the C++ branch and bound) against three independent references:
+
+  * the clustering outcomes the paper states for its example programs,
+  * brute-force enumeration of all set partitions (oracle/clustering.py),
+  * the literal constraint matrix of Fig. "Total ILP formulation", solved with
+    scipy's MILP solver, for the cost functions that are linear in the paper's
+    variables: (a) clusters, (b) fused edges, (c) arrays.
+
+Several partitions may tie, so costs are compared, never partitions.
+"parity unpinned": the linearisation of cost (d) "reads" (the paper describes it
+in prose only); reads is pinned by brute force on the definition alone.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import paper_2407_13585_amd as fc
+from oracle import clustering as OC
+from workloads import Graph, build
+from workloads import paper_graphs as PG
+
+COSTS = ("clusters", "fused_edges", "arrays", "reads", "reads_writes", "bytes")
+
+
+def clusters_of(part, graph):
+    groups = {}
+    for i, n in enumerate(graph.nodes):
+        if n.kind != "input":
+            groups.setdefault(int(part.pi[i]), []).append(n.name)
+    return [sorted(v) for _, v in sorted(groups.items())]
+
+
+# ------------------------------------------------------------------ outcomes the paper states
+def test_scatter_example_prefers_fusing_into_the_scatter():
+    g = PG.scatter_example()
+    legal = OC.legal_partitions(g)
+    # exactly two clusterings fuse anything: {as,bs}|{result} and {bs}|{as,result} (Fig. "Possible clusterings")
+    nontrivial = [p for p in legal if len(p) < 3]
+    assert sorted(sorted(map(sorted, p)) for p in nontrivial) == [[[1, 2], [3]], [[1, 3], [2]]]
+    for cost in ("reads_writes", "arrays", "fused_edges", "bytes"):
+        p = fc.fc_plan(g, cost)
+        assert clusters_of(p, g) == [["bs"], ["as", "result"]]
+        assert p.fused_away[1] == 1 and p.fused_away[2] == 0
+
+
+def test_single_loop_is_one_loop_without_intermediates():
+    g = PG.single_loop()
+    p = fc.fc_plan(g, "reads_writes")
+    assert p.n_clusters == 1
+    assert [int(m) for m in p.fused_away] == [0, 1, 1, 1, 1, 0]
+    assert p.cost == 3.0                      # `as` read twice (orders 0 and the gather's), result written
+    assert fc.fc_plan(g, "reads").cost == 2.0
+
+
+def test_simple_clusters():
+    for g in (PG.simple1(), PG.simple2(), PG.simple4(), PG.simple5()):
+        p = fc.fc_plan(g, "reads_writes")
+        assert p.n_clusters == 1, [n.name for n in g.nodes]
+    # simple1: [is:0, xs:l | bs:0]; `as` is produced in the gather's order and fused away
+    g = PG.simple1()
+    p = fc.fc_plan(g, "reads_writes")
+    assert p.order_out[2] >= 2 and p.fused_away[2] == 1 and p.order_out[3] == 0
+    # simple2: the inner gather is read in the outer gather's order
+    g = PG.simple2()
+    p = fc.fc_plan(g, "reads_writes")
+    assert p.order_out[3] == 3 and p.order_out[4] == 0
+    # simple5 counts two reads of xs (orders differ), one of is
+    assert fc.fc_plan(PG.simple5(), "reads").cost == 3.0
+
+
+def test_simple3_cannot_be_one_cluster():
+    g = PG.simple3()
+    assert fc.fc_plan(g, "clusters").n_clusters == 2
+    with pytest.raises(fc.FcError) as e:
+        fc.fc_partition_check(g, [0, 0, 1, 1])
+    assert e.value.name == "FC_E_ILLEGAL_PARTITION"
+    assert not OC.judge(g, [[2, 3]]).legal
+
+
+def test_scan_never_fuses_vertically_into_a_gather():
+    g = PG.scan_then_gather()
+    assert fc.fc_plan(g, "clusters").n_clusters == 2
+    with pytest.raises(fc.FcError):
+        fc.fc_partition_check(g, [0, 0, 1, 1])
+
+
+def test_scanl_and_scanr_share_a_loop_but_not_a_load():
+    g = PG.scanl_scanr(produced=False)
+    # both in one cluster is legal, and the input is still read twice
+    p = fc.fc_partition_check(g, [0, 1, 1], "reads")
+    assert p.cost == 2.0
+    # with a producer: it cannot fuse with both (orders 0 and 1 conflict)
+    g = PG.scanl_scanr(produced=True)
+    with pytest.raises(fc.FcError):
+        fc.fc_partition_check(g, [0, 1, 1, 1])
+    assert fc.fc_plan(g, "arrays").cost == 3.0
+
+
+def test_two_orders_cannot_both_fuse_with_the_producer():
+    g = PG.simple5(produced_xs=True)
+    with pytest.raises(fc.FcError):
+        fc.fc_partition_check(g, [0, 0, 1, 1, 1, 1])
+    p = fc.fc_plan(g, "reads_writes")
+    assert p.fused_away[2] == 0               # xs stays manifest without duplication
+    g2, origin = fc.fc_duplicate(g)
+    p2 = fc.fc_plan(g2, "reads_writes")
+    assert p2.n_clusters == 1 and len(g2.nodes) == len(g.nodes) + 1
+
+
+def test_greedy_counter_examples_get_the_optimal_choice():
+    g = PG.greedy_bottom_up_bad()
+    p = fc.fc_plan(g, "bytes")
+    assert clusters_of(p, g) == [["is", "large", "ys", "zs"], ["result"]]
+    assert p.fused_away[g.index()["large"]] == 1
+    g = PG.greedy_top_down_bad()
+    for cost in ("reads", "arrays", "reads_writes", "bytes"):
+        p = fc.fc_plan(g, cost)
+        assert clusters_of(p, g) == [["bs"], ["cs", "ds", "es", "result"]], cost
+
+
+def test_benchmark_pipelines():
+    want = {1: (2, 1), 2: (1, 1), 3: (1, 1), 4: (1, 1), 5: (2, 1)}
+    for cfg, (strict, dup) in want.items():
+        w = build(cfg, small=True)
+        assert fc.fc_plan(w.graph, "bytes").n_clusters == strict
+        g2, _ = fc.fc_duplicate(w.graph)
+        assert fc.fc_plan(g2, "bytes").n_clusters == dup
+    # materialise-p arm of the stencil: p stored and folded in one cluster (diagonal), stencil in the next
+    w = build(5, small=True)
+    p = fc.fc_plan(w.graph, "bytes")
+    assert clusters_of(p, w.graph)[0] == ["m", "p"]
+
+
+# ------------------------------------------------------------------ brute force
+@pytest.mark.parametrize("name", sorted(PG.ALL))
+@pytest.mark.parametrize("cost", COSTS)
+def test_plan_cost_equals_brute_force_on_paper_graphs(name, cost):
+    g = PG.ALL[name]()
+    best, _ = OC.optimum(g, cost)
+    p = fc.fc_plan(g, cost, no_split=True)
+    assert p.cost == pytest.approx(best)
+    # the returned clustering is itself legal for the brute-force judge and has that cost
+    blocks = {}
+    for i, n in enumerate(g.nodes):
+        if n.kind != "input":
+            blocks.setdefault(int(p.pi[i]), []).append(i)
+    v = OC.judge(g, list(blocks.values()))
+    assert v.legal, v.why
+    assert OC.cost(g, list(blocks.values()), v, cost) == pytest.approx(best)
+
+
+def random_graph(rng, n_ops):
+    n = 64
+    g = Graph()
+    g.add("in0", "input", "i32", (n,))
+    g.add("in1", "input", "i32", (n,))
+    names = ["in0", "in1"]
+    have_scatter_on = set()
+    for k in range(n_ops):
+        kind = rng.choice(["map1", "map1", "gen", "gather", "scanl", "scanr", "fold", "scatter"])
+        pool = [x for x in names if g[x].shape == (n,)]
+        nm = f"t{k}"
+        if kind == "map1":
+            g.add(nm, "map", "i32", (n,), fn="ident", args=(str(rng.choice(pool)),))
+        elif kind == "gen":
+            g.add(nm, "generate", "i32", (n,), fn="iota_rev")
+        elif kind == "gather":
+            g.add(nm, "gather", "i32", (n,), args=(str(rng.choice(pool)), str(rng.choice(pool))))
+        elif kind in ("scanl", "scanr"):
+            g.add(nm, kind, "i32", (n,), fn="add", args=(str(rng.choice(pool)),))
+        elif kind == "fold":
+            g.add(nm, "fold", "i32", (1,), fn="add", args=(str(rng.choice(pool)),))
+        else:
+            dest = str(rng.choice([x for x in pool if x not in have_scatter_on] or pool))
+            if dest in have_scatter_on:
+                continue
+            have_scatter_on.add(dest)
+            g.add(nm, "scatter", "i32", (n,), fn="add",
+                  args=(dest, str(rng.choice(pool)), str(rng.choice(pool))))
+        names.append(nm)
+    # results: everything without consumers is one anyway; mark one more at random
+    return g
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_plan_cost_equals_brute_force_on_random_graphs(seed):
+    rng = np.random.default_rng(1000 + seed)
+    g = random_graph(rng, int(rng.integers(3, 8)))
+    for cost in COSTS:
+        best, _ = OC.optimum(g, cost)
+        p = fc.fc_plan(g, cost, no_split=True)
+        assert p.cost == pytest.approx(best), (seed, cost, [(n.name, n.kind, n.args) for n in g.nodes])
+
+
+def test_every_legal_partition_is_accepted_and_every_illegal_one_refused():
+    for name in ("scatter_example", "simple3", "simple5", "greedy_top_down_bad", "scanl_scanr"):
+        g = PG.ALL[name]()
+        nodes = [i for i, n in enumerate(g.nodes) if n.kind != "input"]
+        for blocks in OC.set_partitions(nodes):
+            v = OC.judge(g, blocks)
+            # pi from the brute force's own sequence
+            pi = [0] * len(g.nodes)
+            if v.legal:
+                for pos, c in enumerate(v.sequence):
+                    for a in blocks[c]:
+                        pi[a] = pos + 1
+                fc.fc_partition_check(g, pi)
+            else:
+                # try every order of the blocks: none may be accepted
+                ok = False
+                for perm in itertools.permutations(range(len(blocks))):
+                    for pos, c in enumerate(perm):
+                        for a in blocks[c]:
+                            pi[a] = pos + 1
+                    try:
+                        fc.fc_partition_check(g, pi)
+                        ok = True
+                    except fc.FcError:
+                        pass
+                assert not ok, (name, blocks)
+
+
+# ------------------------------------------------------------------ the literal ILP
+def literal_ilp(graph, cost):
+    """Fig. "Total ILP formulation" as a constraint matrix; returns the optimal objective."""
+    from scipy.optimize import Bounds, LinearConstraint, milp
+    nodes = graph.nodes
+    n = len(nodes)
+    edges = graph.edges()
+    E = len(edges)
+    gathers = [i for i, nd in enumerate(nodes) if nd.kind == "gather"]
+    label = {a: 2 + k for k, a in enumerate(gathers)}
+    gcount = len(gathers)
+    # variable layout: pi[n] | x[E] | m[n] | do[n] | pimax
+    PI, X, M, DO, PMAX = 0, n, n + E, 2 * n + E, 3 * n + E
+    nv = 3 * n + E + 1
+    rows, lo, hi = [], [], []
+
+    def add(coefs, l, h):
+        r = np.zeros(nv)
+        for j, c in coefs:
+            r[j] += c
+        rows.append(r), lo.append(l), hi.append(h)
+
+    lb, ub = np.zeros(nv), np.zeros(nv)
+    ub[PI:PI + n] = n
+    ub[X:X + E] = 1
+    ub[M:M + n] = 1
+    ub[DO:DO + n] = gcount + 1
+    ub[PMAX] = n
+
+    def fusible(a, b, k):
+        return OC._fusible(graph, a, b, k)
+
+    for e, (a, b, k) in enumerate(edges):
+        add([(PI + b, 1), (PI + a, -1), (X + e, -1)], 0, np.inf)          # x <= pi_b - pi_a
+        add([(PI + b, 1), (PI + a, -1), (X + e, -n)], -np.inf, 0)         # pi_b - pi_a <= n x
+        add([(X + e, 1), (M + a, 1)], -np.inf, 1)                         # x <= 1 - m_a
+        if not fusible(a, b, k):
+            lb[X + e] = 1                                                 # x = 1 on I
+            continue
+        kind = nodes[b].kind
+        big = gcount + 2
+        if kind == "gather" and k == 1:
+            const, coef_b = label[b], 0
+        elif kind == "scanl":
+            const, coef_b = 0, 0
+        elif kind == "scanr":
+            const, coef_b = 1, 0
+        else:
+            const, coef_b = 0, 1                                          # d^i = d^o_b
+        # -(g+2) x <= do_a - di <= (g+2) x
+        add([(DO + a, 1), (DO + b, -coef_b), (X + e, big)], const, np.inf)
+        add([(DO + a, 1), (DO + b, -coef_b), (X + e, -big)], -np.inf, const)
+    for a, nd in enumerate(nodes):
+        add([(DO + a, 1), (M + a, -gcount)], -np.inf, 1)                  # do <= 1 + g m
+        add([(PI + a, 1), (PMAX, -1)], -np.inf, 0)
+        consumers = [e for e, (p, b, k) in enumerate(edges) if p == a]
+        if nd.kind == "input":
+            ub[PI + a] = 0
+            ub[M + a] = 0
+        else:
+            lb[PI + a] = 1
+            if nd.output or not consumers:
+                ub[M + a] = 0
+        if nd.kind == "scanl":
+            ub[DO + a] = 0
+        if nd.kind == "scanr":
+            lb[DO + a] = ub[DO + a] = 1
+        if nd.kind == "scatter":
+            ub[DO + a] = 1
+            d = graph.index()[nd.args[0]]
+            for (p, b, k) in edges:
+                if p == d and b != a:
+                    add([(PI + a, 1), (PI + b, -1)], 1, np.inf)           # pi_i < pi_scatter
+    c = np.zeros(nv)
+    if cost == "clusters":
+        c[PMAX] = 1
+    elif cost == "fused_edges":
+        for e, (a, b, k) in enumerate(edges):
+            if fusible(a, b, k):
+                c[X + e] = 1
+    elif cost == "arrays":
+        c[M:M + n] = -1
+    res = milp(c, constraints=LinearConstraint(np.array(rows), lo, hi), integrality=np.ones(nv),
+               bounds=Bounds(lb, ub))
+    assert res.status == 0, res.message
+    if cost == "arrays":
+        return sum(1 for nd in nodes if nd.kind != "input") + res.fun
+    return res.fun
+
+
+@pytest.mark.parametrize("name", sorted(PG.ALL))
+def test_plan_matches_the_literal_ilp_on_paper_graphs(name):
+    g = PG.ALL[name]()
+    for cost in ("clusters", "fused_edges", "arrays"):
+        assert fc.fc_plan(g, cost, no_split=True).cost == pytest.approx(literal_ilp(g, cost)), cost
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_plan_matches_the_literal_ilp_on_random_graphs(seed):
+    rng = np.random.default_rng(5000 + seed)
+    g = random_graph(rng, int(rng.integers(4, 9)))
+    for cost in ("clusters", "fused_edges", "arrays"):
+        assert fc.fc_plan(g, cost, no_split=True).cost == pytest.approx(literal_ilp(g, cost)), (seed, cost)
+
+
+def test_constraint_two_is_implied_by_constraint_five():
+    # pi_a <= pi_b follows from x <= pi_b - pi_a (section 4.1): a partition that breaks it is refused
+    g = PG.simple1()
+    with pytest.raises(fc.FcError):
+        fc.fc_partition_check(g, [0, 0, 2, 1])
+
+
+def test_split_post_pass_separates_unrelated_loops():
+    # two independent pipelines: the ILP with cost "clusters" puts them at one level; the split restores two loops
+    g = Graph()
+    g.add("a", "input", "f32", (100,))
+    g.add("b", "input", "f32", (77,))
+    g.add("ma", "map", "f32", (100,), fn="sq_plus_one", args=("a",), output=True)
+    g.add("mb", "map", "f32", (77,), fn="sq_plus_one", args=("b",), output=True)
+    raw = fc.fc_plan(g, "clusters", no_split=True)
+    assert raw.cost == 1.0 and raw.pi[2] == raw.pi[3]
+    split = fc.fc_plan(g, "clusters")
+    assert split.n_clusters == 2 and split.pi[2] != split.pi[3]
+    # consumers of one array in the same order stay together (horizontal fusion survives the split)
+    g = Graph()
+    g.add("a", "input", "f32", (100,))
+    g.add("m1", "map", "f32", (100,), fn="sq_plus_one", args=("a",), output=True)
+    g.add("m2", "map", "f32", (100,), fn="exp_neg", args=("a",), output=True)
+    p = fc.fc_plan(g, "reads")
+    assert p.n_clusters == 1 and p.cost == 1.0

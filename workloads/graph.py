@@ -52,6 +52,7 @@ class Node:
     iparam: Tuple[int, ...] = ()
     args: Tuple[str, ...] = ()
     output: bool = False          # a result of the program: must be manifest
+    infusible: Tuple[int, ...] = ()   # argument positions reached through `!`, force or foreign code
 
     def __post_init__(self):
         if self.kind not in KINDS:
