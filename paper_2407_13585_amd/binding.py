@@ -294,6 +294,29 @@ def fc_run_unfused(graph, buffers: Dict[str, object], scratch, stream: int = 0) 
     _check(lib().fc_run_unfused(g.ref(), _buffers(g, buffers), sp, sb, stream or None))
 
 
+class BoundRun:
+    """fc_run_fused / fc_run_unfused with the arguments marshalled once: for callers that run
+    one program on the same buffers many times.  partition None = fc_run_unfused."""
+
+    def __init__(self, graph, partition: Optional[Partition], buffers: Dict[str, object], scratch):
+        self._g = _cg(graph)
+        self._part = partition
+        self._cp = partition._c() if partition is not None else None
+        self._bufs = _buffers(self._g, buffers)
+        self._keep = (buffers, scratch)                 # the device memory must outlive the calls
+        self._sp, self._sb = _scratch(scratch)
+        self._lib = lib()
+
+    def __call__(self, stream: int = 0) -> None:
+        if self._cp is None:
+            rc = self._lib.fc_run_unfused(self._g.ref(), self._bufs, self._sp, self._sb, stream or None)
+        else:
+            rc = self._lib.fc_run_fused(self._g.ref(), C.byref(self._cp), self._bufs, self._sp, self._sb,
+                                        stream or None)
+        if rc != 0:
+            _check(rc)
+
+
 def fc_cluster_kernel(graph, partition: Optional[Partition], cluster: int) -> str:
     g = _cg(graph)
     cp = partition._c() if partition is not None else None

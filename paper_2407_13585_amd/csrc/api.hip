@@ -2,9 +2,13 @@
 // only; no exception leaves this file.
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cstring>
 #include <exception>
+#include <memory>
+#include <mutex>
 #include <string>
+#include <vector>
 
 #include "model.hpp"
 #include "plan.hpp"
@@ -158,16 +162,62 @@ int fc_scratch_bytes(const fc_graph *g, const fc_partition *p, size_t *bytes) {
   });
 }
 
+// Validating a program and matching its clusters to kernel instances depends only
+// on the nodes and on pi, so the result is memoised: repeated runs of one program
+// (the common case) go straight to buffer resolution and launch.
+struct Prepared {
+  std::vector<unsigned char> key;
+  std::shared_ptr<const fc::PreparedRun> run;
+};
+
 static int run_common(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs, void *scratch,
                       size_t scratch_bytes, void *hip_stream) {
-  fc::Model m;
+  static std::mutex mu;
+  static std::vector<Prepared> cache;        // most recently used first
+  if (!g || g->n < 0 || (g->n > 0 && !g->nodes)) return fail(FC_E_ARG, "null graph");
+  if (p && (p->n_nodes < g->n || (g->n && !p->pi))) return fail(FC_E_ARG, "partition does not cover the graph");
+  std::vector<unsigned char> key(sizeof(int) + (size_t)g->n * (sizeof(fc_node) + sizeof(int32_t)));
+  std::memcpy(key.data(), &g->n, sizeof(int));
+  for (int i = 0; i < g->n; ++i) {
+    // field by field: padding bytes of the caller's structs are not part of the program
+    fc_node nd;
+    std::memset(&nd, 0, sizeof(nd));
+    const fc_node &s = g->nodes[i];
+    nd.kind = s.kind; nd.dtype = s.dtype; nd.fn = s.fn; nd.nargs = s.nargs; nd.rank = s.rank;
+    nd.flags = s.flags; nd.infusible_args = s.infusible_args;
+    std::memcpy(nd.fparam, s.fparam, sizeof(nd.fparam));
+    std::memcpy(nd.iparam, s.iparam, sizeof(nd.iparam));
+    std::memcpy(nd.arg, s.arg, sizeof(nd.arg));
+    std::memcpy(nd.shape, s.shape, sizeof(nd.shape));
+    std::memcpy(key.data() + sizeof(int) + (size_t)i * sizeof(fc_node), &nd, sizeof(nd));
+    int32_t pi = p ? p->pi[i] : -1;
+    std::memcpy(key.data() + sizeof(int) + (size_t)g->n * sizeof(fc_node) + (size_t)i * sizeof(int32_t), &pi, sizeof(pi));
+  }
+  std::shared_ptr<const fc::PreparedRun> run;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    for (size_t k = 0; k < cache.size(); ++k)
+      if (cache[k].key == key) {
+        run = cache[k].run;
+        if (k) std::rotate(cache.begin(), cache.begin() + k, cache.begin() + k + 1);
+        break;
+      }
+  }
   std::string err;
-  int rc = fc::build_model(g, m, err);
-  if (rc != FC_OK) return fail(rc, err);
-  fc::Clustering c;
-  rc = load_clustering(m, p, c, err);
-  if (rc != FC_OK) return fail(rc, err);
-  rc = fc::run_clustering(m, c, bufs, scratch, scratch_bytes, static_cast<hipStream_t>(hip_stream), err);
+  if (!run) {
+    auto fresh = std::make_shared<fc::PreparedRun>();
+    int rc = fc::build_model(g, fresh->model, err);
+    if (rc != FC_OK) return fail(rc, err);
+    rc = load_clustering(fresh->model, p, fresh->clustering, err);
+    if (rc != FC_OK) return fail(rc, err);
+    rc = fc::prepare_run(*fresh, err);
+    if (rc != FC_OK) return fail(rc, err);
+    run = fresh;
+    std::lock_guard<std::mutex> lock(mu);
+    cache.insert(cache.begin(), Prepared{key, run});
+    if (cache.size() > 32) cache.pop_back();
+  }
+  int rc = fc::run_prepared(*run, bufs, scratch, scratch_bytes, static_cast<hipStream_t>(hip_stream), err);
   if (rc != FC_OK) return fail(rc, err);
   return FC_OK;
 }

@@ -54,8 +54,8 @@ template <class Op, class E> hipError_t launch_foldseg(const KArgs &a, const Lau
 }
 template <class EX, class EV, int Mode> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {
   long long tiles = std::max<long long>(1, ((long long)a.n + kScanTile - 1) / kScanTile);
-  if ((size_t)tiles > c.max_tiles) return hipErrorInvalidValue;
-  return launch_k(&scan_kernel<EX, EV, Mode>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status);
+  if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
+  return launch_k(&scan_kernel<EX, EV, Mode>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
 }
 template <class EI, class EV, class EF> hipError_t launch_scatter(const KArgs &a, const LaunchCtx &c) {
   if (a.n == 0) return hipSuccess;

@@ -159,141 +159,236 @@ __global__ __launch_bounds__(kBlock) void foldseg_kernel(const KArgs a) {
 // ------------------------------------------------------------------ single-pass scan / compaction
 // Exclusive (+) scan of the int32 stream EX in one pass over the data (section
 // 2: a scan inside a cluster must be a single pass; the chained scan is one of
-// the implementations named there).  Tile t is processed by workgroup t; each
-// tile publishes its aggregate, then looks back over the status words of its
-// predecessors until it meets an inclusive prefix (decoupled look-back).
-// Workgroups are dispatched in index order, so the lowest unfinished tile is
-// always running and can always finish; every wait is bounded all the same.
-// The scan result never reaches memory unless asked for: kOffs stores it,
-// kScatter writes EV(i) to dest[offs[i]] where EX(i) != 0 (scatter with
+// the implementations named there).  Tile t is processed by workgroup t.
+//
+// Cross-tile step.  A classic decoupled look-back chains tiles through their
+// inclusive prefixes: the front of known prefixes advances one look-back window
+// per memory round trip, and on this chip that chain, not bandwidth, set the
+// pace.  Here no tile ever waits for a prefix.  Every tile publishes its
+// aggregate as soon as its data is reduced; tiles form groups of kScanGroup; the
+// last tile of a group sums the group's aggregates and publishes the group total;
+// a tile's exclusive prefix is the sum of the totals of all earlier groups plus
+// the aggregates of the earlier tiles of its own group -- all of which depend on
+// aggregates only, so the wait is a constant number of round trips wherever the
+// tile sits.  Workgroups are dispatched in index order, so every word a tile
+// waits for belongs to a tile that is already running; every wait is bounded all
+// the same.  The scan result never reaches memory unless asked for: kOffs stores
+// it, kScatter writes EV(i) to dest[offs[i]] where EX(i) != 0 (scatter with
 // collision-free indices: plain stores, no atomics), kCount stores the total.
 constexpr int kScanBlock = 512;                       // threads per workgroup of the scan kernels
 constexpr int kScanWaves = kScanBlock / kWave;
-constexpr int kScanItems = 16;                        // per lane
-constexpr int kScanTile = kScanBlock * kScanItems;    // 8192 elements
+#ifndef FC_SCAN_ITEMS
+#define FC_SCAN_ITEMS 24
+#define FC_SCAN_WAVES 8
+#endif
+constexpr int kScanItems = FC_SCAN_ITEMS;              // per lane
+constexpr int kScanAcc = kScanItems / kVec;
+constexpr int kScanTile = kScanBlock * kScanItems;    // 12288 elements
+#ifndef FC_SCAN_GROUP
+#define FC_SCAN_GROUP 256
+#endif
+constexpr int kScanGroup = FC_SCAN_GROUP;              // tiles per group
 constexpr int kOffs = 1, kScatter = 2, kCount = 4;
 
+// number of status words a launch over n_tiles tiles uses (tile words, then group words)
+__host__ __device__ inline size_t scan_status_words(size_t n_tiles) {
+  return ((n_tiles + 15) / 16) * 16 + (n_tiles + kScanGroup - 1) / kScanGroup;
+}
+
+// sum over the workgroup of an int held by every thread; all threads receive it
+__device__ __forceinline__ int scan_block_sum(int v, int *lds) {
+  int w = wave_reduce<AddI32>(v);
+  __syncthreads();
+  if (lane_id() == 0) lds[wave_id()] = w;
+  __syncthreads();
+  int r = 0;
+#pragma unroll
+  for (int k = 0; k < kScanWaves; ++k) r += lds[k];
+  return r;
+}
+
+// Is the scanned stream a unary map of the scattered value stream (compaction by a
+// predicate on the element itself)?  Then the flags are recomputed from the values
+// when they are needed again instead of being kept in registers across the wait:
+// registers bound how many tiles are in flight, and tiles in flight bound bandwidth.
+template <class EX, class EV> struct FlagOfValue {
+  static constexpr bool value = false;
+  static __device__ __forceinline__ int apply(const KArgs &, typename EV::R) { return 0; }
+};
+template <class F, class EV> struct FlagOfValue<Map<F, EV>, EV> {
+  static constexpr bool value = true;
+  static __device__ __forceinline__ int apply(const KArgs &a, typename EV::R v) { return F::apply(a.p[0], v); }
+};
+
+// Sum of the values of `count` tagged words starting at p (16-byte aligned), this
+// thread's share.  Words are written once per launch, so a word that carries the
+// launch's tag is final whichever cache it came from: the fast path reads pairs of
+// words with ordinary cached, coalesced loads; a word that does not validate (not
+// yet published, or a stale line in this XCD's caches) is re-read at agent scope
+// until it does.  Agent-scope loads go to memory one lane at a time, so they are
+// kept for the few words that need them.
+__device__ __forceinline__ int sum_tagged_words(const unsigned long long *p, unsigned count, unsigned tag,
+                                                Control *ctl) {
+  using Pair = unsigned long long __attribute__((ext_vector_type(2)));
+  int sum = 0;
+  for (unsigned k = 2 * threadIdx.x; k < count; k += 2 * kScanBlock) {
+    Pair w = *reinterpret_cast<const Pair *>(p + k);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if (k + j >= count) break;
+      unsigned long long v = j ? w.y : w.x;
+      unsigned lo = (unsigned)v;
+      if ((lo >> 2) != tag || (lo & 3u) == 0u) v = wait_word(p + k + j, tag, ctl);
+      sum += (int)(unsigned)(v >> 32);
+    }
+  }
+  return sum;
+}
+
+// What a lane holds of one tile between loading it and writing its results.
 template <class EX, class EV, int Mode>
-__global__ __launch_bounds__(kScanBlock) void scan_kernel(const KArgs a, Control *ctl, unsigned long long *status) {
+struct ScanPayload {
+  using V = typename EV::R;
+  static constexpr bool kScat = (Mode & kScatter) != 0;
+  static constexpr bool kRecompute = kScat && FlagOfValue<EX, EV>::value;
+  int x[kRecompute ? 1 : kScanAcc][4];
+  V val[kScat ? kScanAcc : 1][4];
+
+  __device__ __forceinline__ int flag(const KArgs &a, int j, int c) const {
+    return kRecompute ? FlagOfValue<EX, EV>::apply(a, val[kScat ? j : 0][c]) : x[kRecompute ? 0 : j][c];
+  }
+  // wave-striped layout: a wave owns kWave * kScanItems consecutive elements; access j
+  // of a lane covers elements base + j*256 + lane*4 .. +3 (fully coalesced)
+  __device__ __forceinline__ void load(const KArgs &a, unsigned tile, unsigned n) {
+    const unsigned wbase = tile * kScanTile + wave_id() * (kWave * kScanItems);
+#pragma unroll
+    for (int j = 0; j < kScanAcc; ++j) {
+      unsigned i = wbase + j * (kWave * kVec) + lane_id() * kVec;
+      if (i + 3 < n) {
+        if (!kRecompute) {
+          Vec4<int> v = EX::template eval4<0>(a, (int)i);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) x[kRecompute ? 0 : j][c] = v.v[c];
+        }
+        if (kScat) {
+          Vec4<V> u = EV::template eval4<EX::kNodes>(a, (int)i);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) val[kScat ? j : 0][c] = u.v[c];
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          if (!kRecompute) x[kRecompute ? 0 : j][c] = (i + c < n) ? EX::template eval<0>(a, (int)(i + c)) : 0;
+          // past the end: a value whose flag is 0 (the scan must not count it)
+          if (kScat) val[kScat ? j : 0][c] = (i + c < n) ? EV::template eval<EX::kNodes>(a, (int)(i + c)) : V(0);
+        }
+      }
+    }
+  }
+};
+
+template <class EX, class EV, int Mode>
+__global__ __launch_bounds__(kScanBlock, FC_SCAN_WAVES) void scan_kernel(const KArgs a, Control *ctl, unsigned long long *status,
+                                                             unsigned n_tiles) {
   __shared__ int lds_wave[kScanWaves];
-  __shared__ int lds_part[kScanWaves];
-  __shared__ int lds_found[kScanWaves];
+  __shared__ int lds_sum[kScanWaves];
+  using P = ScanPayload<EX, EV, Mode>;
   using V = typename EV::R;
   const unsigned n = (unsigned)a.n;
-  const unsigned n_tiles = gridDim.x;
-  const unsigned tile = blockIdx.x;
   const int lane = lane_id(), wave = wave_id();
   const unsigned epoch = load_agent(&ctl->epoch);
   const unsigned tag = tag_of_epoch(epoch);
+  unsigned long long *group_word = status + ((n_tiles + 15) / 16) * 16;
 
-  // wave-striped layout: wave w owns 1024 consecutive elements; access j of a
-  // lane covers elements base + j*256 + lane*4 .. +3 (fully coalesced)
-  const unsigned wbase = tile * kScanTile + wave * (kWave * kScanItems);
-  int x[4][4];
-  V val[4][4];
-  int s[4];
+  P cur;
+  const unsigned tile = blockIdx.x;
+  cur.load(a, tile, n);
+  {
+
+    const unsigned wbase = tile * kScanTile + wave * (kWave * kScanItems);
+    int s[kScanAcc];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
-    if (i + 3 < n) {
-      Vec4<int> v = EX::template eval4<0>(a, (int)i);
+    for (int j = 0; j < kScanAcc; ++j) {
+      unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
+      int f[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) x[j][c] = v.v[c];
+      for (int c = 0; c < 4; ++c) f[c] = (i + c < n) ? cur.flag(a, j, c) : 0;
+      s[j] = (f[0] + f[1]) + (f[2] + f[3]);
+    }
+    // exclusive prefix of each access inside the wave
+    int excl[kScanAcc];
+    int carry = 0;
+#pragma unroll
+    for (int j = 0; j < kScanAcc; ++j) {
+      int inc = wave_scan_inclusive<AddI32>(s[j]);
+      excl[j] = carry + inc - s[j];
+      carry += __builtin_amdgcn_readlane(inc, 63);
+    }
+    if (lane == 0) lds_wave[wave] = carry;
+    __syncthreads();
+    int wave_excl = 0, aggregate = 0;
+#pragma unroll
+    for (int k = 0; k < kScanWaves; ++k) {
+      int t = lds_wave[k];
+      if (k < wave) wave_excl += t;
+      aggregate += t;
+    }
+
+    if (threadIdx.x == 0) store_agent64(&status[tile], pack_word((unsigned)aggregate, tag, 1u));
+    const unsigned group = tile / kScanGroup, first = group * kScanGroup;
+    const unsigned n_mine = tile - first;          // earlier tiles of my group
+    // Gate: one lane waits for the word that is published last among those this tile
+    // needs (its immediate predecessor's, or the previous group's total).  Words
+    // become valid nearly in tile order, so after the gate the wide reads below
+    // succeed at once; hundreds of lanes spinning on fresh words would flood the
+    // few memory channels that hold them and slow every stream of the kernel.
+    if (threadIdx.x == 0 && tile > 0)
+      (void)wait_word(n_mine > 0 ? &status[tile - 1] : &group_word[group - 1], tag, ctl);
+    __syncthreads();
+    // aggregates of the earlier tiles of my group
+    int sum_group = sum_tagged_words(status + first, n_mine, tag, ctl);
+    if (n_mine == kScanGroup - 1) {
+      // last tile of a full group: publish the group total before waiting for anything else
+      sum_group = scan_block_sum(sum_group, lds_sum);
+      if (threadIdx.x == 0) store_agent64(&group_word[group], pack_word((unsigned)(sum_group + aggregate), tag, 1u));
+      if (threadIdx.x != 0) sum_group = 0;         // counted once in the sum below
+    }
+    // totals of all earlier groups
+    int sum_before = sum_group + sum_tagged_words(group_word, group, tag, ctl);
+    const int tile_excl = scan_block_sum(sum_before, lds_sum);
+
+    if (tile == n_tiles - 1 && threadIdx.x == 0) {
+      if (Mode & kCount) *static_cast<int *>(a.out[2]) = tile_excl + aggregate;
+      // the last tile has read a word of every other tile or of its group, so all of
+      // them have taken their tag: the next launch may use the next one
+      store_agent(&ctl->epoch, epoch + 1u);
+    }
+
+#pragma unroll
+    for (int j = 0; j < kScanAcc; ++j) {
+      unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
+      int f[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) f[c] = (i + c < n) ? cur.flag(a, j, c) : 0;
+      int o[4];
+      o[0] = tile_excl + wave_excl + excl[j];
+      o[1] = o[0] + f[0];
+      o[2] = o[1] + f[1];
+      o[3] = o[2] + f[2];
+      if (Mode & kOffs) {
+        int *offs = static_cast<int *>(a.out[1]);
+        if (i + 3 < n) {
+          store4(offs + i, Vec4<int>{{o[0], o[1], o[2], o[3]}});
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) if (i + c < n) offs[i + c] = o[c];
+        }
+      }
       if (Mode & kScatter) {
-        Vec4<V> u = EV::template eval4<EX::kNodes>(a, (int)i);
+        V *dest = static_cast<V *>(a.out[0]);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) val[j][c] = u.v[c];
+        for (int c = 0; c < 4; ++c) if (f[c] != 0) dest[o[c]] = cur.val[P::kScat ? j : 0][c];
       }
-    } else {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        x[j][c] = (i + c < n) ? EX::template eval<0>(a, (int)(i + c)) : 0;
-        if (Mode & kScatter) val[j][c] = (i + c < n) ? EV::template eval<EX::kNodes>(a, (int)(i + c)) : V(0);
-      }
-    }
-    s[j] = (x[j][0] + x[j][1]) + (x[j][2] + x[j][3]);
-  }
-  // exclusive prefix of each access inside the wave
-  int excl[4];
-  int carry = 0;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int inc = wave_scan_inclusive<AddI32>(s[j]);
-    excl[j] = carry + inc - s[j];
-    carry += __builtin_amdgcn_readlane(inc, 63);
-  }
-  if (lane == 0) lds_wave[wave] = carry;
-  __syncthreads();
-  int wave_excl = 0, aggregate = 0;
-#pragma unroll
-  for (int k = 0; k < kScanWaves; ++k) {
-    int t = lds_wave[k];
-    if (k < wave) wave_excl += t;
-    aggregate += t;
-  }
-
-  // publish the aggregate, then look back: thread t inspects tile - 1 - t, so one
-  // round covers the kScanBlock nearest predecessors.  The window has to be wide:
-  // the front of known prefixes advances by at most one window per memory round
-  // trip, and it must outrun the rate at which tiles stream through the chip.
-  if (threadIdx.x == 0) store_agent64(&status[tile], pack_word((unsigned)aggregate, tag, tile == 0 ? 2u : 1u));
-  int prefix = 0;
-  if (tile > 0) {
-    int pred = (int)tile - 1 - (int)threadIdx.x;
-    while (true) {
-      int value = 0;
-      unsigned state = 2u;                 // before the first tile: prefix 0
-      if (pred >= 0) {
-        unsigned long long w = wait_word(&status[pred], tag, ctl);
-        value = (int)(unsigned)(w >> 32);
-        state = w ? ((unsigned)w & 3u) : 2u;   // a wait that gave up ends the look-back
-      }
-      unsigned long long has_prefix = __ballot(state == 2u);
-      int first = has_prefix ? (int)__builtin_ctzll(has_prefix) : kWave;
-      int part = wave_reduce<AddI32>(lane <= first ? value : 0);
-      if (lane == 0) { lds_part[wave] = part; lds_found[wave] = has_prefix != 0; }
-      __syncthreads();
-      bool found = false;
-#pragma unroll
-      for (int k = 0; k < kScanWaves; ++k) {
-        if (!found) { prefix += lds_part[k]; found = lds_found[k] != 0; }
-      }
-      __syncthreads();
-      if (found) break;
-      pred -= kScanBlock;
-    }
-    if (threadIdx.x == 0) store_agent64(&status[tile], pack_word((unsigned)(prefix + aggregate), tag, 2u));
-  }
-  const int tile_excl = prefix;
-
-  if (tile == n_tiles - 1 && threadIdx.x == 0) {
-    if (Mode & kCount) *static_cast<int *>(a.out[2]) = tile_excl + aggregate;
-    // the last tile has seen a prefix that covers every other tile, so all of them
-    // have taken their tag: the next launch may use the next one
-    store_agent(&ctl->epoch, epoch + 1u);
-  }
-
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
-    int o[4];
-    o[0] = tile_excl + wave_excl + excl[j];
-    o[1] = o[0] + x[j][0];
-    o[2] = o[1] + x[j][1];
-    o[3] = o[2] + x[j][2];
-    if (Mode & kOffs) {
-      int *offs = static_cast<int *>(a.out[1]);
-      if (i + 3 < n) {
-        store4(offs + i, Vec4<int>{{o[0], o[1], o[2], o[3]}});
-      } else {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) if (i + c < n) offs[i + c] = o[c];
-      }
-    }
-    if (Mode & kScatter) {
-      V *dest = static_cast<V *>(a.out[0]);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) if (i + c < n && x[j][c] != 0) dest[o[c]] = val[j][c];
     }
   }
 }

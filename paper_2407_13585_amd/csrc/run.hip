@@ -231,8 +231,23 @@ size_t scratch_bytes_for(const Model &m, const Clustering &c) {
   return total;
 }
 
-int run_clustering(const Model &m, const Clustering &c, const fc_buffer *bufs, void *scratch, size_t scratch_bytes,
-                   hipStream_t stream, std::string &err) {
+int prepare_run(PreparedRun &r, std::string &err) {
+  // plan every cluster before the first launch, so that an unsupported cluster
+  // leaves no partial results behind
+  r.launches.clear();
+  for (const auto &members : clusters_of(r.model, r.clustering)) {
+    ClusterLaunch cl;
+    int rc = plan_cluster(r.model, r.clustering, members, cl, err);
+    if (rc != FC_OK) return rc;
+    r.launches.push_back(cl);
+  }
+  return FC_OK;
+}
+
+int run_prepared(const PreparedRun &r, const fc_buffer *bufs, void *scratch, size_t scratch_bytes, hipStream_t stream,
+                 std::string &err) {
+  const Model &m = r.model;
+  const Clustering &c = r.clustering;
   if (!bufs) { err = "null buffer table"; return FC_E_ARG; }
   if (!scratch || ((uintptr_t)scratch & 255u) || scratch_bytes < FC_SCRATCH_CONTROL_BYTES) {
     err = "scratch must be 256-byte aligned and at least FC_SCRATCH_CONTROL_BYTES";
@@ -274,16 +289,7 @@ int run_clustering(const Model &m, const Clustering &c, const fc_buffer *bufs, v
   ctx.status = reinterpret_cast<unsigned long long *>(static_cast<char *>(scratch) + kStatusOffset);
   ctx.max_tiles = kMaxTiles;
 
-  // plan every cluster before the first launch, so that an unsupported cluster
-  // leaves no partial results behind
-  std::vector<ClusterLaunch> launches;
-  for (const auto &members : clusters_of(m, c)) {
-    ClusterLaunch cl;
-    int rc = plan_cluster(m, c, members, cl, err);
-    if (rc != FC_OK) return rc;
-    launches.push_back(cl);
-  }
-  for (ClusterLaunch &cl : launches) {
+  for (ClusterLaunch cl : r.launches) {
     if (cl.kind == ClusterLaunch::Alias) {
       if (bufs[cl.alias_node].ptr && bufs[cl.alias_node].ptr != ptr[cl.alias_of]) {
         hipError_t e = hipMemcpyAsync(bufs[cl.alias_node].ptr, ptr[cl.alias_of], (size_t)m.bytes(cl.alias_node),

@@ -34,7 +34,17 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
 
 size_t scratch_bytes_for(const Model &m, const Clustering &c);
 
-int run_clustering(const Model &m, const Clustering &c, const fc_buffer *bufs, void *scratch, size_t scratch_bytes,
-                   hipStream_t stream, std::string &err);
+// A validated program with every cluster matched to its kernel instance; what
+// remains per call is binding buffers and launching.
+struct PreparedRun {
+  Model model;
+  Clustering clustering;
+  std::vector<ClusterLaunch> launches;
+};
+
+int prepare_run(PreparedRun &r, std::string &err);
+
+int run_prepared(const PreparedRun &r, const fc_buffer *bufs, void *scratch, size_t scratch_bytes, hipStream_t stream,
+                 std::string &err);
 
 }  // namespace fc

@@ -53,13 +53,10 @@ class DeviceProgram:
                 self.buffers[n.name] = self.buffers[by_name[n.args[0]].name]
         nbytes = B.fc_scratch_bytes(self.cg, partition)
         self.scratch = torch.zeros((nbytes + 3) // 4, dtype=torch.int32, device=self.device)
+        self._bound = B.BoundRun(self.cg, partition, self.buffers, self.scratch)
 
     def run(self, stream: Optional[torch.cuda.Stream] = None) -> None:
-        s = (stream or torch.cuda.current_stream(self.device)).cuda_stream
-        if self.partition is None:
-            B.fc_run_unfused(self.cg, self.buffers, self.scratch, s)
-        else:
-            B.fc_run_fused(self.cg, self.partition, self.buffers, self.scratch, s)
+        self._bound((stream or torch.cuda.current_stream(self.device)).cuda_stream)
 
     def fetch(self, name: str) -> np.ndarray:
         n = self.graph[name]
