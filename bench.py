@@ -31,6 +31,69 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def source_hash() -> str:
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2407_13585_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per launch from the committed counter summary, or None when the kernel
+    sources have changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+    if not os.path.exists(path):
+        return None
+    table, sha = {}, None
+    for line in open(path):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        if t[0] == "source_sha256":
+            sha = t[1]
+        else:
+            table[t[0]] = int(t[2]) + int(t[4])
+    if sha != source_hash():
+        return None
+    return table.get(workload)
+
+
+def gather_ceiling(fc, DeviceProgram, np, torch):
+    """Rate of bare random 4-byte gathers (index stream + gather + fold, no arithmetic) for three
+    table sizes: the ceiling the memory system puts on the gather pipelines."""
+    from workloads import Graph
+    out = {}
+    for logn in (20, 22, 24):
+        n = 1 << logn
+        rng = np.random.default_rng(logn)
+        g = Graph()
+        g.add("idx", "input", "i32", (n,))
+        g.add("xs", "input", "f32", (n,))
+        g.add("zs", "gather", "f32", (n,), args=("idx", "xs"))
+        g.add("r", "fold", "f32", (1,), fn="add", args=("zs",), output=True)
+        part = fc.fc_plan(g, "bytes")
+        sets = max(2, (1 << 30) // (8 * n))
+        progs = [DeviceProgram(g, {"idx": rng.permutation(n).astype(np.int32), "xs": np.ones(n, np.float32)}, part)
+                 for _ in range(min(sets, 8))]
+        for p in progs:
+            p.run()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 16
+        a.record()
+        for r in range(reps):
+            progs[r % len(progs)].run()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) / reps * 1e3
+        out[f"table_2^{logn}_f32"] = {"us": round(us, 2), "Ggather/s": round(n / us / 1e3, 2), "kernel": progs[0].kernels()[0]}
+        log(f"bare gather, table 2^{logn} floats: {us:8.1f} us  {n / us / 1e3:6.1f} G gathers/s")
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,6 +103,8 @@ def main() -> int:
     ap.add_argument("--small", action="store_true", help="small sizes (debugging only; not a valid measurement)")
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--gather-ceiling", action="store_true",
+                    help="also measure the rate of bare random gathers (no arithmetic) for three table sizes")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain copy kernel of known size (256 MiB in, 256 MiB out): the reference "
                          "that hardware counter readings are scaled by")
@@ -86,6 +151,8 @@ def main() -> int:
             cal.run()
         torch.cuda.synchronize()
         log(f"calibration copy: {cal.kernels()} moves {4 * n} B in and {4 * n} B out per launch")
+
+    ceiling = gather_ceiling(fc, DeviceProgram, np, torch) if args.gather_ceiling else None
 
     def one_step(s, events=None):
         for k, c in enumerate(cfgs):
@@ -157,7 +224,7 @@ def main() -> int:
             f"{w.unit_name}/s": round(w.units / (gpu_ms[c] * 1e-3), 1), "lb_bytes": w.lb_bytes,
             "unfused_ms": round(unf_ms[c], 5) if c in unf_ms else None,
             "speedup_vs_unfused": round(unf_ms[c] / gpu_ms[c], 2) if c in unf_ms else None,
-            "kernels": kernels[c],
+            "kernels": kernels[c], "traffic": measured_traffic(w.name),
         }
         log(f"cfg{c}: {gpu_ms[c] * 1e3:9.1f} us  {gbs:8.1f} GB/s  {100 * gbs / HBM_PEAK_GBS:5.1f}% of HBM peak  "
             + (f"unfused {unf_ms[c] * 1e3:10.1f} us  speedup {unf_ms[c] / gpu_ms[c]:6.2f}x" if c in unf_ms else ""))
@@ -178,9 +245,12 @@ def main() -> int:
         "per_config": per,
         "roofline": {"bound": "hbm", "kernel": kernels[dom][0], "workload": work[dom].name,
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(work[dom].name),
+                     "algorithmic_bytes": work[dom].lb_bytes},
         "cpu_baseline": cpu,
     }
+    if ceiling is not None:
+        out["gather_ceiling"] = ceiling
     print(json.dumps(out), flush=True)
     return 0
 

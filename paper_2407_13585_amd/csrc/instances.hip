@@ -186,6 +186,7 @@ std::vector<Instance> build_registry() {
   r.push_back(store_<Gather<Gen<GenIotaRev>, F0>>());         // reverse / backpermute
   r.push_back(store_<Map<FnSqPlusOne, Gather<I0, Map<FnSinXMulX, F1>>>>());
   r.push_back(fold_<AddF32, Map<FnSqPlusOne, F0>>());
+  r.push_back(fold_<AddF32, Gather<I0, F1>>());               // bare gather + fold: the gather-rate ceiling
   r.push_back(store_<Map<FnMul2, F0, Gather<I1, F2>>>());
   return r;
 }
