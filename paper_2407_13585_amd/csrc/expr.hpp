@@ -162,6 +162,15 @@ struct Gen {
   static void sig(std::string &s) { s += "gen" + std::to_string(G::kFn); }
 };
 
+// the constant 1: stands for the flag of a scatter that has none (takes no parameter slot)
+struct AlwaysOne {
+  using R = int;
+  static constexpr int kNodes = 0;
+  template <int Base> static __device__ __forceinline__ int eval(const KArgs &, int) { return 1; }
+  template <int Base> static __device__ __forceinline__ Vec4<int> eval4(const KArgs &, int) { return Vec4<int>{{1, 1, 1, 1}}; }
+  static void sig(std::string &s) { s += "1"; }
+};
+
 // EI yields the index, ES is evaluated there
 template <class EI, class ES>
 struct Gather {

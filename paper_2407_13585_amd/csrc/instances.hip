@@ -52,14 +52,25 @@ template <class Op, class E> hipError_t launch_foldseg(const KArgs &a, const Lau
   if (a.aux == 0) return hipSuccess;
   return launch_k(&foldseg_kernel<Op, E>, grid_for(a.aux, kBlock / 16, kMaxGrid * 8), c.stream, a);
 }
-template <class EX, class EV, int Mode> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {
+template <class EX, class EV, int Mode, bool Reverse = false> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {
   long long tiles = std::max<long long>(1, ((long long)a.n + kScanTile - 1) / kScanTile);
   if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
-  return launch_k(&scan_kernel<EX, EV, Mode>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
+  return launch_k(&scan_kernel<EX, EV, Mode, Reverse>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
 }
-template <class EI, class EV, class EF> hipError_t launch_scatter(const KArgs &a, const LaunchCtx &c) {
+template <class EI, class EV, class EF, bool Add> hipError_t launch_scatter(const KArgs &a, const LaunchCtx &c) {
   if (a.n == 0) return hipSuccess;
-  return launch_k(&scatter_kernel<EI, EV, EF>, grid_for(a.n, kTile, kMaxGrid), c.stream, a);
+  return launch_k(&scatter_kernel<EI, EV, EF, Add>, grid_for(a.n, kTile, kMaxGrid), c.stream, a);
+}
+template <class E1, class E2> hipError_t launch_store2(const KArgs &a, const LaunchCtx &c) {
+  if (a.n == 0) return hipSuccess;
+  return launch_k(&store2_kernel<E1, E2>, grid_for(a.n, kTile, kMaxGrid), c.stream, a);
+}
+// lanes per row by row length: a 16-lane DPP row, a wave, or the whole workgroup
+template <class Op1, class Op2, class E, class RI> hipError_t launch_rowfold(const KArgs &a, const LaunchCtx &c) {
+  if (a.aux == 0) return hipSuccess;
+  if (a.w <= 64) return launch_k(&rowfold_kernel<Op1, Op2, E, RI, 16>, grid_for(a.aux, kBlock / 16, kMaxGrid * 4), c.stream, a);
+  if (a.w <= 2048) return launch_k(&rowfold_kernel<Op1, Op2, E, RI, kWave>, grid_for(a.aux, kBlock / kWave, kMaxGrid * 4), c.stream, a);
+  return launch_k(&rowfold_kernel<Op1, Op2, E, RI, kBlock>, grid_for(a.aux, 1, kMaxGrid * 4), c.stream, a);
 }
 
 // ---- signatures -----------------------------------------------------------
@@ -74,15 +85,26 @@ template <class ES, class Op, class EF> Instance store_fold_() {
 template <class Op, class E> Instance foldseg_() {
   return {std::string("foldseg.") + Op::name() + "[" + sig_of<E>() + "]", &launch_foldseg<Op, E>};
 }
-template <class EX, class EV, int Mode> Instance scan_() {
-  std::string s = "scan[" + sig_of<EX>() + "]";
+template <class EX, class EV, int Mode, bool Reverse = false> Instance scan_() {
+  std::string s = std::string(Reverse ? "scanr[" : "scan[") + sig_of<EX>() + "]";
   if (Mode & kOffs) s += "+offs";
   if (Mode & kScatter) s += "+scatter[" + sig_of<EV>() + "]";
   if (Mode & kCount) s += "+count";
-  return {s, &launch_scan<EX, EV, Mode>};
+  return {s, &launch_scan<EX, EV, Mode, Reverse>};
 }
-template <class EI, class EV, class EF> Instance scatter_() {
-  return {"scatter[" + sig_of<EI>() + "," + sig_of<EV>() + "," + sig_of<EF>() + "]", &launch_scatter<EI, EV, EF>};
+template <class EI, class EV, class EF, bool Add = false> Instance scatter_() {
+  return {std::string(Add ? "scatter.add[" : "scatter[") + sig_of<EI>() + "," + sig_of<EV>() + "," + sig_of<EF>() + "]",
+          &launch_scatter<EI, EV, EF, Add>};
+}
+template <class E1, class E2> Instance store2_() {
+  return {"store[" + sig_of<E1>() + "]+store[" + sig_of<E2>() + "]", &launch_store2<E1, E2>};
+}
+template <class Op1, class Op2, class E, class RI = NoRowIndex> Instance rowfold_() {
+  std::string s = std::string("rowfold.") + Op1::name();
+  if (!std::is_same<Op2, NoSecondOp>::value) s += std::string("+") + Op2::name();
+  s += "[" + sig_of<E>() + "]";
+  if (!std::is_same<RI, NoRowIndex>::value) s += "@gather(" + sig_of<RI>() + ")";
+  return {s, &launch_rowfold<Op1, Op2, E, RI>};
 }
 
 using F0 = In<0, float>;
@@ -165,6 +187,7 @@ std::vector<Instance> build_registry() {
   r.push_back(foldseg_<MaxF32, F0>());
   r.push_back(foldseg_<AddI32, I0>());
   r.push_back(scan_<I0, I0, kOffs>());
+  r.push_back(scan_<I0, I0, kOffs, true>());                  // scanr: the same pass over the mirrored index space
   r.push_back(scatter_<I0, I1, I2>());
   r.push_back(scatter_<I0, F1, I2>());
   // ---- fused clusters ----
@@ -187,6 +210,34 @@ std::vector<Instance> build_registry() {
   r.push_back(store_<Map<FnSqPlusOne, Gather<I0, Map<FnSinXMulX, F1>>>>());
   r.push_back(fold_<AddF32, Map<FnSqPlusOne, F0>>());
   r.push_back(fold_<AddF32, Gather<I0, F1>>());               // bare gather + fold: the gather-rate ceiling
+  // ---- example programs of the paper ----
+  // `singleLoop`: one loop, no intermediates, the input read in two orders
+  r.push_back(store_<Map<FnAdd3, Gather<Gen<GenIotaRev>, F0>, Map<FnAffine, F0>, Map<FnSqPlusOne, Map<FnAffine, F0>>>>());
+  // `greedyTopDownBad`: cs fused vertically into es and the fold; bs read twice from memory
+  r.push_back(fold_<AddF32, Map<FnAdd2, Map<FnAffine, F0>, Map<FnIdentF, F0>>>());
+  // `simple5`: one array read in order 0 and in a gather's order inside one loop
+  r.push_back(store_<Map<FnMul2, Map<FnSqPlusOne, F0>, Gather<I1, F0>>>());
+  // diagonal fusion: a map stored and forwarded to the next map, which is stored too
+  r.push_back(store2_<Map<FnAffine, F0>, Map<FnAffine, Map<FnAffine, F0>>>());
+  r.push_back(store2_<Map<FnIdentI, I0>, Map<FnIdentI, I0>>());
+  // `scatterExample`: combining scatter with its source tuple fused in
+  r.push_back(scatter_<Map<FnIdentI, I0>, Map<FnIdentI, I0>, AlwaysOne, true>());
+  r.push_back(scatter_<I0, I1, AlwaysOne, true>());
+  r.push_back(scatter_<I0, I0, AlwaysOne, true>());
+  r.push_back(scatter_<I0, I1, I2, true>());
+  r.push_back(scatter_<I0, I1, AlwaysOne>());
+  r.push_back(scatter_<I0, F1, AlwaysOne>());
+  // row folds: alone (the unfused arm), under a gather (`simple4`), and two folds that
+  // contract a gathered 2-D array (`greedyBottomUpBad`)
+  r.push_back(rowfold_<AddF32, NoSecondOp, F0>());
+  r.push_back(rowfold_<MulF32, NoSecondOp, F0>());
+  r.push_back(rowfold_<MaxF32, NoSecondOp, F0>());
+  r.push_back(rowfold_<AddI32, NoSecondOp, I0>());
+  r.push_back(rowfold_<AddF32, NoSecondOp, F0, I1>());
+  r.push_back(rowfold_<AddF32, MulF32, Gather<Gen<GenRowOf2D>, F0>>());
+  r.push_back(rowfold_<AddF32, NoSecondOp, Gather<Gen<GenRowOf2D>, F0>>());
+  r.push_back(rowfold_<MulF32, NoSecondOp, Gather<Gen<GenRowOf2D>, F0>>());
+  r.push_back(store_<Gather<Gen<GenRowOf2D>, F0>>());
   r.push_back(store_<Map<FnMul2, F0, Gather<I1, F2>>>());
   return r;
 }

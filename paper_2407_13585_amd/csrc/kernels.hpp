@@ -6,6 +6,7 @@
 #pragma once
 
 #include <tuple>
+#include <type_traits>
 #include <utility>
 
 #include "expr.hpp"
@@ -43,6 +44,34 @@ __global__ __launch_bounds__(kBlock) void store_kernel(const KArgs a) {
     }
   }
   if (blockIdx.x == 0 && threadIdx.x < n - n4) out[n4 + threadIdx.x] = E::template eval<0>(a, (int)(n4 + threadIdx.x));
+}
+
+// two arrays written in one pass (diagonal fusion: a value is forwarded to the next
+// combinator in registers and stored as well; section 1, Fig. "Three types of fusion")
+template <class E1, class E2>
+__global__ __launch_bounds__(kBlock) void store2_kernel(const KArgs a) {
+  using T1 = typename E1::R;
+  using T2 = typename E2::R;
+  T1 *out1 = static_cast<T1 *>(a.out[0]);
+  T2 *out2 = static_cast<T2 *>(a.out[1]);
+  const unsigned n = (unsigned)a.n, n4 = n & ~3u;
+  for (unsigned base = blockIdx.x * kTile; base < n4; base += gridDim.x * kTile) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
+      if (i < n4) {
+        Vec4<T1> v1 = E1::template eval4<0>(a, (int)i);
+        Vec4<T2> v2 = E2::template eval4<E1::kNodes>(a, (int)i);
+        store4(out1 + i, v1);
+        store4(out2 + i, v2);
+      }
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x < n - n4) {
+    int i = (int)(n4 + threadIdx.x);
+    out1[i] = E1::template eval<0>(a, i);
+    out2[i] = E2::template eval<E1::kNodes>(a, i);
+  }
 }
 
 // ------------------------------------------------------------------ fold (and store + fold)
@@ -177,17 +206,10 @@ __global__ __launch_bounds__(kBlock) void foldseg_kernel(const KArgs a) {
 // collision-free indices: plain stores, no atomics), kCount stores the total.
 constexpr int kScanBlock = 512;                       // threads per workgroup of the scan kernels
 constexpr int kScanWaves = kScanBlock / kWave;
-#ifndef FC_SCAN_ITEMS
-#define FC_SCAN_ITEMS 24
-#define FC_SCAN_WAVES 8
-#endif
-constexpr int kScanItems = FC_SCAN_ITEMS;              // per lane
+constexpr int kScanItems = 24;                        // per lane: six 128-bit accesses (measured best of 16..32)
 constexpr int kScanAcc = kScanItems / kVec;
 constexpr int kScanTile = kScanBlock * kScanItems;    // 12288 elements
-#ifndef FC_SCAN_GROUP
-#define FC_SCAN_GROUP 256
-#endif
-constexpr int kScanGroup = FC_SCAN_GROUP;              // tiles per group
+constexpr int kScanGroup = 256;                       // tiles per group
 constexpr int kOffs = 1, kScatter = 2, kCount = 4;
 
 // number of status words a launch over n_tiles tiles uses (tile words, then group words)
@@ -246,7 +268,7 @@ __device__ __forceinline__ int sum_tagged_words(const unsigned long long *p, uns
 }
 
 // What a lane holds of one tile between loading it and writing its results.
-template <class EX, class EV, int Mode>
+template <class EX, class EV, int Mode, bool Reverse>
 struct ScanPayload {
   using V = typename EV::R;
   static constexpr bool kScat = (Mode & kScatter) != 0;
@@ -264,7 +286,7 @@ struct ScanPayload {
 #pragma unroll
     for (int j = 0; j < kScanAcc; ++j) {
       unsigned i = wbase + j * (kWave * kVec) + lane_id() * kVec;
-      if (i + 3 < n) {
+      if (!Reverse && i + 3 < n) {
         if (!kRecompute) {
           Vec4<int> v = EX::template eval4<0>(a, (int)i);
 #pragma unroll
@@ -278,21 +300,22 @@ struct ScanPayload {
       } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          if (!kRecompute) x[kRecompute ? 0 : j][c] = (i + c < n) ? EX::template eval<0>(a, (int)(i + c)) : 0;
-          // past the end: a value whose flag is 0 (the scan must not count it)
-          if (kScat) val[kScat ? j : 0][c] = (i + c < n) ? EV::template eval<EX::kNodes>(a, (int)(i + c)) : V(0);
+          // scanr walks the array from its end: position i + c of the pass is element n - 1 - (i + c)
+          const int e = Reverse ? (int)(n - 1 - (i + c)) : (int)(i + c);
+          if (!kRecompute) x[kRecompute ? 0 : j][c] = (i + c < n) ? EX::template eval<0>(a, e) : 0;
+          if (kScat) val[kScat ? j : 0][c] = (i + c < n) ? EV::template eval<EX::kNodes>(a, e) : V(0);
         }
       }
     }
   }
 };
 
-template <class EX, class EV, int Mode>
-__global__ __launch_bounds__(kScanBlock, FC_SCAN_WAVES) void scan_kernel(const KArgs a, Control *ctl, unsigned long long *status,
+template <class EX, class EV, int Mode, bool Reverse>
+__global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Control *ctl, unsigned long long *status,
                                                              unsigned n_tiles) {
   __shared__ int lds_wave[kScanWaves];
   __shared__ int lds_sum[kScanWaves];
-  using P = ScanPayload<EX, EV, Mode>;
+  using P = ScanPayload<EX, EV, Mode, Reverse>;
   using V = typename EV::R;
   const unsigned n = (unsigned)a.n;
   const int lane = lane_id(), wave = wave_id();
@@ -377,11 +400,11 @@ __global__ __launch_bounds__(kScanBlock, FC_SCAN_WAVES) void scan_kernel(const K
       o[3] = o[2] + f[2];
       if (Mode & kOffs) {
         int *offs = static_cast<int *>(a.out[1]);
-        if (i + 3 < n) {
+        if (!Reverse && i + 3 < n) {
           store4(offs + i, Vec4<int>{{o[0], o[1], o[2], o[3]}});
         } else {
 #pragma unroll
-          for (int c = 0; c < 4; ++c) if (i + c < n) offs[i + c] = o[c];
+          for (int c = 0; c < 4; ++c) if (i + c < n) offs[Reverse ? n - 1 - (i + c) : i + c] = o[c];
         }
       }
       if (Mode & kScatter) {
@@ -394,9 +417,14 @@ __global__ __launch_bounds__(kScanBlock, FC_SCAN_WAVES) void scan_kernel(const K
 }
 
 // ------------------------------------------------------------------ scatter (elementwise)
-// for every i with EF(i) != 0: dest[EI(i)] = EV(i).  Indices are taken to be
-// distinct (overwrite scatter), so plain stores suffice.
-template <class EI, class EV, class EF>
+// for every i with EF(i) != 0: dest[EI(i)] = f(dest[EI(i)], EV(i)).  Overwrite: the
+// indices are taken to be distinct, so plain stores suffice (no atomics).  Add:
+// colliding indices combine; integer atomics make the result exact in any order.
+template <bool Add, class T> __device__ __forceinline__ void scatter_one(T *dest, int j, T v) {
+  if (Add) atomicAdd(dest + j, v); else dest[j] = v;
+}
+
+template <class EI, class EV, class EF, bool Add>
 __global__ __launch_bounds__(kBlock) void scatter_kernel(const KArgs a) {
   using V = typename EV::R;
   V *dest = static_cast<V *>(a.out[0]);
@@ -410,13 +438,80 @@ __global__ __launch_bounds__(kBlock) void scatter_kernel(const KArgs a) {
         Vec4<int> j = EI::template eval4<0>(a, (int)i);
         Vec4<V> v = EV::template eval4<EI::kNodes>(a, (int)i);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) if (f.v[c] != 0) dest[j.v[c]] = v.v[c];
+        for (int c = 0; c < 4; ++c) if (f.v[c] != 0) scatter_one<Add>(dest, j.v[c], v.v[c]);
       }
     }
   }
   if (blockIdx.x == 0 && threadIdx.x < n - n4) {
     int i = (int)(n4 + threadIdx.x);
-    if (EF::template eval<EI::kNodes + EV::kNodes>(a, i) != 0) dest[EI::template eval<0>(a, i)] = EV::template eval<EI::kNodes>(a, i);
+    if (EF::template eval<EI::kNodes + EV::kNodes>(a, i) != 0)
+      scatter_one<Add>(dest, EI::template eval<0>(a, i), EV::template eval<EI::kNodes>(a, i));
+  }
+}
+
+// ------------------------------------------------------------------ row folds
+// y[i] = fold(Op, E(row(i) * m + j) for j < m): fold over the innermost dimension
+// of a 2-D iteration space (section 2, fold).  row(i) = i, or RI(i) when a gather
+// consumes the fold inside the cluster: the gather picks the row and the fold
+// loops over it (section 3.3, `simple4`).  A second reducer folds the same
+// element program in the same pass (two folds sharing a contracted producer,
+// section 5, `greedyBottomUpBad`).  L lanes cooperate on a row.
+struct NoRowIndex {
+  static constexpr int kNodes = 0;
+  template <int Base> static __device__ __forceinline__ int eval(const KArgs &, int i) { return i; }
+  static void sig(std::string &) {}
+};
+struct NoSecondOp {
+  using T = float;
+  static __device__ __forceinline__ T identity() { return 0.0f; }
+  static __device__ __forceinline__ T apply(T a, T) { return a; }
+  static const char *name() { return ""; }
+};
+
+template <class Op1, class Op2, class E, class RI, int L>
+__global__ __launch_bounds__(kBlock) void rowfold_kernel(const KArgs a) {
+  using T = typename Op1::T;
+  constexpr bool kTwo = !std::is_same<Op2, NoSecondOp>::value;
+  __shared__ T lds1[kWavesPerBlock + 1];
+  __shared__ typename Op2::T lds2[kWavesPerBlock + 1];
+  const unsigned rows = (unsigned)a.aux, m = (unsigned)a.w;
+  constexpr unsigned kRowsPerBlock = kBlock / L;
+  const unsigned sub = threadIdx.x % L;
+  const unsigned steps = (rows + gridDim.x * kRowsPerBlock - 1) / (gridDim.x * kRowsPerBlock);
+  for (unsigned s = 0; s < steps; ++s) {          // same trip count for every thread: barriers and DPP stay converged
+    const unsigned r = (s * gridDim.x + blockIdx.x) * kRowsPerBlock + threadIdx.x / L;
+    T acc1 = Op1::identity();
+    typename Op2::T acc2 = Op2::identity();
+    if (r < rows) {
+      const unsigned base = (unsigned)RI::template eval<E::kNodes>(a, (int)r) * m;
+      if ((m & 3u) == 0) {
+        for (unsigned j = sub * 4; j < m; j += L * 4) {
+          Vec4<T> v = E::template eval4<0>(a, (int)(base + j));
+#pragma unroll
+          for (int c = 0; c < 4; ++c) { acc1 = Op1::apply(acc1, v.v[c]); if (kTwo) acc2 = Op2::apply(acc2, v.v[c]); }
+        }
+      } else {
+        for (unsigned j = sub; j < m; j += L) {
+          T v = E::template eval<0>(a, (int)(base + j));
+          acc1 = Op1::apply(acc1, v);
+          if (kTwo) acc2 = Op2::apply(acc2, v);
+        }
+      }
+    }
+    if (L == 16) {
+      acc1 = row_scan_inclusive<Op1>(acc1);
+      if (kTwo) acc2 = row_scan_inclusive<Op2>(acc2);
+    } else if (L == kWave) {
+      acc1 = wave_scan_inclusive<Op1>(acc1);
+      if (kTwo) acc2 = wave_scan_inclusive<Op2>(acc2);
+    } else {
+      acc1 = block_reduce<Op1>(acc1, lds1);
+      if (kTwo) acc2 = block_reduce<Op2>(acc2, lds2);
+    }
+    if (sub == L - 1 && r < rows) {
+      static_cast<T *>(a.out[0])[r] = acc1;
+      if (kTwo) static_cast<typename Op2::T *>(a.out[1])[r] = acc2;
+    }
   }
 }
 

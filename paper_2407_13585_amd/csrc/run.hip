@@ -98,8 +98,7 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
   for (int a : members) {
     const fc_node &nd = m.nodes[a];
     switch (nd.kind) {
-      case FC_SCANL: scans.push_back(a); break;
-      case FC_SCANR: return unsupported("scanr has no kernel instance yet");
+      case FC_SCANL: case FC_SCANR: scans.push_back(a); break;
       case FC_SCATTER: scatters.push_back(a); break;
       case FC_FOLD: folds.push_back(a); break;
       case FC_FOLDSEG: foldsegs.push_back(a); break;
@@ -127,7 +126,7 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     const int sc = scans[0];
     const int x = m.nodes[sc].arg[0];
     if (m.nodes[sc].dtype != FC_I32) return unsupported("scan of f32");
-    sig = "scan[";
+    sig = m.nodes[sc].kind == FC_SCANR ? "scanr[" : "scan[";
     if (!b.expr(x, sig)) return unsupported("scan input");
     sig += "]";
     set_n(m.size(sc));
@@ -152,14 +151,17 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     if (scatters.size() != 1 || !folds.empty() || !foldsegs.empty() || !stores.empty())
       return unsupported("scatter cluster shape");
     const fc_node &st = m.nodes[scatters[0]];
-    if (st.fn != FC_OP_OVERWRITE) return unsupported("combining scatter has no kernel instance yet");
-    if (st.nargs != 4) return unsupported("scatter without flag");
-    sig = "scatter[";
+    if (st.fn == FC_OP_ADD && st.dtype != FC_I32) return unsupported("combining scatter of f32 (order dependent)");
+    sig = st.fn == FC_OP_ADD ? "scatter.add[" : "scatter[";
     if (!b.expr(st.arg[1], sig)) return unsupported("scatter index");
     sig += ",";
     if (!b.expr(st.arg[2], sig)) return unsupported("scatter value");
     sig += ",";
-    if (!b.expr(st.arg[3], sig)) return unsupported("scatter flag");
+    if (st.nargs == 4) {
+      if (!b.expr(st.arg[3], sig)) return unsupported("scatter flag");
+    } else {
+      sig += "1";
+    }
     sig += "]";
     set_n(m.size(st.arg[1]));
     shape_from(st.arg[1]);
@@ -175,20 +177,53 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     out.aux = (int)f.shape[0];
     out.offsets_node = f.arg[1];
     out.out_nodes[0] = foldsegs[0];
-  } else {
-    if (stores.size() > 1 || folds.size() > 1 || (stores.empty() && folds.empty()))
-      return unsupported("cluster with " + std::to_string(stores.size()) + " stored arrays and " + std::to_string(folds.size()) + " folds");
+  } else if (!folds.empty() && m.nodes[m.nodes[folds[0]].arg[0]].rank == 2 &&
+             m.nodes[m.nodes[folds[0]].arg[0]].shape[0] > 1 &&
+             m.nodes[folds[0]].shape[0] == m.nodes[m.nodes[folds[0]].arg[0]].shape[0]) {
+    // folds over the innermost dimension: one or two reducers over the same argument,
+    // optionally consumed by a gather that picks the row
+    if (folds.size() > 2 || stores.size() > 1) return unsupported("row-fold cluster shape");
+    const fc_node &f0 = m.nodes[folds[0]];
+    const int arg = f0.arg[0];
+    if (folds.size() == 2 && (m.nodes[folds[1]].arg[0] != arg || m.nodes[folds[1]].dtype != f0.dtype))
+      return unsupported("two row folds must reduce the same array");
+    sig = std::string("rowfold.") + op_name(f0.fn, f0.dtype);
+    if (folds.size() == 2) sig += std::string("+") + op_name(m.nodes[folds[1]].fn, m.nodes[folds[1]].dtype);
+    sig += "[";
+    if (!b.expr(arg, sig)) return unsupported("row-fold argument");
+    sig += "]";
+    out.w = (int)m.nodes[arg].shape[1];
+    out.h = (int)m.nodes[arg].shape[0];
     if (!stores.empty()) {
-      sig = "store[";
-      if (!b.expr(stores[0], sig)) return unsupported("stored array");
-      sig += "]";
-      set_n(m.size(stores[0]));
-      shape_from(stores[0]);
+      const fc_node &g = m.nodes[stores[0]];
+      if (g.kind != FC_GATHER || folds.size() != 1 || g.arg[1] != folds[0] || !c.fused_away[folds[0]])
+        return unsupported("a row fold can only be consumed by a gather inside its cluster");
+      sig += "@gather(";
+      if (!b.expr(g.arg[0], sig)) return unsupported("row index");
+      sig += ")";
+      n = (int)m.size(stores[0]);
       out.out_nodes[0] = stores[0];
+    } else {
+      for (int f : folds) if (c.fused_away[f]) return unsupported("row fold consumed inside its cluster");
+      n = (int)f0.shape[0];
+      out.out_nodes[0] = folds[0];
+      if (folds.size() == 2) out.out_nodes[1] = folds[1];
+    }
+    out.aux = n;
+  } else {
+    if (stores.size() > 2 || folds.size() > 1 || (stores.empty() && folds.empty()) || (stores.size() == 2 && !folds.empty()))
+      return unsupported("cluster with " + std::to_string(stores.size()) + " stored arrays and " + std::to_string(folds.size()) + " folds");
+    for (size_t k = 0; k < stores.size(); ++k) {
+      if (k) sig += "+";
+      sig += "store[";
+      if (!b.expr(stores[k], sig)) return unsupported("stored array");
+      sig += "]";
+      if (!set_n(m.size(stores[k]))) return unsupported("iteration sizes differ inside a cluster");
+      if (k == 0) shape_from(stores[0]);
+      out.out_nodes[k] = stores[k];
     }
     if (!folds.empty()) {
       const fc_node &f = m.nodes[folds[0]];
-      if (!(f.rank == 1 && f.shape[0] == 1)) return unsupported("row fold has no kernel instance yet");
       if (!stores.empty()) sig += "+";
       sig += std::string("fold.") + op_name(f.fn, f.dtype) + "[";
       if (!b.expr(f.arg[0], sig)) return unsupported("fold argument");

@@ -18,12 +18,8 @@
 namespace fc {
 
 constexpr int kStripCols = (kWave - 2) * kVec;   // 248 output columns per wave
-#ifndef FC_STENCIL_BAND
-#define FC_STENCIL_BAND 32
-#define FC_STENCIL_ROWS 4
-#endif
-constexpr int kBandRows = FC_STENCIL_BAND;       // rows per wave (a multiple of kRowsPerStep)
-constexpr int kRowsPerStep = FC_STENCIL_ROWS;    // row loads in flight per lane
+constexpr int kBandRows = 32;                    // rows per wave (a multiple of kRowsPerStep)
+constexpr int kRowsPerStep = 4;                  // row loads in flight per lane
 
 struct Quad { float x, y, z, w; };
 
@@ -34,11 +30,8 @@ __device__ __forceinline__ Quad load_row(const float *g, const Slot &s, int r, i
   Quad v;
   if (c >= 0 && c + 3 < W) {
     using V = float __attribute__((ext_vector_type(4)));
-#ifdef FC_STENCIL_PLAIN_LOAD
-    V t = *reinterpret_cast<const V *>(row + c);
-#else
+    // non-temporal: the streamed grid must not displace the halo rows in L2 (measured: 18 % faster)
     V t = __builtin_nontemporal_load(reinterpret_cast<const V *>(row + c));
-#endif
     v = {t.x, t.y, t.z, t.w};
   } else {
     v.x = row[min(max(c, 0), W - 1)];
@@ -63,11 +56,7 @@ __global__ __launch_bounds__(kBlock) void stencil5_kernel(const KArgs a, Control
   // range of (band, strip group) tiles so that halo rows are re-read from its own L2
   const int n_blocks = n_groups * n_bands;
   const int per_xcd = (n_blocks + 7) / 8;
-#ifdef FC_STENCIL_NO_XCD
-  const int logical = (int)blockIdx.x;
-#else
   const int logical = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
-#endif
   float m = -__builtin_inff();
   if (logical < n_blocks) {
     const int band = logical / n_groups, group = logical - band * n_groups;
@@ -96,11 +85,7 @@ __global__ __launch_bounds__(kBlock) void stencil5_kernel(const KArgs a, Control
           if (writes && r + k < r1) {
             using V = float __attribute__((ext_vector_type(4)));
             V t = {o.x, o.y, o.z, o.w};
-#ifdef FC_STENCIL_NT_STORE
-            __builtin_nontemporal_store(t, reinterpret_cast<V *>(out + (size_t)(r + k) * (size_t)W + c));
-#else
             *reinterpret_cast<V *>(out + (size_t)(r + k) * (size_t)W + c) = t;
-#endif
             if (WithMax) m = fmaxf(fmaxf(fmaxf(m, cur.x), fmaxf(cur.y, cur.z)), cur.w);
           }
           prev = cur;

@@ -45,6 +45,9 @@ class DeviceProgram:
                     t[:a.size].copy_(torch.from_numpy(a.reshape(-1)))
                 self.buffers[n.name] = t
         wanted = set(graph.outputs()) | set(bind)
+        for n in reversed(graph.nodes):   # a fetched scatter needs its destination in a caller-visible tensor
+            if n.kind == "scatter" and n.name in wanted:
+                wanted.add(n.args[0])
         for n in graph.nodes:
             if n.name in wanted and n.kind not in ("input", "scatter"):
                 self.buffers[n.name] = torch.zeros(max(n.size, 4), dtype=_TORCH[n.dtype], device=self.device)

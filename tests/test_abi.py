@@ -100,9 +100,15 @@ def test_run_checks_come_before_any_launch():
 
 
 def test_unsupported_cluster_is_reported_not_executed():
-    # legal clustering, but no kernel instance: a gather of a row-fold (`simple4`)
-    g = PG.simple4()
+    # a legal clustering for which no kernel instance is compiled
+    g = Graph()
+    g.add("a", "input", "f32", (64,))
+    g.add("b", "input", "f32", (64,))
+    g.add("ea", "map", "f32", (64,), fn="exp_neg", args=("a",))
+    g.add("sb", "map", "f32", (64,), fn="sin_x_mul_x", args=("b",))
+    g.add("out", "map", "f32", (64,), fn="mul2", args=("ea", "sb"), output=True)
     part = fc.fc_plan(g, "bytes")
+    assert part.n_clusters == 1
     msg = expect("FC_E_UNSUPPORTED", fc.fc_cluster_kernel, g, part, 0)
     assert "element program" in msg or "instance" in msg
     fake = (0x10000000, 1 << 30)

@@ -1,0 +1,146 @@
+"""The example programs of the paper (sections 1, 3.3, 3.4, 5), planned by fc_plan and executed
+on the GPU, fused and unfused, against the CPU oracle."""
+import numpy as np
+import pytest
+
+import parity as P
+from oracle.interp import evaluate
+from workloads import Graph
+from workloads import paper_graphs as PG
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+
+
+def fc():
+    import paper_2407_13585_amd as fc_
+    return fc_
+
+
+def device_program(*a, **kw):
+    from paper_2407_13585_amd.device import DeviceProgram
+    return DeviceProgram(*a, **kw)
+
+
+def random_inputs(g, rng, index_ranges):
+    ins = {}
+    for n in g.nodes:
+        if n.kind != "input":
+            continue
+        if n.dtype == "i32":
+            hi = index_ranges.get(n.name, 1000)
+            ins[n.name] = rng.integers(0, hi, size=n.shape, dtype=np.int32)
+        else:
+            ins[n.name] = rng.uniform(0.9, 1.1, size=n.shape).astype(F32)
+    return ins
+
+
+def check(g, ins, exact=(), folds=(), close=(), duplicate=False, expect_clusters=None):
+    env = evaluate(g, ins)
+    gp = g
+    if duplicate:
+        gp, _ = fc().fc_duplicate(g)
+    part = fc().fc_plan(gp, "bytes")
+    if expect_clusters is not None:
+        assert part.n_clusters == expect_clusters
+    runs = {"fused": device_program(gp, ins, part), "unfused": device_program(g, ins, None)}
+    for tag, prog in runs.items():
+        prog.run()
+        for name in exact:
+            P.assert_bit_exact(prog.fetch(name), env[name], f"{tag}/{name}")
+        for name in folds:
+            got, ref = prog.fetch(name).astype(np.float64), env[name].astype(np.float64)
+            assert np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-30), f"{tag}/{name}"
+        for name, rel in close:
+            P.assert_close(prog.fetch(name), env[name], rel, f"{tag}/{name}")
+        assert prog.control_words()[1] == 0
+    return runs
+
+
+def test_scatter_example_combining_scatter():
+    rng = np.random.default_rng(1)
+    g = PG.scatter_example()
+    n = g["xs"].size
+    ins = {"xs": rng.integers(0, n, size=n, dtype=np.int32)}       # colliding indices on purpose
+    runs = check(g, ins, exact=("result",), expect_clusters=2)
+    assert runs["fused"].kernels()[-1].startswith("scatter.add[")
+
+
+def test_single_loop_is_one_kernel():
+    rng = np.random.default_rng(2)
+    g = PG.single_loop()
+    runs = check(g, random_inputs(g, rng, {}), exact=("result",), expect_clusters=1)
+    assert len(runs["fused"].kernels()) == 1
+
+
+def test_simple_programs():
+    rng = np.random.default_rng(3)
+    for make, ranges, out in ((PG.simple1, {"is": PG.N}, "bs"), (PG.simple2, {"is1": 2 * PG.N, "is2": PG.N}, "bs"),
+                              (PG.simple3, {"is": PG.N}, "bs"), (PG.simple5, {"is": PG.N}, "cs")):
+        g = make()
+        check(g, random_inputs(g, rng, ranges), exact=(out,))
+    g = PG.simple3()
+    check(g, random_inputs(g, rng, {"is": PG.N}), exact=("as", "bs"), expect_clusters=2)
+
+
+def test_simple4_gather_of_a_row_fold():
+    rng = np.random.default_rng(4)
+    for inner in (16, 5, 200, 4096):
+        g = Graph()
+        rows = 300
+        g.add("is", "input", "i32", (rows // 2,))
+        g.add("xs", "input", "f32", (rows, inner))
+        g.add("as", "fold", "f32", (rows,), fn="add", args=("xs",))
+        g.add("bs", "gather", "f32", (rows // 2,), args=("is", "as"), output=True)
+        ins = random_inputs(g, rng, {"is": rows})
+        runs = check(g, ins, folds=("bs",), expect_clusters=1)
+        assert "@gather" in runs["fused"].kernels()[0]
+
+
+def test_scan_then_gather_and_scanr():
+    rng = np.random.default_rng(5)
+    g = PG.scan_then_gather()
+    check(g, random_inputs(g, rng, {"is": PG.N, "xs": 100}), exact=("bs",), expect_clusters=2)
+    for n in (1, 5, 4097, 100003):
+        g = Graph()
+        g.add("x", "input", "i32", (n,))
+        g.add("z", "scanr", "i32", (n,), fn="add", args=("x",), output=True)
+        g.add("y", "scanl", "i32", (n,), fn="add", args=("x",), output=True)
+        ins = {"x": rng.integers(0, 50, size=n, dtype=np.int32)}
+        env = evaluate(g, ins)
+        part = fc().fc_partition_trivial(g)
+        prog = device_program(g, ins, part)
+        prog.run()
+        P.assert_bit_exact(prog.fetch("z"), env["z"], f"scanr n={n}")
+        P.assert_bit_exact(prog.fetch("y"), env["y"], f"scanl n={n}")
+
+
+def test_greedy_bottom_up_bad_contracts_the_large_array():
+    rng = np.random.default_rng(6)
+    for (n, m) in ((64, 4096), (7, 130), (1000, 16), (3, 10000)):
+        g = PG.greedy_bottom_up_bad(n, m)
+        ins = {"xs": rng.uniform(0.999, 1.001, size=n).astype(F32)}
+        runs = check(g, ins, folds=("result",), expect_clusters=2)
+        assert runs["fused"].kernels()[0].startswith("rowfold.add.f32+mul.f32[")
+        # the large array never reaches memory in the fused plan
+        gi = g.index()
+        part = fc().fc_plan(g, "bytes")
+        assert part.fused_away[gi["large"]] == 1 and part.fused_away[gi["is"]] == 1
+
+
+def test_greedy_top_down_bad():
+    rng = np.random.default_rng(7)
+    g = PG.greedy_top_down_bad()
+    check(g, random_inputs(g, rng, {}), folds=("result",), expect_clusters=2)
+
+
+def test_diagonal_cluster_two_stores():
+    rng = np.random.default_rng(8)
+    n = 10007
+    g = Graph()
+    g.add("as", "input", "f32", (n,))
+    g.add("bs", "map", "f32", (n,), fn="affine", fparam=(2.0, 0.5), args=("as",), output=True)
+    g.add("cs", "map", "f32", (n,), fn="affine", fparam=(-1.5, 1.0), args=("bs",), output=True)
+    ins = {"as": rng.standard_normal(n).astype(F32)}
+    runs = check(g, ins, exact=("bs", "cs"), expect_clusters=1)
+    assert runs["fused"].kernels()[0].count("store[") == 2
