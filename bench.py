@@ -94,6 +94,42 @@ def gather_ceiling(fc, DeviceProgram, np, torch):
     return out
 
 
+def paper_examples(fc, DeviceProgram, np, torch):
+    """The programs the paper times that can be rebuilt from its text (section 5, "Greedy
+    counterexamples", and `singleLoop` of section 1): fused by fc_plan versus no fusion."""
+    from workloads import paper_graphs as PG
+    rng = np.random.default_rng(7)
+    cases = {
+        "greedyBottomUpBad(n=64, m=10^6)": (PG.greedy_bottom_up_bad(64, 1000000),
+                                            {"xs": (1.0 + rng.uniform(-4, 4, 64) / 1e6).astype(np.float32)}),
+        "greedyTopDownBad(n=2^24)": (PG.greedy_top_down_bad(1 << 24), {"as": rng.standard_normal(1 << 24).astype(np.float32)}),
+        "singleLoop(n=2^24)": (PG.single_loop(1 << 24), {"as": rng.standard_normal(1 << 24).astype(np.float32)}),
+    }
+    out = {}
+    for name, (g, ins) in cases.items():
+        part = fc.fc_plan(g, "bytes")
+        progs = {"fused": DeviceProgram(g, ins, part), "unfused": DeviceProgram(g, ins, None)}
+        t = {}
+        for tag, p in progs.items():
+            p.run()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 10
+            a.record()
+            for _ in range(reps):
+                p.run()
+            b.record()
+            torch.cuda.synchronize()
+            t[tag] = a.elapsed_time(b) / reps * 1e3
+        out[name] = {"fused_us": round(t["fused"], 1), "unfused_us": round(t["unfused"], 1),
+                     "speedup": round(t["unfused"] / t["fused"], 2), "clusters": part.n_clusters,
+                     "kernels": progs["fused"].kernels()}
+        log(f"{name}: fused {t['fused']:9.1f} us ({part.n_clusters} kernels)  unfused {t['unfused']:9.1f} us  "
+            f"speedup {t['unfused'] / t['fused']:6.2f}x")
+        del progs
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +141,8 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--gather-ceiling", action="store_true",
                     help="also measure the rate of bare random gathers (no arithmetic) for three table sizes")
+    ap.add_argument("--paper-examples", action="store_true",
+                    help="also time the paper's small example programs, fused against unfused")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain copy kernel of known size (256 MiB in, 256 MiB out): the reference "
                          "that hardware counter readings are scaled by")
@@ -153,6 +191,7 @@ def main() -> int:
         log(f"calibration copy: {cal.kernels()} moves {4 * n} B in and {4 * n} B out per launch")
 
     ceiling = gather_ceiling(fc, DeviceProgram, np, torch) if args.gather_ceiling else None
+    examples = paper_examples(fc, DeviceProgram, np, torch) if args.paper_examples else None
 
     def one_step(s, events=None):
         for k, c in enumerate(cfgs):
@@ -251,6 +290,8 @@ def main() -> int:
     }
     if ceiling is not None:
         out["gather_ceiling"] = ceiling
+    if examples is not None:
+        out["paper_examples"] = examples
     print(json.dumps(out), flush=True)
     return 0
 

@@ -70,6 +70,17 @@ template <class Op1, class Op2, class E, class RI> hipError_t launch_rowfold(con
   if (a.aux == 0) return hipSuccess;
   if (a.w <= 64) return launch_k(&rowfold_kernel<Op1, Op2, E, RI, 16>, grid_for(a.aux, kBlock / 16, kMaxGrid * 4), c.stream, a);
   if (a.w <= 2048) return launch_k(&rowfold_kernel<Op1, Op2, E, RI, kWave>, grid_for(a.aux, kBlock / kWave, kMaxGrid * 4), c.stream, a);
+  if (a.aux < 1024 && a.w >= 4 * kTile) {
+    // few long rows: cut every row into chunks (a multiple of the 128-bit stride) so that ~2048 workgroups run
+    unsigned splits = std::min<unsigned>((unsigned)(a.w / kTile), std::max(1u, 2048u / (unsigned)a.aux));
+    splits = std::min<unsigned>(splits, (unsigned)(kMaxPartials / 2) / (unsigned)a.aux);
+    if (splits > 1) {
+      unsigned chunk = (((unsigned)a.w + splits - 1) / splits + kBlock * kVec - 1) / (kBlock * kVec) * (kBlock * kVec);
+      splits = ((unsigned)a.w + chunk - 1) / chunk;
+      return launch_k(&rowfold_split_kernel<Op1, Op2, E, RI>, (unsigned)a.aux * splits, c.stream, a, c.ctl, c.partials,
+                      splits, chunk);
+    }
+  }
   return launch_k(&rowfold_kernel<Op1, Op2, E, RI, kBlock>, grid_for(a.aux, 1, kMaxGrid * 4), c.stream, a);
 }
 

@@ -515,4 +515,67 @@ __global__ __launch_bounds__(kBlock) void rowfold_kernel(const KArgs a) {
   }
 }
 
+// Few long rows: a row is cut into `splits` chunks, one workgroup each, so that the
+// whole chip works on it.  Chunk results are published as tagged words; the
+// workgroup of a row's last chunk waits for the row's other chunks and combines
+// them in chunk order.  The very last workgroup waits for every chunk of the
+// launch before it advances the epoch.
+template <class Op1, class Op2, class E, class RI>
+__global__ __launch_bounds__(kBlock) void rowfold_split_kernel(const KArgs a, Control *ctl, unsigned long long *partials,
+                                                               unsigned splits, unsigned chunk_len) {
+  using T = typename Op1::T;
+  using U = typename Op2::T;
+  constexpr bool kTwo = !std::is_same<Op2, NoSecondOp>::value;
+  __shared__ T lds1[kWavesPerBlock + 1];
+  __shared__ U lds2[kWavesPerBlock + 1];
+  const unsigned m = (unsigned)a.w;
+  const unsigned r = blockIdx.x / splits, chunk = blockIdx.x % splits;
+  const unsigned epoch = load_agent(&ctl->epoch);
+  const unsigned tag = tag_of_epoch(epoch);
+  unsigned long long *second = partials + kMaxPartials / 2;
+  const unsigned base = (unsigned)RI::template eval<E::kNodes>(a, (int)r) * m;
+  const unsigned lo = chunk * chunk_len, hi = min(m, lo + chunk_len);
+  T acc1 = Op1::identity();
+  U acc2 = Op2::identity();
+  if ((m & 3u) == 0) {
+    for (unsigned j = lo + threadIdx.x * 4; j < hi; j += kBlock * 4) {
+      Vec4<T> v = E::template eval4<0>(a, (int)(base + j));
+#pragma unroll
+      for (int c = 0; c < 4; ++c) { acc1 = Op1::apply(acc1, v.v[c]); if (kTwo) acc2 = Op2::apply(acc2, v.v[c]); }
+    }
+  } else {
+    for (unsigned j = lo + threadIdx.x; j < hi; j += kBlock) {
+      T v = E::template eval<0>(a, (int)(base + j));
+      acc1 = Op1::apply(acc1, v);
+      if (kTwo) acc2 = Op2::apply(acc2, v);
+    }
+  }
+  acc1 = block_reduce<Op1>(acc1, lds1);
+  if (kTwo) acc2 = block_reduce<Op2>(acc2, lds2);
+  if (threadIdx.x == 0) {
+    store_agent64(&partials[blockIdx.x], pack_word((unsigned)as_bits(acc1), tag, 1u));
+    if (kTwo) store_agent64(&second[blockIdx.x], pack_word((unsigned)as_bits(acc2), tag, 1u));
+  }
+  if (chunk == splits - 1 && threadIdx.x == 0) {
+    T s1 = Op1::identity();
+    U s2 = Op2::identity();
+    for (unsigned k = 0; k < splits; ++k) {
+      unsigned long long w = wait_word(&partials[r * splits + k], tag, ctl);
+      s1 = Op1::apply(s1, w ? from_bits<T>((int)(unsigned)(w >> 32)) : Op1::identity());
+      if (kTwo) {
+        unsigned long long w2 = wait_word(&second[r * splits + k], tag, ctl);
+        s2 = Op2::apply(s2, w2 ? from_bits<U>((int)(unsigned)(w2 >> 32)) : Op2::identity());
+      }
+    }
+    static_cast<T *>(a.out[0])[r] = s1;
+    if (kTwo) static_cast<U *>(a.out[1])[r] = s2;
+  }
+  if (blockIdx.x == gridDim.x - 1) {
+    // every workgroup has taken its tag once its word is visible
+    for (unsigned k = threadIdx.x; k < gridDim.x; k += kBlock) (void)wait_word(&partials[k], tag, ctl);
+    __syncthreads();
+    if (threadIdx.x == 0) store_agent(&ctl->epoch, epoch + 1u);
+  }
+}
+
 }  // namespace fc

@@ -117,9 +117,10 @@ def test_scan_then_gather_and_scanr():
 
 def test_greedy_bottom_up_bad_contracts_the_large_array():
     rng = np.random.default_rng(6)
-    for (n, m) in ((64, 4096), (7, 130), (1000, 16), (3, 10000)):
+    for (n, m) in ((64, 4096), (7, 130), (1000, 16), (3, 10000), (64, 65536), (5, 1000003), (2, 1 << 20)):
         g = PG.greedy_bottom_up_bad(n, m)
-        ins = {"xs": rng.uniform(0.999, 1.001, size=n).astype(F32)}
+        # values so close to 1 that the product over a row of any length stays in range
+        ins = {"xs": (1.0 + rng.uniform(-4.0, 4.0, size=n) / m).astype(F32)}
         runs = check(g, ins, folds=("result",), expect_clusters=2)
         assert runs["fused"].kernels()[0].startswith("rowfold.add.f32+mul.f32[")
         # the large array never reaches memory in the fused plan

@@ -21,7 +21,7 @@ def scatter_example() -> Graph:
     return g
 
 
-def single_loop() -> Graph:
+def single_loop(N: int = N) -> Graph:
     """section 1: bs = reverse as; cs = map f as; ds = map g cs; result = zipWith3 (+) bs cs ds."""
     g = Graph()
     g.add("as", "input", "f32", (N,))
@@ -116,7 +116,7 @@ def greedy_bottom_up_bad(n: int = 64, m: int = 4096) -> Graph:
     return g
 
 
-def greedy_top_down_bad() -> Graph:
+def greedy_top_down_bad(N: int = N) -> Graph:
     """section 5: diagonal fusion of cs with bs versus vertical fusion of cs with es."""
     g = Graph()
     g.add("as", "input", "f32", (N,))
