@@ -155,6 +155,13 @@ int fc_num_edges(const fc_graph *g, int32_t *n_edges);
  * cost.  Graphs of more than 64 non-input nodes are refused (FC_E_LIMIT). */
 int fc_plan(const fc_graph *g, int cost_fn, uint32_t flags, fc_partition *out);
 
+/* The greedy comparison arms of section 5 ("Greedy"): direction 0 walks the fusible edges
+ * from the top of the graph, 1 from the bottom, and fuses an edge whenever a legal
+ * clustering still exists that fuses it together with the edges already taken.  The
+ * result is locally maximal, not optimal.  Same outputs and limits as fc_plan; cost is the
+ * value of cost_fn for the returned clustering. */
+int fc_plan_greedy(const fc_graph *g, int direction, int cost_fn, uint32_t flags, fc_partition *out);
+
 /* The clustering with every combinator in a cluster of its own (no fusion). */
 int fc_partition_trivial(const fc_graph *g, fc_partition *out);
 

@@ -283,3 +283,31 @@ def optimum(graph, kind: str) -> Tuple[float, List[List[List[int]]]]:
 def legal_partitions(graph) -> List[List[List[int]]]:
     nodes = [i for i, nd in enumerate(graph.nodes) if nd.kind != "input"]
     return [b for b in set_partitions(nodes) if judge(graph, b).legal]
+
+
+def greedy(graph, direction: str, kind: str) -> Tuple[float, List[Tuple[int, int]]]:
+    """The greedy comparison arms of section 5 ("Greedy"): walk the fusible edges from the top of
+    the graph ('top_down': producers nearest the inputs first) or from the bottom ('bottom_up':
+    consumers nearest the results first); fuse an edge if some legal clustering still fuses it
+    together with all edges taken so far.  Returns the cost of the cheapest legal clustering that
+    fuses the accepted edges, and those edges."""
+    legal = legal_partitions(graph)
+
+    def fuses(blocks, pairs):
+        where = {a: c for c, blk in enumerate(blocks) for a in blk}
+        return all(where[a] == where[b] for a, b in pairs)
+
+    edges = [(a, b, k) for (a, b, k) in _edges(graph) if _fusible(graph, a, b, k)]
+    if direction == "top_down":
+        edges.sort(key=lambda e: (e[0], e[1]))
+    elif direction == "bottom_up":
+        edges.sort(key=lambda e: (-e[1], -e[0]))
+    else:
+        raise ValueError(direction)
+    taken: List[Tuple[int, int]] = []
+    for (a, b, k) in edges:
+        trial = taken + [(a, b)]
+        if any(fuses(p, trial) for p in legal):
+            taken = trial
+    best = min(cost(graph, p, judge(graph, p), kind) for p in legal if fuses(p, taken))
+    return best, taken

@@ -99,6 +99,7 @@ def lib() -> C.CDLL:
     PG, PP = C.POINTER(fc_graph), C.POINTER(fc_partition)
     L.fc_num_edges.argtypes = [PG, C.POINTER(C.c_int32)]
     L.fc_plan.argtypes = [PG, C.c_int, C.c_uint32, PP]
+    L.fc_plan_greedy.argtypes = [PG, C.c_int, C.c_int, C.c_uint32, PP]
     L.fc_partition_trivial.argtypes = [PG, PP]
     L.fc_partition_check.argtypes = [PG, PP, C.c_int, C.POINTER(C.c_double)]
     L.fc_duplicate.argtypes = [PG, C.POINTER(fc_node), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -106,7 +107,7 @@ def lib() -> C.CDLL:
     L.fc_run_fused.argtypes = [PG, PP, C.POINTER(fc_buffer), C.c_void_p, C.c_size_t, C.c_void_p]
     L.fc_run_unfused.argtypes = [PG, C.POINTER(fc_buffer), C.c_void_p, C.c_size_t, C.c_void_p]
     L.fc_cluster_kernel.argtypes = [PG, PP, C.c_int32, C.c_char_p, C.c_size_t]
-    for f in ("fc_num_edges", "fc_plan", "fc_partition_trivial", "fc_partition_check", "fc_duplicate",
+    for f in ("fc_num_edges", "fc_plan", "fc_plan_greedy", "fc_partition_trivial", "fc_partition_check", "fc_duplicate",
               "fc_scratch_bytes", "fc_run_fused", "fc_run_unfused", "fc_cluster_kernel"):
         getattr(L, f).restype = C.c_int
     _lib = L
@@ -207,6 +208,16 @@ def fc_plan(graph, cost: str = "bytes", no_split: bool = False) -> Partition:
     part = Partition.empty(len(g.names), g.n_edges)
     cp = part._c()
     _check(lib().fc_plan(g.ref(), COST[cost], FC_PLAN_NO_SPLIT if no_split else 0, C.byref(cp)))
+    return _finish(part, cp)
+
+
+def fc_plan_greedy(graph, direction: str, cost: str = "bytes", no_split: bool = False) -> Partition:
+    """direction: 'top_down' or 'bottom_up'."""
+    g = _cg(graph)
+    part = Partition.empty(len(g.names), g.n_edges)
+    cp = part._c()
+    d = {"top_down": 0, "bottom_up": 1}[direction]
+    _check(lib().fc_plan_greedy(g.ref(), d, COST[cost], FC_PLAN_NO_SPLIT if no_split else 0, C.byref(cp)))
     return _finish(part, cp)
 
 

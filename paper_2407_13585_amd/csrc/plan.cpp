@@ -31,6 +31,8 @@ struct Search {
   long long visited = 0;
   long long limit;
   bool aborted = false;
+  std::vector<int> forced;         // per node: representative of the set it must share a cluster with
+  bool stop_at_first = false;      // feasibility question only
   // block graph: adj[b] = bitmask of blocks that must run strictly after b
   std::vector<uint64_t> adj;
 
@@ -38,6 +40,14 @@ struct Search {
     for (int a = 0; a < m.n; ++a) {
       if (m.is_input(a)) block[a] = -2; else order.push_back(a);
     }
+    forced.resize(m.n);
+    for (int a = 0; a < m.n; ++a) forced[a] = a;
+  }
+
+  int forced_root(int a) const { while (forced[a] != a) a = forced[a]; return a; }
+  void force_together(int a, int b) {
+    a = forced_root(a); b = forced_root(b);
+    if (a != b) forced[std::max(a, b)] = std::min(a, b);
   }
 
   bool reaches(int from, int to) const {
@@ -106,6 +116,7 @@ struct Search {
     if (derive_and_check(m, pi, c, err) != FC_OK) return;
     double cost = evaluate_cost(m, c, cost_fn);
     if (cost < best) { best = cost; best_pi = pi; }
+    if (stop_at_first) aborted = true;
   }
 
   void go(size_t k) {
@@ -121,6 +132,11 @@ struct Search {
     }
     for (int b = 0; b < n_blocks; ++b) if (std::find(cand.begin(), cand.end(), b) == cand.end()) cand.push_back(b);
     if (n_blocks < 64) cand.push_back(n_blocks);
+    // a node tied to already placed nodes has no choice
+    int must = -1;
+    for (size_t j = 0; j < k; ++j)
+      if (forced_root(order[j]) == forced_root(a)) { must = block[order[j]]; break; }
+    if (must >= 0) cand.assign(1, must);
     for (int b : cand) {
       const bool fresh = b == n_blocks;
       // edges into `a`: infusible ones need another block; all of them order the blocks
@@ -190,6 +206,51 @@ int choose_clustering(const Model &m, int cost_fn, bool split, Clustering &out, 
   cost = evaluate_cost(m, out, cost_fn);
   n_clusters = split ? split_components(m, out) : renumber_levels(m, out);
   // the split changes cluster numbers only; re-derive the per-edge and per-node variables
+  Clustering again;
+  rc = derive_and_check(m, out.pi, again, err);
+  if (rc != FC_OK) return rc;
+  out = again;
+  return FC_OK;
+}
+
+// --------------------------------------------------------------------------- greedy
+int choose_greedy(const Model &m, int direction, int cost_fn, bool split, Clustering &out, int &n_clusters, double &cost,
+                  std::string &err) {
+  if (cost_fn < FC_COST_CLUSTERS || cost_fn > FC_COST_BYTES) { err = "unknown cost function"; return FC_E_ARG; }
+  int non_input = 0;
+  for (int a = 0; a < m.n; ++a) non_input += !m.is_input(a);
+  if (non_input > 64) { err = "the greedy chooser handles at most 64 combinators"; return FC_E_LIMIT; }
+  std::vector<int> edges;
+  for (size_t e = 0; e < m.edges.size(); ++e) if (m.edges[e].fusible) edges.push_back((int)e);
+  // top-down: edges nearest the inputs first; bottom-up: edges nearest the results first
+  std::stable_sort(edges.begin(), edges.end(), [&](int x, int y) {
+    const Edge &a = m.edges[x], &b = m.edges[y];
+    if (direction == 0) return a.a != b.a ? a.a < b.a : a.b < b.b;
+    return a.b != b.b ? a.b > b.b : a.a > b.a;
+  });
+  std::vector<std::pair<int, int>> accepted;
+  auto make_search = [&](bool first_only) {
+    Search s(m, cost_fn, 200000000LL);
+    for (auto &p : accepted) s.force_together(p.first, p.second);
+    s.stop_at_first = first_only;
+    return s;
+  };
+  for (int e : edges) {
+    accepted.push_back({m.edges[e].a, m.edges[e].b});
+    Search s = make_search(true);
+    s.go(0);
+    if (s.best_pi.empty()) {
+      if (s.aborted && s.visited > s.limit) { err = "search limit reached"; return FC_E_LIMIT; }
+      accepted.pop_back();          // no clustering fuses this edge together with the ones taken so far
+    }
+  }
+  Search s = make_search(false);
+  s.go(0);
+  if (s.aborted || s.best_pi.empty()) { err = "greedy search failed"; return FC_E_LIMIT; }
+  int rc = derive_and_check(m, s.best_pi, out, err);
+  if (rc != FC_OK) return rc;
+  cost = evaluate_cost(m, out, cost_fn);
+  n_clusters = split ? split_components(m, out) : renumber_levels(m, out);
   Clustering again;
   rc = derive_and_check(m, out.pi, again, err);
   if (rc != FC_OK) return rc;

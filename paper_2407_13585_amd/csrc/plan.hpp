@@ -14,6 +14,14 @@ namespace fc {
 int choose_clustering(const Model &m, int cost_fn, bool split, Clustering &out, int &n_clusters, double &cost,
                       std::string &err);
 
+// The greedy comparison arms of section 5 ("Greedy"): walk the fusible edges from the top
+// (direction 0) or from the bottom (direction 1) of the graph, fuse an edge whenever some
+// legal clustering still fuses it together with the edges taken so far; the result is
+// locally maximal.  Among the clusterings that fuse exactly those edges the cheapest
+// under cost_fn is returned.
+int choose_greedy(const Model &m, int direction, int cost_fn, bool split, Clustering &out, int &n_clusters, double &cost,
+                  std::string &err);
+
 // Clones map / generate nodes so that every copy is read in one traversal order.
 int duplicate_producers(const Model &m, std::vector<fc_node> &out_nodes, std::vector<int> &origin);
 

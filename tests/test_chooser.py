@@ -351,3 +351,50 @@ def test_split_post_pass_separates_unrelated_loops():
     g.add("m2", "map", "f32", (100,), fn="exp_neg", args=("a",), output=True)
     p = fc.fc_plan(g, "reads")
     assert p.n_clusters == 1 and p.cost == 1.0
+
+
+# ------------------------------------------------------------------ greedy comparison arms
+def test_greedy_arms_fall_into_the_papers_traps():
+    # section 5: bottom-up greedy fuses the final map into ys first and must then keep `large` manifest;
+    # top-down greedy fuses cs into bs diagonally instead of vertically into es
+    g = PG.greedy_bottom_up_bad()
+    ilp = fc.fc_plan(g, "bytes")
+    up = fc.fc_plan_greedy(g, "bottom_up", "bytes")
+    down = fc.fc_plan_greedy(g, "top_down", "bytes")
+    assert up.fused_away[g.index()["large"]] == 0 and up.cost > 100 * ilp.cost
+    assert down.cost == ilp.cost
+    g = PG.greedy_top_down_bad()
+    ilp = fc.fc_plan(g, "bytes")
+    down = fc.fc_plan_greedy(g, "top_down", "bytes")
+    up = fc.fc_plan_greedy(g, "bottom_up", "bytes")
+    assert clusters_of(down, g) == [["bs", "cs"], ["ds", "es", "result"]] and down.cost > ilp.cost
+    assert up.cost == ilp.cost
+
+
+@pytest.mark.parametrize("name", sorted(PG.ALL))
+def test_greedy_matches_the_oracle_and_never_beats_the_ilp_on_paper_graphs(name):
+    g = PG.ALL[name]()
+    for direction in ("top_down", "bottom_up"):
+        for cost in ("reads_writes", "bytes"):
+            want, _ = OC.greedy(g, direction, cost)
+            got = fc.fc_plan_greedy(g, direction, cost, no_split=True)
+            assert got.cost == pytest.approx(want), (direction, cost)
+            assert got.cost >= fc.fc_plan(g, cost, no_split=True).cost - 1e-9
+
+
+@pytest.mark.parametrize("seed", range(15))
+def test_greedy_matches_the_oracle_on_random_graphs(seed):
+    rng = np.random.default_rng(7000 + seed)
+    g = random_graph(rng, int(rng.integers(3, 7)))
+    if not OC.legal_partitions(g):
+        # the random program reads a scatter's destination after the scatter: no clustering is legal
+        with pytest.raises(fc.FcError):
+            fc.fc_plan_greedy(g, "top_down", "reads_writes")
+        with pytest.raises(fc.FcError):
+            fc.fc_plan(g, "reads_writes")
+        return
+    for direction in ("top_down", "bottom_up"):
+        want, _ = OC.greedy(g, direction, "reads_writes")
+        got = fc.fc_plan_greedy(g, direction, "reads_writes", no_split=True)
+        assert got.cost == pytest.approx(want), (seed, direction)
+        assert got.cost >= fc.fc_plan(g, "reads_writes", no_split=True).cost - 1e-9
