@@ -190,6 +190,29 @@ def main() -> int:
         torch.cuda.synchronize()
         log(f"calibration copy: {cal.kernels()} moves {4 * n} B in and {4 * n} B out per launch")
 
+    # pipeline 1 is 256 KiB and launch-latency bound; the same program at a bandwidth-sized n shows
+    # what its kernel sustains (reported beside the step, not part of it)
+    scaled = None
+    if 1 in cfgs and not args.small:
+        from workloads import configs as WC
+        ws = WC.reverse_dot(n=1 << 26, seed=1)
+        gs, _ = fc.fc_duplicate(ws.graph)
+        ps = [DeviceProgram(gs, ws.inputs, fc.fc_plan(gs, "bytes")) for _ in range(3)]
+        for p in ps:
+            p.run()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for r in range(12):
+            ps[r % 3].run()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) / 12 * 1e3
+        gbs = ws.lb_bytes / us / 1e3
+        scaled = {"n": 1 << 26, "kernel_us": round(us, 2), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        log(f"cfg1 scaled to n=2^26: {us:9.1f} us  {gbs:8.1f} GB/s  {100 * gbs / HBM_PEAK_GBS:5.1f}% of HBM peak")
+        del ps
+
     ceiling = gather_ceiling(fc, DeviceProgram, np, torch) if args.gather_ceiling else None
     examples = paper_examples(fc, DeviceProgram, np, torch) if args.paper_examples else None
 
@@ -288,6 +311,8 @@ def main() -> int:
                      "algorithmic_bytes": work[dom].lb_bytes},
         "cpu_baseline": cpu,
     }
+    if scaled is not None:
+        out["cfg1_scaled"] = scaled
     if ceiling is not None:
         out["gather_ceiling"] = ceiling
     if examples is not None:
