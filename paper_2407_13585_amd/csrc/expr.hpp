@@ -11,6 +11,7 @@
 //   eval4(args, i)    values at i .. i+3 (i a multiple of 4), 128-bit loads on leaves
 //   sig(std::string&) the textual signature the host matcher compares against
 //   kNodes            number of combinator nodes in the tree (parameter slots)
+//   kMirror           the tree reads an array through `reverse` as well (tile order, kernels.hpp)
 // Parameter slots are numbered in pre-order, leaves included.
 #pragma once
 
@@ -99,6 +100,7 @@ template <int K, class T>
 struct In {
   using R = T;
   static constexpr int kNodes = 1;
+  static constexpr bool kMirror = false;
   template <int Base> static __device__ __forceinline__ T eval(const KArgs &a, int i) {
     return static_cast<const T *>(a.in[K])[i];
   }
@@ -120,6 +122,7 @@ template <class F, class... E>
 struct Map {
   using R = typename F::R;
   static constexpr int kNodes = 1 + (E::kNodes + ... + 0);
+  static constexpr bool kMirror = (E::kMirror || ... || false);
   template <int Base, int... K>
   static __device__ __forceinline__ R eval_(const KArgs &a, int i, std::integer_sequence<int, K...>) {
     return F::apply(a.p[Base], E::template eval<ChildBase<Base + 1, K, E...>::value>(a, i)...);
@@ -150,6 +153,7 @@ template <class G>
 struct Gen {
   using R = int;
   static constexpr int kNodes = 1;
+  static constexpr bool kMirror = false;
   template <int Base> static __device__ __forceinline__ int eval(const KArgs &a, int i) {
     return G::apply(a.p[Base], a, i);
   }
@@ -166,6 +170,7 @@ struct Gen {
 struct AlwaysOne {
   using R = int;
   static constexpr int kNodes = 0;
+  static constexpr bool kMirror = false;
   template <int Base> static __device__ __forceinline__ int eval(const KArgs &, int) { return 1; }
   template <int Base> static __device__ __forceinline__ Vec4<int> eval4(const KArgs &, int) { return Vec4<int>{{1, 1, 1, 1}}; }
   static void sig(std::string &s) { s += "1"; }
@@ -176,6 +181,7 @@ template <class EI, class ES>
 struct Gather {
   using R = typename ES::R;
   static constexpr int kNodes = 1 + EI::kNodes + ES::kNodes;
+  static constexpr bool kMirror = EI::kMirror || ES::kMirror;
   template <int Base> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
     int j = EI::template eval<Base + 1>(a, i);
     return ES::template eval<Base + 1 + EI::kNodes>(a, j);
@@ -194,6 +200,62 @@ struct Gather {
     ES::sig(s);
     s += ")";
   }
+};
+
+// `reverse` (section 2, gather: the index is generate(n-1-i)): the source is read
+// backwards, so four consecutive results are one 128-bit read of the source,
+// taken in the opposite order, whenever the extent is a multiple of four.
+template <class ES>
+struct Gather<Gen<GenIotaRev>, ES> {
+  using R = typename ES::R;
+  using EI = Gen<GenIotaRev>;
+  static constexpr int kNodes = 1 + EI::kNodes + ES::kNodes;
+  static constexpr bool kMirror = true;
+  template <int Base> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
+    int j = EI::template eval<Base + 1>(a, i);
+    return ES::template eval<Base + 1 + EI::kNodes>(a, j);
+  }
+  template <int Base> static __device__ __forceinline__ Vec4<R> eval4(const KArgs &a, int i) {
+    const int total = a.p[Base + 1].ext[0] * a.p[Base + 1].ext[1];
+    Vec4<R> r;
+    if ((total & 3) == 0) {
+      Vec4<R> v = ES::template eval4<Base + 1 + EI::kNodes>(a, total - 4 - i);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) r.v[c] = v.v[3 - c];
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) r.v[c] = ES::template eval<Base + 1 + EI::kNodes>(a, total - 1 - (i + c));
+    }
+    return r;
+  }
+  static void sig(std::string &s) {
+    s += "gather(";
+    EI::sig(s);
+    s += ",";
+    ES::sig(s);
+    s += ")";
+  }
+};
+
+// KeepLoads<E>::type is E with every external array read by ordinary loads
+// instead of non-temporal ones.  Streams are read non-temporally so that they do
+// not displace gathered arrays from the caches; a program that reads one array
+// forwards and mirrored wants the opposite: the second read of a line should find
+// it (measured on the reversed dot product at 2^26 elements: 1.37x the array's
+// bytes fetched with non-temporal loads, 1.00x with ordinary ones).
+template <int K, class T>
+struct InKeep : In<K, T> {
+  template <int Base> static __device__ __forceinline__ Vec4<T> eval4(const KArgs &a, int i) {
+    using V = T __attribute__((ext_vector_type(4)));
+    V v = *reinterpret_cast<const V *>(static_cast<const T *>(a.in[K]) + i);
+    return Vec4<T>{{v.x, v.y, v.z, v.w}};
+  }
+};
+template <class E> struct KeepLoads { using type = E; };
+template <int K, class T> struct KeepLoads<In<K, T>> { using type = InKeep<K, T>; };
+template <class F, class... E> struct KeepLoads<Map<F, E...>> { using type = Map<F, typename KeepLoads<E>::type...>; };
+template <class EI, class ES> struct KeepLoads<Gather<EI, ES>> {
+  using type = Gather<typename KeepLoads<EI>::type, typename KeepLoads<ES>::type>;
 };
 
 }  // namespace fc

@@ -24,23 +24,61 @@ __device__ __forceinline__ void store4(T *p, const Vec4<T> &v) {
   *reinterpret_cast<V *>(p) = x;
 }
 
+// Iteration for element programs that read an array forwards and through
+// `reverse` (two traversal orders of one array in one loop, section 3.3
+// `simple5`).  Position i reads a[i] and a[n-1-i]; position n-1-i reads the same
+// two.  A lane therefore takes the 128-bit group at i together with its mirror
+// image at n4-4-i: the two groups issue the same two 128-bit reads, the second
+// pair hits in the vector cache, and the array comes from HBM once instead of
+// twice.  load(i) evaluates a group, use(i, value) consumes it; every group of
+// [0, n4) is used once.  All loads of a step are issued before the first use.
+template <class L, class U>
+__device__ __forceinline__ void for_each_mirrored_group(unsigned n4, L &&load, U &&use) {
+  const unsigned half = ((n4 / 4 + 1) / 2) * 4;     // the first half, the middle group included
+  for (unsigned base = blockIdx.x * kTile; base < half; base += gridDim.x * kTile) {
+    decltype(load(0u)) v[kUnroll][2];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
+      if (i < half) {
+        v[u][0] = load(i);
+        v[u][1] = load(n4 - 4 - i);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
+      if (i < half) {
+        use(i, v[u][0]);
+        if (n4 - 4 - i != i) use(n4 - 4 - i, v[u][1]);
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------ elementwise: out[i] = E(i)
 template <class E>
 __global__ __launch_bounds__(kBlock) void store_kernel(const KArgs a) {
   using T = typename E::R;
   T *out = static_cast<T *>(a.out[0]);
   const unsigned n = (unsigned)a.n, n4 = n & ~3u;
-  for (unsigned base = blockIdx.x * kTile; base < n4; base += gridDim.x * kTile) {
-    Vec4<T> v[kUnroll];
+  if constexpr (E::kMirror) {
+    for_each_mirrored_group(
+        n4, [&](unsigned i) { return KeepLoads<E>::type::template eval4<0>(a, (int)i); },
+        [&](unsigned i, const Vec4<T> &v) { store4(out + i, v); });
+  } else {
+    for (unsigned base = blockIdx.x * kTile; base < n4; base += gridDim.x * kTile) {
+      Vec4<T> v[kUnroll];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
-      if (i < n4) v[u] = E::template eval4<0>(a, (int)i);
-    }
+      for (int u = 0; u < kUnroll; ++u) {
+        unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
+        if (i < n4) v[u] = E::template eval4<0>(a, (int)i);
+      }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
-      if (i < n4) store4(out + i, v[u]);
+      for (int u = 0; u < kUnroll; ++u) {
+        unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
+        if (i < n4) store4(out + i, v[u]);
+      }
     }
   }
   if (blockIdx.x == 0 && threadIdx.x < n - n4) out[n4 + threadIdx.x] = E::template eval<0>(a, (int)(n4 + threadIdx.x));
@@ -55,15 +93,28 @@ __global__ __launch_bounds__(kBlock) void store2_kernel(const KArgs a) {
   T1 *out1 = static_cast<T1 *>(a.out[0]);
   T2 *out2 = static_cast<T2 *>(a.out[1]);
   const unsigned n = (unsigned)a.n, n4 = n & ~3u;
-  for (unsigned base = blockIdx.x * kTile; base < n4; base += gridDim.x * kTile) {
+  if constexpr (E1::kMirror || E2::kMirror) {
+    for_each_mirrored_group(
+        n4,
+        [&](unsigned i) {
+          return std::make_pair(KeepLoads<E1>::type::template eval4<0>(a, (int)i),
+                                KeepLoads<E2>::type::template eval4<E1::kNodes>(a, (int)i));
+        },
+        [&](unsigned i, const std::pair<Vec4<T1>, Vec4<T2>> &v) {
+          store4(out1 + i, v.first);
+          store4(out2 + i, v.second);
+        });
+  } else {
+    for (unsigned base = blockIdx.x * kTile; base < n4; base += gridDim.x * kTile) {
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
-      if (i < n4) {
-        Vec4<T1> v1 = E1::template eval4<0>(a, (int)i);
-        Vec4<T2> v2 = E2::template eval4<E1::kNodes>(a, (int)i);
-        store4(out1 + i, v1);
-        store4(out2 + i, v2);
+      for (int u = 0; u < kUnroll; ++u) {
+        unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
+        if (i < n4) {
+          Vec4<T1> v1 = E1::template eval4<0>(a, (int)i);
+          Vec4<T2> v2 = E2::template eval4<E1::kNodes>(a, (int)i);
+          store4(out1 + i, v1);
+          store4(out2 + i, v2);
+        }
       }
     }
   }
@@ -109,22 +160,31 @@ __global__ __launch_bounds__(kBlock) void fold_kernel(const KArgs a, Control *ct
   using T = typename Op::T;
   const unsigned n = (unsigned)a.n, n4 = n & ~3u;
   T acc = Op::identity();
-  for (unsigned base = blockIdx.x * kTile; base < n4; base += gridDim.x * kTile) {
-    Vec4<T> v[kUnroll];
+  if constexpr (E::kMirror) {
+    for_each_mirrored_group(
+        n4, [&](unsigned i) { return KeepLoads<E>::type::template eval4<0>(a, (int)i); },
+        [&](unsigned, const Vec4<T> &v) {
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
-      if (i < n4) {
-        v[u] = E::template eval4<0>(a, (int)i);
-      } else {
+          for (int c = 0; c < 4; ++c) acc = Op::apply(acc, v.v[c]);
+        });
+  } else {
+    for (unsigned base = blockIdx.x * kTile; base < n4; base += gridDim.x * kTile) {
+      Vec4<T> v[kUnroll];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) v[u].v[c] = Op::identity();
+      for (int u = 0; u < kUnroll; ++u) {
+        unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
+        if (i < n4) {
+          v[u] = E::template eval4<0>(a, (int)i);
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) v[u].v[c] = Op::identity();
+        }
       }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc = Op::apply(acc, v[u].v[c]);
     }
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) acc = Op::apply(acc, v[u].v[c]);
   }
   if (blockIdx.x == 0 && threadIdx.x < n - n4) acc = Op::apply(acc, E::template eval<0>(a, (int)(n4 + threadIdx.x)));
   fold_finish<Op>(acc, a, 0, ctl, partials);
@@ -138,16 +198,30 @@ __global__ __launch_bounds__(kBlock) void store_fold_kernel(const KArgs a, Contr
   S *out = static_cast<S *>(a.out[0]);
   const unsigned n = (unsigned)a.n, n4 = n & ~3u;
   T acc = Op::identity();
-  for (unsigned base = blockIdx.x * kTile; base < n4; base += gridDim.x * kTile) {
+  if constexpr (ES::kMirror || EF::kMirror) {
+    for_each_mirrored_group(
+        n4,
+        [&](unsigned i) {
+          return std::make_pair(KeepLoads<ES>::type::template eval4<0>(a, (int)i),
+                                KeepLoads<EF>::type::template eval4<ES::kNodes>(a, (int)i));
+        },
+        [&](unsigned i, const std::pair<Vec4<S>, Vec4<T>> &v) {
+          store4(out + i, v.first);
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
-      if (i < n4) {
-        Vec4<S> s = ES::template eval4<0>(a, (int)i);
-        Vec4<T> f = EF::template eval4<ES::kNodes>(a, (int)i);
-        store4(out + i, s);
+          for (int c = 0; c < 4; ++c) acc = Op::apply(acc, v.second.v[c]);
+        });
+  } else {
+    for (unsigned base = blockIdx.x * kTile; base < n4; base += gridDim.x * kTile) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc = Op::apply(acc, f.v[c]);
+      for (int u = 0; u < kUnroll; ++u) {
+        unsigned i = base + u * (kBlock * kVec) + threadIdx.x * kVec;
+        if (i < n4) {
+          Vec4<S> s = ES::template eval4<0>(a, (int)i);
+          Vec4<T> f = EF::template eval4<ES::kNodes>(a, (int)i);
+          store4(out + i, s);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc = Op::apply(acc, f.v[c]);
+        }
       }
     }
   }

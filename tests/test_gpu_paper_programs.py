@@ -73,6 +73,14 @@ def test_single_loop_is_one_kernel():
     assert len(runs["fused"].kernels()) == 1
 
 
+def test_single_loop_sizes():
+    # the reversed read: whole tiles, a ragged tail, tile counts off the groups of the mirrored order
+    rng = np.random.default_rng(12)
+    for n in (1, 3, 4, 4096, 4100, 16 * 4096, 21 * 4096 + 4, 47 * 4096 + 1, 2070 * 4096 + 12):
+        g = PG.single_loop(n)
+        check(g, random_inputs(g, rng, {}), exact=("result",), expect_clusters=1)
+
+
 def test_simple_programs():
     rng = np.random.default_rng(3)
     for make, ranges, out in ((PG.simple1, {"is": PG.N}, "bs"), (PG.simple2, {"is1": 2 * PG.N, "is2": PG.N}, "bs"),

@@ -103,7 +103,9 @@ def test_plans_have_the_expected_shape():
 
 
 # ------------------------------------------------------------------ ragged sizes, tiles, edges
-@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 255, 4095, 4096, 4097, 8191, 12289, 1 << 20])
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 255, 4095, 4096, 4097, 8191, 12289, 1 << 20,
+                               # tile counts around the groups of 16 the mirrored tile order forms
+                               16 * 4096, 17 * 4096 + 4, 33 * 4096 + 3, 38 * 4096 + 2052, 2100 * 4096 + 8])
 def test_fold_sizes(n):
     w = C.reverse_dot(n=n, seed=100 + n)
     run_all_modes(1, w)
