@@ -33,7 +33,28 @@ struct Slot {     // parameters of one combinator node
   float f[2];
   int i[2];       // the node's own integer parameters
   int ext[2];     // the node's own extents (outer, inner); inner is 1 for 1-D arrays
+  unsigned m[3];  // constants the host derives from the parameters (mod_eq_constants)
 };
+
+// x mod k == r for x >= 0 without a division.  With k = 2^s * d, d odd, and
+// inv = d^-1 mod 2^32: t is a multiple of k exactly if rotr(t * inv, s) <= (2^32-1) / k
+// (test for a zero remainder by multiplying with the inverse of the odd part);
+// apply it to t = x - r, which needs x >= r.  A residue outside [0, k) matches no x.
+inline void mod_eq_constants(Slot &s) {
+  const unsigned k = (unsigned)s.i[0];
+  if (s.i[0] <= 0 || s.i[1] < 0 || s.i[1] >= s.i[0]) {
+    s.i[1] = (int)0x80000000u;                // no non-negative int32 reaches it
+    s.m[0] = s.m[1] = s.m[2] = 0;
+    return;
+  }
+  unsigned shift = 0, d = k;
+  while ((d & 1u) == 0) { d >>= 1; ++shift; }
+  unsigned inv = d;                            // Newton steps double the number of correct low bits (3 to start with)
+  for (int it = 0; it < 5; ++it) inv *= 2u - d * inv;
+  s.m[0] = inv;
+  s.m[1] = shift;
+  s.m[2] = 0xffffffffu / k;
+}
 
 struct KArgs {    // arguments of one cluster launch
   const void *in[kMaxIn];   // external arrays read by the cluster
@@ -75,7 +96,13 @@ struct FnExpNeg { using R = float; static constexpr int kFn = FC_FN_EXP_NEG;
   static __device__ __forceinline__ R apply(const Slot &, float x) { return expf(-x); } };
 struct FnModEq { using R = int; static constexpr int kFn = FC_FN_MOD_EQ;
   static __device__ __forceinline__ R apply(const Slot &s, int x) {
-    return ((unsigned)x % (unsigned)s.i[0]) == (unsigned)s.i[1] ? 1 : 0; } };
+    const unsigned t = (unsigned)x - (unsigned)s.i[1];
+    const unsigned p = t * s.m[0];
+    const unsigned q = __builtin_amdgcn_alignbit(p, p, s.m[1]);     // rotate right
+    return ((unsigned)x >= (unsigned)s.i[1] && q <= s.m[2]) ? 1 : 0; } };
+
+// element functions whose result is 0 or 1
+template <class E> struct YieldsZeroOne { static constexpr bool value = false; };
 
 // index functions of generate
 struct GenIota { static constexpr int kFn = FC_FN_IOTA;
@@ -148,6 +175,8 @@ struct Map {
     s += ")";
   }
 };
+
+template <class... E> struct YieldsZeroOne<Map<FnModEq, E...>> { static constexpr bool value = true; };
 
 template <class G>
 struct Gen {

@@ -285,6 +285,14 @@ constexpr int kScanAcc = kScanItems / kVec;
 constexpr int kScanTile = kScanBlock * kScanItems;    // 12288 elements
 constexpr int kScanGroup = 256;                       // tiles per group
 constexpr int kOffs = 1, kScatter = 2, kCount = 4;
+// A compaction (the scanned stream is a 0/1 predicate, the kept elements are
+// scattered, the offsets are not stored) parks the kept elements of a tile in
+// LDS (see scan_kernel); the other forms hold the tile in registers across the
+// wait.  The LDS buffer takes half a tile; a tile that keeps more uses registers.
+template <class EX, int Mode> struct ScanParks {
+  static constexpr bool value = (Mode & kScatter) != 0 && (Mode & kOffs) == 0 && YieldsZeroOne<EX>::value;
+  static constexpr int cap = value ? kScanTile / 2 : 1;
+};
 
 // number of status words a launch over n_tiles tiles uses (tile words, then group words)
 __host__ __device__ inline size_t scan_status_words(size_t n_tiles) {
@@ -304,9 +312,8 @@ __device__ __forceinline__ int scan_block_sum(int v, int *lds) {
 }
 
 // Is the scanned stream a unary map of the scattered value stream (compaction by a
-// predicate on the element itself)?  Then the flags are recomputed from the values
-// when they are needed again instead of being kept in registers across the wait:
-// registers bound how many tiles are in flight, and tiles in flight bound bandwidth.
+// predicate on the element itself)?  Then the flags are computed from the values
+// already loaded instead of reading the array a second time.
 template <class EX, class EV> struct FlagOfValue {
   static constexpr bool value = false;
   static __device__ __forceinline__ int apply(const KArgs &, typename EV::R) { return 0; }
@@ -323,11 +330,12 @@ template <class F, class EV> struct FlagOfValue<Map<F, EV>, EV> {
 // yet published, or a stale line in this XCD's caches) is re-read at agent scope
 // until it does.  Agent-scope loads go to memory one lane at a time, so they are
 // kept for the few words that need them.
+template <int Threads = kScanBlock>
 __device__ __forceinline__ int sum_tagged_words(const unsigned long long *p, unsigned count, unsigned tag,
                                                 Control *ctl) {
   using Pair = unsigned long long __attribute__((ext_vector_type(2)));
   int sum = 0;
-  for (unsigned k = 2 * threadIdx.x; k < count; k += 2 * kScanBlock) {
+  for (unsigned k = 2 * (threadIdx.x % Threads); k < count; k += 2 * Threads) {
     Pair w = *reinterpret_cast<const Pair *>(p + k);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -341,44 +349,112 @@ __device__ __forceinline__ int sum_tagged_words(const unsigned long long *p, uns
   return sum;
 }
 
+// The same sum with the reads split from their use: the constructor issues this
+// thread's first Pairs reads (cached, coalesced) of the range, sum() validates
+// them and goes on with sum_tagged_words for whatever lies beyond.  Two ranges
+// constructed back to back have their reads in flight together.
+template <int Threads, int Pairs>
+struct TaggedPairs {
+  using Pair = unsigned long long __attribute__((ext_vector_type(2)));
+  const unsigned long long *p;
+  unsigned count;
+  Pair w[Pairs];
+  __device__ __forceinline__ TaggedPairs(const unsigned long long *p_, unsigned count_) : p(p_), count(count_) {
+#pragma unroll
+    for (int u = 0; u < Pairs; ++u) {
+      const unsigned k = 2 * (threadIdx.x % Threads) + u * 2 * Threads;
+      w[u] = Pair{0ull, 0ull};
+      if (k < count) w[u] = *reinterpret_cast<const Pair *>(p + k);
+    }
+  }
+  __device__ __forceinline__ int sum(unsigned tag, Control *ctl) const {
+    int s = 0;
+#pragma unroll
+    for (int u = 0; u < Pairs; ++u) {
+      const unsigned k = 2 * (threadIdx.x % Threads) + u * 2 * Threads;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        if (k + j >= count) break;
+        unsigned long long v = j ? w[u].y : w[u].x;
+        const unsigned lo = (unsigned)v;
+        if ((lo >> 2) != tag || (lo & 3u) == 0u) v = wait_word(p + k + j, tag, ctl);
+        s += (int)(unsigned)(v >> 32);
+      }
+    }
+    const unsigned done = Pairs * 2 * Threads;
+    if (count > done) s += sum_tagged_words<Threads>(p + done, count - done, tag, ctl);
+    return s;
+  }
+};
+
 // What a lane holds of one tile between loading it and writing its results.
+// Registers bound how many tiles are in flight, and tiles in flight bound
+// bandwidth, so a scanned stream of zeros and ones (a predicate) is kept as one
+// bit per element -- a single register for the 24 elements of a lane.
 template <class EX, class EV, int Mode, bool Reverse>
 struct ScanPayload {
   using V = typename EV::R;
   static constexpr bool kScat = (Mode & kScatter) != 0;
-  static constexpr bool kRecompute = kScat && FlagOfValue<EX, EV>::value;
-  int x[kRecompute ? 1 : kScanAcc][4];
+  static constexpr bool kBits = YieldsZeroOne<EX>::value;
+  static_assert(kScanItems <= 32, "one bit per element in a 32-bit register");
+  int x[kBits ? 1 : kScanAcc][4];
+  unsigned bits;
   V val[kScat ? kScanAcc : 1][4];
 
-  __device__ __forceinline__ int flag(const KArgs &a, int j, int c) const {
-    return kRecompute ? FlagOfValue<EX, EV>::apply(a, val[kScat ? j : 0][c]) : x[kRecompute ? 0 : j][c];
+  // element c of access j of the scanned stream; positions past the end of the array read 0
+  __device__ __forceinline__ int flag(int j, int c) const {
+    return kBits ? (int)((bits >> (j * 4 + c)) & 1u) : x[kBits ? 0 : j][c];
+  }
+  __device__ __forceinline__ void set(int j, int c, int v) {
+    if (kBits) bits |= (unsigned)(v != 0) << (j * 4 + c); else x[kBits ? 0 : j][c] = v;
   }
   // wave-striped layout: a wave owns kWave * kScanItems consecutive elements; access j
-  // of a lane covers elements base + j*256 + lane*4 .. +3 (fully coalesced)
+  // of a lane covers elements base + j*256 + lane*4 .. +3 (fully coalesced).
+  // A tile that lies wholly inside the array takes a path without any
+  // per-lane condition, so that its 128-bit reads are issued back to back and
+  // are all in flight together; the last tile (and scanr) takes the guarded path.
   __device__ __forceinline__ void load(const KArgs &a, unsigned tile, unsigned n) {
     const unsigned wbase = tile * kScanTile + wave_id() * (kWave * kScanItems);
+    bits = 0u;
+    if (!Reverse && (unsigned long long)(tile + 1) * kScanTile <= n) {
+      if (kScat) {
 #pragma unroll
-    for (int j = 0; j < kScanAcc; ++j) {
-      unsigned i = wbase + j * (kWave * kVec) + lane_id() * kVec;
-      if (!Reverse && i + 3 < n) {
-        if (!kRecompute) {
-          Vec4<int> v = EX::template eval4<0>(a, (int)i);
-#pragma unroll
-          for (int c = 0; c < 4; ++c) x[kRecompute ? 0 : j][c] = v.v[c];
-        }
-        if (kScat) {
-          Vec4<V> u = EV::template eval4<EX::kNodes>(a, (int)i);
+        for (int j = 0; j < kScanAcc; ++j) {
+          Vec4<V> u = EV::template eval4<EX::kNodes>(a, (int)(wbase + j * (kWave * kVec) + lane_id() * kVec));
 #pragma unroll
           for (int c = 0; c < 4; ++c) val[kScat ? j : 0][c] = u.v[c];
         }
-      } else {
+      }
+      if (kScat && FlagOfValue<EX, EV>::value) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          // scanr walks the array from its end: position i + c of the pass is element n - 1 - (i + c)
-          const int e = Reverse ? (int)(n - 1 - (i + c)) : (int)(i + c);
-          if (!kRecompute) x[kRecompute ? 0 : j][c] = (i + c < n) ? EX::template eval<0>(a, e) : 0;
-          if (kScat) val[kScat ? j : 0][c] = (i + c < n) ? EV::template eval<EX::kNodes>(a, e) : V(0);
-        }
+        for (int j = 0; j < kScanAcc; ++j)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) set(j, c, FlagOfValue<EX, EV>::apply(a, val[kScat ? j : 0][c]));
+      } else {
+        Vec4<int> v[kScanAcc];
+#pragma unroll
+        for (int j = 0; j < kScanAcc; ++j)
+          v[j] = EX::template eval4<0>(a, (int)(wbase + j * (kWave * kVec) + lane_id() * kVec));
+#pragma unroll
+        for (int j = 0; j < kScanAcc; ++j)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) set(j, c, v[j].v[c]);
+      }
+      return;
+    }
+#pragma unroll
+    for (int j = 0; j < kScanAcc; ++j) {
+      const unsigned i = wbase + j * (kWave * kVec) + lane_id() * kVec;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        // scanr walks the array from its end: position i + c of the pass is element n - 1 - (i + c)
+        const int e = Reverse ? (int)(n - 1 - (i + c)) : (int)(i + c);
+        const bool in = i + c < n;
+        if (kScat) val[kScat ? j : 0][c] = in ? EV::template eval<EX::kNodes>(a, e) : V(0);
+        if (kScat && FlagOfValue<EX, EV>::value)
+          set(j, c, in ? FlagOfValue<EX, EV>::apply(a, val[kScat ? j : 0][c]) : 0);
+        else
+          set(j, c, in ? EX::template eval<0>(a, e) : 0);
       }
     }
   }
@@ -391,6 +467,9 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
   __shared__ int lds_sum[kScanWaves];
   using P = ScanPayload<EX, EV, Mode, Reverse>;
   using V = typename EV::R;
+  constexpr bool kPark = ScanParks<EX, Mode>::value;
+  constexpr int kParkCap = ScanParks<EX, Mode>::cap;
+  __shared__ V parked[kParkCap];
   const unsigned n = (unsigned)a.n;
   const int lane = lane_id(), wave = wave_id();
   const unsigned epoch = load_agent(&ctl->epoch);
@@ -409,7 +488,7 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
       unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
       int f[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) f[c] = (i + c < n) ? cur.flag(a, j, c) : 0;
+      for (int c = 0; c < 4; ++c) f[c] = cur.flag(j, c);
       s[j] = (f[0] + f[1]) + (f[2] + f[3]);
     }
     // exclusive prefix of each access inside the wave
@@ -434,6 +513,66 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
     if (threadIdx.x == 0) store_agent64(&status[tile], pack_word((unsigned)aggregate, tag, 1u));
     const unsigned group = tile / kScanGroup, first = group * kScanGroup;
     const unsigned n_mine = tile - first;          // earlier tiles of my group
+
+    if (kPark && aggregate <= kParkCap) {
+      // Compaction.  Registers bound how many tiles are being loaded, and a tile
+      // that sat in registers until its prefix arrived held them for about twice
+      // the time its loads took.  So the kept elements are put into LDS in their
+      // final order, seven of the eight waves end here and give their registers
+      // and wave slots to the next tile, and one wave alone waits for the prefix
+      // and copies the run to its place.  Every word it waits for is published by
+      // a tile's loading phase, which waits for nothing.  Which wave stays rotates
+      // with the tile, so that the waiting waves spread over the four SIMDs.
+#pragma unroll
+      for (int j = 0; j < kScanAcc; ++j) {
+        unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
+        int o = wave_excl + excl[j];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          if (cur.flag(j, c) != 0) parked[o++] = cur.val[P::kScat ? j : 0][c];
+        }
+      }
+      __syncthreads();
+      if (wave != (int)(tile % kScanWaves)) return;
+      if (lane == 0 && tile > 0)
+        (void)wait_word(n_mine > 0 ? &status[tile - 1] : &group_word[group - 1], tag, ctl);
+      // the aggregates of the group's earlier tiles and the totals of the earlier groups
+      // are independent reads: both are issued before either is looked at
+      TaggedPairs<kWave, kScanGroup / (2 * kWave)> mine(status + first, n_mine);
+      TaggedPairs<kWave, 1> before(group_word, group);
+      int sum_group = wave_reduce<AddI32>(mine.sum(tag, ctl));
+      if (n_mine == kScanGroup - 1 && lane == 0)
+        store_agent64(&group_word[group], pack_word((unsigned)(sum_group + aggregate), tag, 1u));
+      const int tile_excl = sum_group + wave_reduce<AddI32>(before.sum(tag, ctl));
+      if (tile == n_tiles - 1 && lane == 0) {
+        if (Mode & kCount) *static_cast<int *>(a.out[2]) = tile_excl + aggregate;
+        store_agent(&ctl->epoch, epoch + 1u);
+      }
+      // copy the run to its place with 128-bit stores: single elements up to the first
+      // 16-byte boundary of the destination, whole groups of four, single elements again
+      V *dest = static_cast<V *>(a.out[0]) + tile_excl;
+      const int head = min((int)((16u - (unsigned)(reinterpret_cast<size_t>(dest) & 15u)) & 15u) / (int)sizeof(V), aggregate);
+      const int groups = (aggregate - head) / kVec;
+      if (lane < head) dest[lane] = parked[lane];
+      constexpr int kCopy = 4;
+      for (int g0 = 0; g0 < groups; g0 += kCopy * kWave) {
+        Vec4<V> v[kCopy];
+#pragma unroll
+        for (int u = 0; u < kCopy; ++u) {
+          const int k = head + min(g0 + u * kWave + lane, groups - 1) * kVec;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) v[u].v[c] = parked[k + c];
+        }
+#pragma unroll
+        for (int u = 0; u < kCopy; ++u) {
+          const int g = g0 + u * kWave + lane;
+          if (g < groups) store4(dest + head + g * kVec, v[u]);
+        }
+      }
+      const int tail = head + groups * kVec;
+      if (tail + lane < aggregate) dest[tail + lane] = parked[tail + lane];
+      return;
+    }
     // Gate: one lane waits for the word that is published last among those this tile
     // needs (its immediate predecessor's, or the previous group's total).  Words
     // become valid nearly in tile order, so after the gate the wide reads below
@@ -466,7 +605,7 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
       unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
       int f[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) f[c] = (i + c < n) ? cur.flag(a, j, c) : 0;
+      for (int c = 0; c < 4; ++c) f[c] = cur.flag(j, c);
       int o[4];
       o[0] = tile_excl + wave_excl + excl[j];
       o[1] = o[0] + f[0];

@@ -43,6 +43,7 @@ struct Builder {
     s.f[0] = nd.fparam[0]; s.f[1] = nd.fparam[1];
     s.i[0] = nd.iparam[0]; s.i[1] = nd.iparam[1];
     s.ext[0] = (int)nd.shape[0]; s.ext[1] = (int)nd.shape[1];
+    if (nd.kind == FC_MAP && nd.fn == FC_FN_MOD_EQ) mod_eq_constants(s);
     return true;
   }
 

@@ -124,6 +124,21 @@ def test_compaction_degenerate_flags():
         run_all_modes(4, C.compaction(v=v))
 
 
+@pytest.mark.parametrize("modulus,residue", [(1, 0), (2, 0), (2, 1), (3, 2), (4, 3), (6, 0), (6, 4), (7, 6), (12, 8),
+                                             (1000, 999), (65536, 123), (3 << 20, 5), (2 ** 31 - 1, 17), (5, 5), (5, 9)])
+def test_compaction_moduli(modulus, residue):
+    # the predicate is evaluated without a division (even and odd moduli, powers of two, a
+    # residue outside [0, modulus) that matches nothing); kept fractions from all to none
+    # cross the size of the buffer that holds a tile's kept elements
+    rng = np.random.default_rng(400 + modulus % 1000 + residue)
+    n = 70001
+    v = rng.integers(0, 2 ** 31, size=n, dtype=np.int32)
+    v[: n // 3] = (v[: n // 3] // modulus) * modulus + residue if residue < modulus else v[: n // 3]
+    v = np.abs(v.astype(np.int64)) % (2 ** 31)
+    v[:8] = [0, 1, 2, 2 ** 31 - 1, 2 ** 31 - 2, modulus % 2 ** 31, max(residue, 0) % 2 ** 31, 3]
+    run_all_modes(4, C.compaction(v=v.astype(np.int32), modulus=modulus, residue=residue))
+
+
 def test_empty_inputs():
     w = C.reverse_dot(xs=np.zeros(0, F32))
     env = evaluate(w.graph, w.inputs)
