@@ -7,8 +7,6 @@
 #include "stencil.hpp"
 
 #include <algorithm>
-#include <map>
-#include <mutex>
 
 namespace fc {
 
@@ -40,34 +38,11 @@ template <class... P>
 hipError_t launch_k(void (*k)(P...), unsigned grid, hipStream_t s, P... a) {
   return launch_k(k, grid, s, (int)kBlock, a...);
 }
-// Workgroups of a kernel that are resident on the current device at once.  The
-// kernels that stride over tiles are launched with at most that many: one
-// workgroup more starts a second round that lasts as long as the first (the
-// reversed dot product at 2^26 elements: 51 us with 64 registers per lane and 8
-// workgroups per CU, 69 us with 66 registers, 7 per CU and a grid of 8 per CU).
+// the kernels that stride over tiles are launched with as many workgroups as are resident at once
 template <class... P>
 unsigned resident_grid(void (*k)(P...)) {
-  static std::mutex mu;
-  static std::map<std::pair<int, const void *>, unsigned> grids;
-  static std::map<int, int> cus;
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return kMaxGrid;
-  std::lock_guard<std::mutex> lock(mu);
-  const auto key = std::make_pair(dev, reinterpret_cast<const void *>(k));
-  auto it = grids.find(key);
-  if (it != grids.end()) return it->second;
-  if (!cus.count(dev)) {
-    hipDeviceProp_t prop;
-    cus[dev] = hipGetDeviceProperties(&prop, dev) == hipSuccess ? prop.multiProcessorCount : 0;
-  }
-  int per_cu = 0;
-  unsigned g = kMaxGrid;
-  if (cus[dev] > 0 &&
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(k), kBlock, 0) == hipSuccess &&
-      per_cu > 0)
-    g = std::min<unsigned>((unsigned)per_cu * (unsigned)cus[dev], kMaxPartials);
-  grids[key] = g;
-  return g;
+  const unsigned r = resident_workgroups(k, kBlock);
+  return r ? std::min<unsigned>(r, kMaxPartials) : kMaxGrid;
 }
 
 template <class E> hipError_t launch_store(const KArgs &a, const LaunchCtx &c) {
