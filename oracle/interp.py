@@ -20,8 +20,9 @@ Precision rules
     integer work are exact.
 
 Readings taken where the paper leaves a choice
-  * scanl is exclusive and identity seeded ("the combined value of all prior
-    elements"); scanr is its mirror image.
+  * scanl is exclusive and identity seeded (element i combines the elements
+    before it, not itself); scanr is its mirror image; a two-dimensional array
+    is scanned row by row.
   * fold takes the identity of its operator as initial value, so an empty fold
     (and an empty segment of foldSeg) yields that identity.
   * a fold whose result has shape (1,) reduces the flattened input; otherwise it
@@ -162,16 +163,18 @@ def _foldseg(op, vals, off, dtype):
 
 
 def _scan(op, a, dtype, reverse):
+    """Exclusive (+) scan; a multidimensional array is scanned row by row, i.e. along its
+    innermost dimension (section 2, scanl / scanr)."""
     if op != "add":
         raise ValueError("scan supports (+) only")
-    flat = _acc(a.reshape(-1), dtype)
+    rows = _acc(a.reshape(-1, a.shape[-1]) if a.ndim > 1 else a.reshape(1, -1), dtype)
     if reverse:
-        flat = flat[::-1]
-    out = np.zeros_like(flat)
-    if flat.size:
-        np.cumsum(flat[:-1], out=out[1:])   # exclusive: element i combines all prior elements
+        rows = rows[:, ::-1]
+    out = np.zeros_like(rows)
+    if rows.shape[1]:
+        np.cumsum(rows[:, :-1], axis=1, out=out[:, 1:])   # exclusive: element i combines the elements before it
     if reverse:
-        out = out[::-1]
+        out = out[:, ::-1]
     if dtype == "i32":
         if out.size and out.max() > np.iinfo(np.int32).max:
             raise OverflowError("int32 scan overflowed")

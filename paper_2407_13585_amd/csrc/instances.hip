@@ -66,6 +66,15 @@ template <class EX, class EV, int Mode, bool Reverse = false> hipError_t launch_
   if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
   return launch_k(&scan_kernel<EX, EV, Mode, Reverse>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
 }
+// lanes per row by row length, as for the row folds
+template <class E, bool Reverse> hipError_t launch_rowscan(const KArgs &a, const LaunchCtx &c) {
+  if (a.aux == 0 || a.w == 0) return hipSuccess;
+  if (a.w <= 64)
+    return launch_k(&rowscan_kernel<E, Reverse, 16>, grid_for(a.aux, kBlock / 16, resident_grid(&rowscan_kernel<E, Reverse, 16>)), c.stream, a);
+  if (a.w <= 1024)
+    return launch_k(&rowscan_kernel<E, Reverse, kWave>, grid_for(a.aux, kBlock / kWave, resident_grid(&rowscan_kernel<E, Reverse, kWave>)), c.stream, a);
+  return launch_k(&rowscan_kernel<E, Reverse, kBlock>, grid_for(a.aux, 1, resident_grid(&rowscan_kernel<E, Reverse, kBlock>)), c.stream, a);
+}
 template <class EI, class EV, class EF, bool Add> hipError_t launch_scatter(const KArgs &a, const LaunchCtx &c) {
   if (a.n == 0) return hipSuccess;
   return launch_k(&scatter_kernel<EI, EV, EF, Add>, grid_for(a.n, kTile, resident_grid(&scatter_kernel<EI, EV, EF, Add>)), c.stream, a);
@@ -111,6 +120,9 @@ template <class EX, class EV, int Mode, bool Reverse = false> Instance scan_() {
   if (Mode & kScatter) s += "+scatter[" + sig_of<EV>() + "]";
   if (Mode & kCount) s += "+count";
   return {s, &launch_scan<EX, EV, Mode, Reverse>};
+}
+template <class E, bool Reverse = false> Instance rowscan_() {
+  return {std::string(Reverse ? "rowscanr[" : "rowscan[") + sig_of<E>() + "]+offs", &launch_rowscan<E, Reverse>};
 }
 template <class EI, class EV, class EF, bool Add = false> Instance scatter_() {
   return {std::string(Add ? "scatter.add[" : "scatter[") + sig_of<EI>() + "," + sig_of<EV>() + "," + sig_of<EF>() + "]",
@@ -208,6 +220,11 @@ std::vector<Instance> build_registry() {
   r.push_back(foldseg_<AddI32, I0>());
   r.push_back(scan_<I0, I0, kOffs>());
   r.push_back(scan_<I0, I0, kOffs, true>());                  // scanr: the same pass over the mirrored index space
+  // scans of two-dimensional arrays: every row on its own; the second with its producer fused in
+  r.push_back(rowscan_<I0>());
+  r.push_back(rowscan_<I0, true>());
+  r.push_back(rowscan_<ModFlag>());
+  r.push_back(rowscan_<ModFlag, true>());
   r.push_back(scatter_<I0, I1, I2>());
   r.push_back(scatter_<I0, F1, I2>());
   // ---- fused clusters ----

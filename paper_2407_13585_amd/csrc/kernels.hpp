@@ -607,6 +607,55 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
   }
 }
 
+// ------------------------------------------------------------------ row scans
+// scanl / scanr of a two-dimensional array scan every row on its own (section 2:
+// in a multidimensional array the scan is performed over each row).  A row is one
+// pass: L lanes walk it in steps of L elements, a carry links the steps, rows are
+// independent.  L is a 16-lane DPP row, a wave, or the workgroup, by row length.
+// out[1] receives the exclusive prefix sums; scanr is the same pass from the right.
+template <class E, bool Reverse, int L>
+__global__ __launch_bounds__(kBlock) void rowscan_kernel(const KArgs a) {
+  static_assert(L == 16 || L == kWave || L == kBlock, "lanes per row");
+  constexpr int kRows = kBlock / L;                     // rows a workgroup handles at a time
+  __shared__ int lds[kWavesPerBlock];
+  int *out = static_cast<int *>(a.out[1]);
+  const int rows = a.aux, w = a.w;
+  const int sub = (int)threadIdx.x % L, which = (int)threadIdx.x / L;
+  for (int r0 = (int)blockIdx.x * kRows; r0 < rows; r0 += (int)gridDim.x * kRows) {
+    const int r = r0 + which;
+    int carry = 0;
+    // every lane runs the same number of steps, so DPP and the barriers stay converged
+    for (int c0 = 0; c0 < w; c0 += L) {
+      const int c = c0 + sub;
+      const bool live = r < rows && c < w;
+      const int e = r * w + (Reverse ? w - 1 - c : c);
+      const int x = live ? E::template eval<0>(a, e) : 0;
+      int inc, total;
+      if (L == 16) {
+        inc = row_scan_inclusive<AddI32>(x);
+        total = __shfl(inc, 15, 16);
+      } else if (L == kWave) {
+        inc = wave_scan_inclusive<AddI32>(x);
+        total = __builtin_amdgcn_readlane(inc, kWave - 1);
+      } else {
+        inc = wave_scan_inclusive<AddI32>(x);
+        __syncthreads();                                  // lds of the previous step has been read
+        if (lane_id() == kWave - 1) lds[wave_id()] = inc;
+        __syncthreads();
+        total = 0;
+#pragma unroll
+        for (int k = 0; k < kWavesPerBlock; ++k) {
+          const int t = lds[k];
+          if (k < wave_id()) inc += t;
+          total += t;
+        }
+      }
+      if (live) out[e] = carry + inc - x;
+      carry += total;
+    }
+  }
+}
+
 // ------------------------------------------------------------------ scatter (elementwise)
 // for every i with EF(i) != 0: dest[EI(i)] = f(dest[EI(i)], EV(i)).  Overwrite: the
 // indices are taken to be distinct, so plain stores suffice (no atomics).  Add:

@@ -127,7 +127,13 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     const int sc = scans[0];
     const int x = m.nodes[sc].arg[0];
     if (m.nodes[sc].dtype != FC_I32) return unsupported("scan of f32");
-    sig = m.nodes[sc].kind == FC_SCANR ? "scanr[" : "scan[";
+    // a two-dimensional array is scanned row by row (one row: the same as one dimension)
+    const bool by_rows = m.nodes[sc].rank == 2 && m.nodes[sc].shape[0] != 1;
+    if (by_rows && (!scatters.empty() || !folds.empty() || c.fused_away[sc]))
+      return unsupported("a row scan can only be stored");
+    sig = by_rows ? (m.nodes[sc].kind == FC_SCANR ? "rowscanr[" : "rowscan[")
+                  : (m.nodes[sc].kind == FC_SCANR ? "scanr[" : "scan[");
+    if (by_rows) out.aux = (int)m.nodes[sc].shape[0];
     if (!b.expr(x, sig)) return unsupported("scan input");
     sig += "]";
     set_n(m.size(sc));

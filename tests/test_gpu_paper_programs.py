@@ -123,6 +123,34 @@ def test_scan_then_gather_and_scanr():
         P.assert_bit_exact(prog.fetch("y"), env["y"], f"scanl n={n}")
 
 
+def test_row_scans():
+    # scans of two-dimensional arrays run row by row; row lengths on both sides of the
+    # 16-lane / wave / workgroup variants, ragged against their step, with and without a fused producer
+    rng = np.random.default_rng(9)
+    for (rows, w) in ((1, 5), (3, 1), (37, 16), (300, 17), (129, 64), (65, 65), (40, 1000), (9, 1024), (7, 1025),
+                      (5, 5000), (2, 70001), (2051, 33)):
+        g = Graph()
+        g.add("x", "input", "i32", (rows, w))
+        g.add("l", "scanl", "i32", (rows, w), fn="add", args=("x",), output=True)
+        g.add("r", "scanr", "i32", (rows, w), fn="add", args=("x",), output=True)
+        ins = {"x": rng.integers(0, 1000, size=(rows, w), dtype=np.int32)}
+        env = evaluate(g, ins)
+        prog = device_program(g, ins, fc().fc_partition_trivial(g))
+        prog.run()
+        P.assert_bit_exact(prog.fetch("l"), env["l"], f"scanl {rows}x{w}")
+        P.assert_bit_exact(prog.fetch("r"), env["r"], f"scanr {rows}x{w}")
+        if rows > 1:
+            assert all(k.startswith("rowscan") for k in prog.kernels())
+    # producer fused into the row scan: offsets of the kept elements inside every row
+    g = Graph()
+    g.add("v", "input", "i32", (200, 777))
+    g.add("flags", "map", "i32", (200, 777), fn="mod_eq", iparam=(3, 0), args=("v",))
+    g.add("offs", "scanl", "i32", (200, 777), fn="add", args=("flags",), output=True)
+    ins = {"v": rng.integers(0, 2 ** 31, size=(200, 777), dtype=np.int32)}
+    runs = check(g, ins, exact=("offs",), expect_clusters=1)
+    assert runs["fused"].kernels() == ["rowscan[map10(in0:i32)]+offs"]
+
+
 def test_greedy_bottom_up_bad_contracts_the_large_array():
     rng = np.random.default_rng(6)
     for (n, m) in ((64, 4096), (7, 130), (1000, 16), (3, 10000), (64, 65536), (5, 1000003), (2, 1 << 20)):

@@ -322,6 +322,28 @@ def test_scan_is_exclusive():
     assert np.array_equal(run(g1, {"a": ones})["l"], np.arange(1000, dtype=np.int32))
 
 
+def test_scan_of_a_two_dimensional_array_scans_every_row():
+    # section 2 (scanl / scanr): in a multidimensional array the scan is performed over each row
+    rng = np.random.default_rng(31)
+    a = rng.integers(0, 100, size=(5, 7), dtype=np.int32)
+    g = Graph()
+    g.add("a", "input", "i32", (5, 7))
+    g.add("l", "scanl", "i32", (5, 7), fn="add", args=("a",))
+    g.add("r", "scanr", "i32", (5, 7), fn="add", args=("a",))
+    env = run(g, {"a": a})
+    for i in range(5):
+        row = a[i].tolist()
+        assert env["l"][i].tolist() == [sum(row[:j]) for j in range(7)]
+        assert env["r"][i].tolist() == [sum(row[j + 1:]) for j in range(7)]
+    # rows do not leak into each other: the first column of scanl and the last of scanr are zero
+    assert not env["l"][:, 0].any() and not env["r"][:, -1].any()
+    # a single row is the one-dimensional scan
+    g1 = Graph()
+    g1.add("a", "input", "i32", (1, 7))
+    g1.add("l", "scanl", "i32", (1, 7), fn="add", args=("a",))
+    assert run(g1, {"a": a[:1]})["l"][0].tolist() == [sum(a[0].tolist()[:j]) for j in range(7)]
+
+
 def test_compaction_invariants():
     w = C.compaction(n=50021, seed=21)
     env = evaluate(w.graph, w.inputs)
