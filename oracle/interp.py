@@ -16,8 +16,8 @@ Precision rules
     every operation rounded on its own (numpy never contracts a*b+c).
   * sin and exp are evaluated in fp64 and rounded once to fp32.
   * a fold / segmented fold with (+) over fp32 accumulates in fp64 and returns the
-    fp64 value (the reference the 1e-5 bound is measured against); max and all
-    integer work are exact.
+    fp64 value (the reference the 1e-5 bound is measured against); so does a
+    scatter that combines fp32 values with (+); max and all integer work are exact.
 
 Readings taken where the paper leaves a choice
   * scanl is exclusive and identity seeded (element i combines the elements
@@ -195,7 +195,13 @@ def _scatter(fn, dest, idx, val, flag):
             raise ValueError("overwrite scatter needs distinct destination indices")
         out[ki] = kv
     elif fn == "add":
-        np.add.at(out, ki, kv)               # sequential in source order
+        if out.dtype == F32:
+            # fp32 sums depend on the order of the updates, which the paper leaves open
+            # (section 2, scatter); the reference is the sum accumulated in fp64, as for folds
+            out = out.astype(np.float64)
+            np.add.at(out, ki, kv.astype(np.float64))
+        else:
+            np.add.at(out, ki, kv)           # sequential in source order; exact
     else:
         raise ValueError(f"unknown scatter function {fn}")
     return out.reshape(dest.shape)

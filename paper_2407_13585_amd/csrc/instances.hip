@@ -262,6 +262,8 @@ std::vector<Instance> build_registry() {
   r.push_back(scatter_<I0, I1, AlwaysOne, true>());
   r.push_back(scatter_<I0, I0, AlwaysOne, true>());
   r.push_back(scatter_<I0, I1, I2, true>());
+  r.push_back(scatter_<I0, F1, AlwaysOne, true>());          // fp32 sums: the order of the updates is not fixed
+  r.push_back(scatter_<I0, F1, I2, true>());
   r.push_back(scatter_<I0, I1, AlwaysOne>());
   r.push_back(scatter_<I0, F1, AlwaysOne>());
   // row folds: alone (the unfused arm), under a gather (`simple4`), and two folds that

@@ -659,9 +659,15 @@ __global__ __launch_bounds__(kBlock) void rowscan_kernel(const KArgs a) {
 // ------------------------------------------------------------------ scatter (elementwise)
 // for every i with EF(i) != 0: dest[EI(i)] = f(dest[EI(i)], EV(i)).  Overwrite: the
 // indices are taken to be distinct, so plain stores suffice (no atomics).  Add:
-// colliding indices combine; integer atomics make the result exact in any order.
+// colliding indices combine with hardware atomics.  Integer sums are exact in any
+// order.  fp32 sums depend on the order of the updates, which nothing fixes
+// (section 2, scatter: no guarantee on the order when the operator is not
+// associative and commutative); every single addition is correctly rounded.
 template <bool Add, class T> __device__ __forceinline__ void scatter_one(T *dest, int j, T v) {
   if (Add) atomicAdd(dest + j, v); else dest[j] = v;
+}
+template <> __device__ __forceinline__ void scatter_one<true, float>(float *dest, int j, float v) {
+  unsafeAtomicAdd(dest + j, v);      // the hardware's fp32 add, not a compare-and-swap loop
 }
 
 template <class EI, class EV, class EF, bool Add>

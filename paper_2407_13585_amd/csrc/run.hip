@@ -158,7 +158,6 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     if (scatters.size() != 1 || !folds.empty() || !foldsegs.empty() || !stores.empty())
       return unsupported("scatter cluster shape");
     const fc_node &st = m.nodes[scatters[0]];
-    if (st.fn == FC_OP_ADD && st.dtype != FC_I32) return unsupported("combining scatter of f32 (order dependent)");
     sig = st.fn == FC_OP_ADD ? "scatter.add[" : "scatter[";
     if (!b.expr(st.arg[1], sig)) return unsupported("scatter index");
     sig += ",";

@@ -123,6 +123,36 @@ def test_scan_then_gather_and_scanr():
         P.assert_bit_exact(prog.fetch("y"), env["y"], f"scanl n={n}")
 
 
+def test_scatter_add_fp32():
+    # colliding fp32 sums: hardware atomics, update order not fixed; every destination within
+    # 1e-5 of the sum of the magnitudes that went into it (the bound the row sums of SpMV use)
+    rng = np.random.default_rng(10)
+    for (n, k, flagged) in ((1, 1, False), (4099, 17, False), (1 << 20, 1000, True), (300001, 1 << 18, True)):
+        g = Graph()
+        g.add("dest", "input", "f32", (k,))
+        g.add("i", "input", "i32", (n,))
+        g.add("x", "input", "f32", (n,))
+        args = ("dest", "i", "x")
+        if flagged:
+            g.add("f", "input", "i32", (n,))
+            args += ("f",)
+        g.add("h", "scatter", "f32", (k,), fn="add", args=args, output=True)
+        ins = {"dest": rng.standard_normal(k).astype(F32), "i": rng.integers(0, k, n, dtype=np.int32),
+               "x": rng.standard_normal(n).astype(F32)}
+        if flagged:
+            ins["f"] = rng.integers(0, 2, n, dtype=np.int32)
+        env = evaluate(g, ins)
+        keep = ins["f"] != 0 if flagged else np.ones(n, bool)
+        scale = np.abs(ins["dest"]).astype(np.float64)
+        np.add.at(scale, ins["i"][keep], np.abs(ins["x"][keep]).astype(np.float64))
+        for part in (fc().fc_plan(g, "bytes"), None):
+            prog = device_program(g, ins, part)
+            prog.run()
+            got = prog.fetch("h").astype(np.float64)
+            assert np.all(np.abs(got - env["h"]) <= 1e-5 * scale + 1e-30), (n, k)
+            assert prog.kernels()[-1].startswith("scatter.add[")
+
+
 def test_row_scans():
     # scans of two-dimensional arrays run row by row; row lengths on both sides of the
     # 16-lane / wave / workgroup variants, ragged against their step, with and without a fused producer

@@ -391,6 +391,41 @@ def test_scatter_semantics():
         run(g, dict(ins, i=np.array([6, 0, 5, 2], np.int32)))
 
 
+def test_scatter_add_fp32_reference_is_the_exact_sum():
+    # fp32 (+) with colliding indices: the update order is not fixed (section 2, scatter), so the
+    # reference is the sum in fp64.  A histogram of ones has a closed form; a large start value
+    # followed by many small ones shows that nothing is rounded away on the way.
+    n, k = 100000, 7
+    g = Graph()
+    g.add("dest", "input", "f32", (k,))
+    g.add("i", "input", "i32", (n,))
+    g.add("x", "input", "f32", (n,))
+    g.add("h", "scatter", "f32", (k,), fn="add", args=("dest", "i", "x"))
+    idx = (np.arange(n) % k).astype(np.int32)
+    env = run(g, {"dest": np.zeros(k, F32), "i": idx, "x": np.ones(n, F32)})
+    assert env["h"].dtype == np.float64
+    assert env["h"].tolist() == [float(len(range(j, n, k))) for j in range(k)]
+    dest = np.zeros(k, F32)
+    dest[3] = F32(2.0 ** 26)                       # one more is below half an ulp of this in fp32
+    env = run(g, {"dest": dest, "i": np.full(n, 3, np.int32), "x": np.ones(n, F32)})
+    assert env["h"][3] == 2.0 ** 26 + n and not env["h"][[0, 1, 2, 4, 5, 6]].any()
+    # brute force, with a flag
+    rng = np.random.default_rng(5)
+    g2 = Graph()
+    g2.add("dest", "input", "f32", (5,))
+    g2.add("i", "input", "i32", (40,))
+    g2.add("x", "input", "f32", (40,))
+    g2.add("f", "input", "i32", (40,))
+    g2.add("h", "scatter", "f32", (5,), fn="add", args=("dest", "i", "x", "f"))
+    ins = {"dest": rng.standard_normal(5).astype(F32), "i": rng.integers(0, 5, 40, dtype=np.int32),
+           "x": rng.standard_normal(40).astype(F32), "f": rng.integers(0, 2, 40, dtype=np.int32)}
+    want = [float(d) for d in ins["dest"]]
+    for j, x, f in zip(ins["i"].tolist(), ins["x"].tolist(), ins["f"].tolist()):
+        if f:
+            want[j] += x
+    assert np.allclose(run(g2, ins)["h"], want, rtol=0, atol=1e-12)
+
+
 # ---------------------------------------------------------------- stencil + max
 def test_stencil_constant_grid_pins_clamping():
     c = F32(0.3)
