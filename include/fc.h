@@ -155,6 +155,15 @@ int fc_num_edges(const fc_graph *g, int32_t *n_edges);
  * cost.  Graphs of more than 64 non-input nodes are refused (FC_E_LIMIT). */
 int fc_plan(const fc_graph *g, int cost_fn, uint32_t flags, fc_partition *out);
 
+/* fc_plan for a linear combination of the cost functions: minimises
+ * sum_k weights[k] * cost_k, k over the FC_COST_COUNT values of fc_cost (section 5.1,
+ * "Runtime analysis", proposes such a combination with coefficients found by tuning as
+ * the way to a cost function that models run time on a given machine).  weights: HOST,
+ * FC_COST_COUNT entries, none negative, not all zero (else FC_E_ARG).  out->cost is the
+ * weighted sum for the chosen clustering.  Same outputs and limits as fc_plan. */
+#define FC_COST_COUNT 6
+int fc_plan_weighted(const fc_graph *g, const double *weights, uint32_t flags, fc_partition *out);
+
 /* The greedy comparison arms of section 5 ("Greedy"): direction 0 walks the fusible edges
  * from the top of the graph, 1 from the bottom, and fuses an edge whenever a legal
  * clustering still exists that fuses it together with the edges already taken.  The

@@ -99,6 +99,7 @@ def lib() -> C.CDLL:
     PG, PP = C.POINTER(fc_graph), C.POINTER(fc_partition)
     L.fc_num_edges.argtypes = [PG, C.POINTER(C.c_int32)]
     L.fc_plan.argtypes = [PG, C.c_int, C.c_uint32, PP]
+    L.fc_plan_weighted.argtypes = [PG, C.POINTER(C.c_double), C.c_uint32, PP]
     L.fc_plan_greedy.argtypes = [PG, C.c_int, C.c_int, C.c_uint32, PP]
     L.fc_partition_trivial.argtypes = [PG, PP]
     L.fc_partition_check.argtypes = [PG, PP, C.c_int, C.POINTER(C.c_double)]
@@ -107,7 +108,7 @@ def lib() -> C.CDLL:
     L.fc_run_fused.argtypes = [PG, PP, C.POINTER(fc_buffer), C.c_void_p, C.c_size_t, C.c_void_p]
     L.fc_run_unfused.argtypes = [PG, C.POINTER(fc_buffer), C.c_void_p, C.c_size_t, C.c_void_p]
     L.fc_cluster_kernel.argtypes = [PG, PP, C.c_int32, C.c_char_p, C.c_size_t]
-    for f in ("fc_num_edges", "fc_plan", "fc_plan_greedy", "fc_partition_trivial", "fc_partition_check", "fc_duplicate",
+    for f in ("fc_num_edges", "fc_plan", "fc_plan_weighted", "fc_plan_greedy", "fc_partition_trivial", "fc_partition_check", "fc_duplicate",
               "fc_scratch_bytes", "fc_run_fused", "fc_run_unfused", "fc_cluster_kernel"):
         getattr(L, f).restype = C.c_int
     _lib = L
@@ -209,6 +210,42 @@ def fc_plan(graph, cost: str = "bytes", no_split: bool = False) -> Partition:
     cp = part._c()
     _check(lib().fc_plan(g.ref(), COST[cost], FC_PLAN_NO_SPLIT if no_split else 0, C.byref(cp)))
     return _finish(part, cp)
+
+
+def _weights(weights) -> "C.Array":
+    """weights: {cost name: coefficient} or a sequence of len(COST) coefficients in fc_cost order."""
+    if isinstance(weights, dict):
+        unknown = set(weights) - set(COST)
+        if unknown:
+            raise ValueError(f"unknown cost functions {sorted(unknown)}")
+        vec = [float(weights.get(k, 0.0)) for k in sorted(COST, key=COST.get)]
+    else:
+        vec = [float(x) for x in weights]
+        if len(vec) != len(COST):
+            raise ValueError(f"expected {len(COST)} weights")
+    return (C.c_double * len(COST))(*vec)
+
+
+def fc_plan_weighted(graph, weights, no_split: bool = False) -> Partition:
+    g = _cg(graph)
+    part = Partition.empty(len(g.names), g.n_edges)
+    cp = part._c()
+    _check(lib().fc_plan_weighted(g.ref(), _weights(weights), FC_PLAN_NO_SPLIT if no_split else 0, C.byref(cp)))
+    return _finish(part, cp)
+
+
+def cost_vector(graph, pi: Sequence[int]) -> np.ndarray:
+    """The values of all cost functions (fc_cost order) for the clustering with these cluster numbers."""
+    g = _cg(graph)
+    out = np.zeros(len(COST))
+    for name, k in COST.items():
+        part = Partition.empty(len(g.names), g.n_edges)
+        part.pi[:] = np.asarray(pi, dtype=np.int32)
+        cp = part._c()
+        v = C.c_double()
+        _check(lib().fc_partition_check(g.ref(), C.byref(cp), k, C.byref(v)))
+        out[k] = v.value
+    return out
 
 
 def fc_plan_greedy(graph, direction: str, cost: str = "bytes", no_split: bool = False) -> Partition:

@@ -94,6 +94,22 @@ int fc_plan(const fc_graph *g, int cost_fn, uint32_t flags, fc_partition *out) {
   });
 }
 
+int fc_plan_weighted(const fc_graph *g, const double *weights, uint32_t flags, fc_partition *out) {
+  return guarded([&]() {
+    if (!weights) return fail(FC_E_ARG, "weights is NULL");
+    fc::Model m;
+    std::string err;
+    int rc = fc::build_model(g, m, err);
+    if (rc != FC_OK) return fail(rc, err);
+    fc::Clustering c;
+    int n_clusters = 0;
+    double cost = 0;
+    rc = fc::choose_clustering_weighted(m, weights, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err);
+    if (rc != FC_OK) return fail(rc, err);
+    return fill_partition(m, c, n_clusters, cost, out);
+  });
+}
+
 int fc_plan_greedy(const fc_graph *g, int direction, int cost_fn, uint32_t flags, fc_partition *out) {
   return guarded([&]() {
     fc::Model m;

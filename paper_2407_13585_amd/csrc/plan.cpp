@@ -20,9 +20,11 @@ namespace fc {
 
 namespace {
 
+constexpr int kCosts = FC_COST_BYTES + 1;
+
 struct Search {
   const Model &m;
-  int cost_fn;
+  double weight[kCosts];           // the objective is sum_k weight[k] * cost_k; one cost function = a unit vector
   std::vector<int> order;          // non-input nodes in program order
   std::vector<int> block;          // per node, -1 = unassigned (inputs: -2)
   int n_blocks = 0;
@@ -36,7 +38,8 @@ struct Search {
   // block graph: adj[b] = bitmask of blocks that must run strictly after b
   std::vector<uint64_t> adj;
 
-  Search(const Model &m_, int cf, long long lim) : m(m_), cost_fn(cf), block(m_.n, -1), limit(lim), adj(64, 0) {
+  Search(const Model &m_, const double *w, long long lim) : m(m_), block(m_.n, -1), limit(lim), adj(64, 0) {
+    for (int k = 0; k < kCosts; ++k) weight[k] = w[k];
     for (int a = 0; a < m.n; ++a) {
       if (m.is_input(a)) block[a] = -2; else order.push_back(a);
     }
@@ -63,10 +66,10 @@ struct Search {
     return false;
   }
 
-  // cost of the decisions taken so far; never above the cost of any completion
+  // cost of the decisions taken so far; never above the cost of any completion (every
+  // cost function only grows as nodes are placed, and the weights are not negative)
   double lower_bound() const {
-    const bool weighted = cost_fn == FC_COST_BYTES;
-    double reads = 0, writes = 0, unfused = 0;
+    double reads = 0, writes = 0, unfused = 0, bytes = 0;
     for (int a = 0; a < m.n; ++a) {
       if (block[a] == -1) continue;
       uint64_t readers = 0;
@@ -80,17 +83,19 @@ struct Search {
           if (m.edges[e].fusible) unfused += 1;
         }
       }
-      double wgt = weighted ? (double)m.bytes(a) : 1.0;
-      reads += wgt * __builtin_popcountll(readers);
-      if (manifest) writes += wgt;
+      const int r = __builtin_popcountll(readers);
+      reads += r;
+      if (manifest) writes += 1;
+      bytes += (double)m.bytes(a) * (r + (manifest ? 1 : 0));
     }
-    switch (cost_fn) {
-      case FC_COST_CLUSTERS: return n_blocks;
-      case FC_COST_FUSED_EDGES: return unfused;
-      case FC_COST_ARRAYS: return writes;
-      case FC_COST_READS: return reads;
-      default: return reads + writes;
-    }
+    return weight[FC_COST_CLUSTERS] * n_blocks + weight[FC_COST_FUSED_EDGES] * unfused + weight[FC_COST_ARRAYS] * writes +
+           weight[FC_COST_READS] * reads + weight[FC_COST_READS_WRITES] * (reads + writes) + weight[FC_COST_BYTES] * bytes;
+  }
+
+  double objective(const Clustering &c) const {
+    double v = 0;
+    for (int k = 0; k < kCosts; ++k) if (weight[k] != 0) v += weight[k] * evaluate_cost(m, c, k);
+    return v;
   }
 
   void leaf() {
@@ -114,7 +119,7 @@ struct Search {
     Clustering c;
     std::string err;
     if (derive_and_check(m, pi, c, err) != FC_OK) return;
-    double cost = evaluate_cost(m, c, cost_fn);
+    double cost = objective(c);
     if (cost < best) { best = cost; best_pi = pi; }
     if (stop_at_first) aborted = true;
   }
@@ -190,20 +195,39 @@ struct Search {
 
 }  // namespace
 
+namespace {
+void unit_weights(int cost_fn, double *w) {
+  for (int k = 0; k < kCosts; ++k) w[k] = k == cost_fn ? 1.0 : 0.0;
+}
+}  // namespace
+
 int choose_clustering(const Model &m, int cost_fn, bool split, Clustering &out, int &n_clusters, double &cost,
                       std::string &err) {
   if (cost_fn < FC_COST_CLUSTERS || cost_fn > FC_COST_BYTES) { err = "unknown cost function"; return FC_E_ARG; }
+  double w[kCosts];
+  unit_weights(cost_fn, w);
+  return choose_clustering_weighted(m, w, split, out, n_clusters, cost, err);
+}
+
+int choose_clustering_weighted(const Model &m, const double *weights, bool split, Clustering &out, int &n_clusters,
+                               double &cost, std::string &err) {
+  bool any = false;
+  for (int k = 0; k < kCosts; ++k) {
+    if (!(weights[k] >= 0) || weights[k] > 1e300) { err = "cost weights must be finite and not negative"; return FC_E_ARG; }
+    any = any || weights[k] > 0;
+  }
+  if (!any) { err = "all cost weights are zero"; return FC_E_ARG; }
   int non_input = 0;
   for (int a = 0; a < m.n; ++a) non_input += !m.is_input(a);
   if (non_input > 64) { err = "the exact chooser handles at most 64 combinators"; return FC_E_LIMIT; }
-  Search s(m, cost_fn, 200000000LL);
+  Search s(m, weights, 200000000LL);
   s.go(0);
   if (s.aborted) { err = "search limit reached before optimality was proven"; return FC_E_LIMIT; }
   if (s.best_pi.empty() && non_input > 0) { err = "no feasible clustering"; return FC_E_ILLEGAL_PARTITION; }
   std::vector<int> pi = s.best_pi.empty() ? std::vector<int>(m.n, 0) : s.best_pi;
   int rc = derive_and_check(m, pi, out, err);
   if (rc != FC_OK) return rc;
-  cost = evaluate_cost(m, out, cost_fn);
+  cost = s.objective(out);
   n_clusters = split ? split_components(m, out) : renumber_levels(m, out);
   // the split changes cluster numbers only; re-derive the per-edge and per-node variables
   Clustering again;
@@ -229,8 +253,10 @@ int choose_greedy(const Model &m, int direction, int cost_fn, bool split, Cluste
     return a.b != b.b ? a.b > b.b : a.a > b.a;
   });
   std::vector<std::pair<int, int>> accepted;
+  double w[kCosts];
+  unit_weights(cost_fn, w);
   auto make_search = [&](bool first_only) {
-    Search s(m, cost_fn, 200000000LL);
+    Search s(m, w, 200000000LL);
     for (auto &p : accepted) s.force_together(p.first, p.second);
     s.stop_at_first = first_only;
     return s;

@@ -14,6 +14,12 @@ namespace fc {
 int choose_clustering(const Model &m, int cost_fn, bool split, Clustering &out, int &n_clusters, double &cost,
                       std::string &err);
 
+// The same for a linear combination of the cost functions (section 5.1 names it as the
+// way to cost functions fitted to a machine): weights[k] multiplies cost function k of
+// fc_cost; none negative, not all zero.  `cost` is the weighted sum for the ILP solution.
+int choose_clustering_weighted(const Model &m, const double *weights, bool split, Clustering &out, int &n_clusters,
+                               double &cost, std::string &err);
+
 // The greedy comparison arms of section 5 ("Greedy"): walk the fusible edges from the top
 // (direction 0) or from the bottom (direction 1) of the graph, fuse an edge whenever some
 // legal clustering still fuses it together with the edges taken so far; the result is

@@ -16,6 +16,7 @@ import numpy as np
 import pytest
 
 import paper_2407_13585_amd as fc
+from paper_2407_13585_amd import binding as B
 from oracle import clustering as OC
 from workloads import Graph, build
 from workloads import paper_graphs as PG
@@ -398,3 +399,66 @@ def test_greedy_matches_the_oracle_on_random_graphs(seed):
         got = fc.fc_plan_greedy(g, direction, "reads_writes", no_split=True)
         assert got.cost == pytest.approx(want), (seed, direction)
         assert got.cost >= fc.fc_plan(g, "reads_writes", no_split=True).cost - 1e-9
+
+
+# ------------------------------------------------------------------ linear combinations of cost functions
+def weighted_optimum(g, weights):
+    """Brute force: least weighted sum of the cost functions over all legal clusterings."""
+    best = float("inf")
+    for blocks in OC.legal_partitions(g):
+        v = OC.judge(g, blocks)
+        best = min(best, sum(w * OC.cost(g, blocks, v, k) for k, w in weights.items()))
+    return best
+
+
+WEIGHTS = [{"clusters": 5.0, "bytes": 1e-3}, {"clusters": 1.0, "fused_edges": 0.5, "arrays": 2.0},
+           {"reads": 1.0, "reads_writes": 0.25, "bytes": 1e-4, "clusters": 0.1}, {"bytes": 1.0, "clusters": 1e6}]
+
+
+@pytest.mark.parametrize("name", sorted(PG.ALL))
+def test_weighted_plan_equals_brute_force_on_paper_graphs(name):
+    g = PG.ALL[name]()
+    for w in WEIGHTS:
+        p = fc.fc_plan_weighted(g, w, no_split=True)
+        assert p.cost == pytest.approx(weighted_optimum(g, w)), (name, w)
+        # the reported cost is the weighted sum of the cost functions of the returned clustering
+        vec = fc.cost_vector(g, p.pi)
+        assert p.cost == pytest.approx(sum(w.get(k, 0.0) * vec[i] for k, i in B.COST.items()))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_weighted_plan_equals_brute_force_on_random_graphs(seed):
+    rng = np.random.default_rng(3000 + seed)
+    g = random_graph(rng, int(rng.integers(3, 8)))
+    for w in WEIGHTS:
+        assert fc.fc_plan_weighted(g, w, no_split=True).cost == pytest.approx(weighted_optimum(g, w)), (seed, w)
+
+
+def test_unit_weights_are_the_single_cost_functions_and_bad_weights_are_refused():
+    g = PG.single_loop()
+    for cost in COSTS:
+        assert fc.fc_plan_weighted(g, {cost: 1.0}, no_split=True).cost == pytest.approx(fc.fc_plan(g, cost, no_split=True).cost)
+    for bad in ({"bytes": -1.0}, {"bytes": 0.0}, {"bytes": float("nan")}, {"bytes": float("inf")}):
+        with pytest.raises(fc.FcError):
+            fc.fc_plan_weighted(g, bad)
+    with pytest.raises(ValueError):
+        fc.fc_plan_weighted(g, {"flops": 1.0})
+    # a launch that costs more than any traffic makes the chooser minimise clusters; a free launch, bytes
+    big = PG.greedy_bottom_up_bad(4, 1000)
+    assert fc.fc_plan_weighted(big, {"clusters": 1e12, "bytes": 1.0}).n_clusters == fc.fc_plan(big, "clusters").n_clusters
+    cheap_launch = fc.fc_plan_weighted(big, {"clusters": 1e-12, "bytes": 1.0})
+    assert fc.cost_vector(big, cheap_launch.pi)[B.COST["bytes"]] == pytest.approx(fc.fc_plan(big, "bytes", no_split=True).cost)
+
+
+def test_fit_of_cost_coefficients_recovers_a_linear_model():
+    from paper_2407_13585_amd import tune
+    rng = np.random.default_rng(7)
+    costs = np.zeros((40, len(B.COST)))
+    costs[:, B.COST["clusters"]] = rng.integers(1, 9, 40)
+    costs[:, B.COST["bytes"]] = rng.integers(1, 100, 40) * 1e6
+    costs[:, B.COST["reads"]] = rng.integers(1, 9, 40)          # a column the model does not use
+    times = 6.0 * costs[:, B.COST["clusters"]] + 2e-7 * costs[:, B.COST["bytes"]]
+    w = tune.fit_weights(costs, times * (1 + 0.01 * rng.standard_normal(40)))
+    assert w["clusters"] == pytest.approx(6.0, rel=0.1) and w["bytes"] == pytest.approx(2e-7, rel=0.1)
+    with pytest.raises(ValueError):
+        tune.fit_weights(costs, np.zeros(40))

@@ -211,3 +211,32 @@ def test_diagonal_cluster_two_stores():
     ins = {"as": rng.standard_normal(n).astype(F32)}
     runs = check(g, ins, exact=("bs", "cs"), expect_clusters=1)
     assert runs["fused"].kernels()[0].count("store[") == 2
+
+
+def test_tuned_cost_weights():
+    # section 5.1: a linear combination of cost functions with coefficients found by tuning.
+    # Clusterings of three programs are timed, launch cost and inverse bandwidth fitted, and the
+    # plans of the fitted cost function must run correctly and be about as fast as the best
+    # clustering that was timed.
+    from paper_2407_13585_amd import tune
+    rng = np.random.default_rng(11)
+    programs = []
+    for g in (PG.single_loop(1 << 22), PG.greedy_top_down_bad(1 << 22), PG.greedy_bottom_up_bad(64, 1 << 16)):
+        ins = random_inputs(g, rng, {})
+        if "xs" in ins and g["xs"].shape == (64,):
+            ins["xs"] = (1.0 + rng.uniform(-4.0, 4.0, size=64) / (1 << 16)).astype(F32)
+        programs.append((g, ins))
+    weights, samples = tune.tune(programs, reps=10)
+    assert set(weights) == {"clusters", "bytes"} and all(w >= 0 for w in weights.values()) and weights["bytes"] > 0
+    # between 1 and 20 TB/s, and a launch costs less than 50 us: the coefficients have their physical meaning
+    assert 1e12 < 1e6 / weights["bytes"] < 2e13 and weights["clusters"] < 50.0
+    for k, (g, ins) in enumerate(programs):
+        part = fc().fc_plan_weighted(g, weights)
+        env = evaluate(g, ins)
+        prog = device_program(g, ins, part)
+        prog.run()
+        for name in g.outputs():
+            got, ref = prog.fetch(name).astype(np.float64), np.asarray(env[name], dtype=np.float64)
+            assert np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-30), name
+        best = min(s["us"] for s in samples if s["program"] == k)
+        assert tune.time_partition(g, ins, part, reps=10) <= 1.3 * best + 5.0
