@@ -46,9 +46,11 @@ typedef enum fc_kind {
   FC_GATHER   = 3,  /* ys[j] = src[idx[j]]; arg0 = idx (read in output order), arg1 = src (read in the gather's own order) */
   FC_FOLD     = 4,  /* shape (1): fold of the flattened argument; else fold of the innermost dimension */
   FC_FOLDSEG  = 5,  /* arg0 = flat values, arg1 = offsets[R+1] (infusible); y[r] = fold of values[off[r], off[r+1]) */
-  FC_SCANL    = 6,  /* exclusive prefix combine, identity seeded; traversal order 0 */
+  FC_SCANL    = 6,  /* exclusive prefix combine, identity seeded; traversal order 0; a rank-2 array is scanned row by row */
   FC_SCANR    = 7,  /* exclusive suffix combine; traversal order 1 */
-  FC_SCATTER  = 8,  /* arg0 = dest (infusible, updated in place), arg1 = index, arg2 = value, arg3 = flag (optional) */
+  FC_SCATTER  = 8,  /* arg0 = dest (infusible, updated in place), arg1 = index, arg2 = value, arg3 = flag (optional);
+                       fn = OVERWRITE (kept indices distinct) or ADD (colliding indices combine: exact for i32,
+                       in an unspecified order for f32) */
   FC_FORCE    = 9   /* identity; every edge out of it is infusible */
 } fc_kind;
 
@@ -68,7 +70,8 @@ typedef enum fc_fn {
   FC_FN_ADD3 = 7,         /* (a+b)+c                                     */
   FC_FN_ADD5 = 8,         /* (((a+b)+c)+d)+e                             */
   FC_FN_EXP_NEG = 9,      /* exp(-x)                                     */
-  FC_FN_MOD_EQ = 10,      /* i32 -> i32: (x mod iparam[0] == iparam[1]) ? 1 : 0, x >= 0 */
+  FC_FN_MOD_EQ = 10,      /* i32 -> i32: (x mod iparam[0] == iparam[1]) ? 1 : 0 for x >= 0; iparam[0] > 0;
+                             a residue outside [0, iparam[0]) matches no x */
   /* generate functions (index -> i32) */
   FC_FN_IOTA = 32,            /* i                                                       */
   FC_FN_IOTA_REV = 33,        /* n-1-i                                                   */
