@@ -33,7 +33,7 @@ struct Slot {     // parameters of one combinator node
   float f[2];
   int i[2];       // the node's own integer parameters
   int ext[2];     // the node's own extents (outer, inner); inner is 1 for 1-D arrays
-  unsigned m[3];  // constants the host derives from the parameters (mod_eq_constants)
+  unsigned m[3];  // constants the host derives from the parameters (mod_eq_constants, div_constants)
 };
 
 // x mod k == r for x >= 0 without a division.  With k = 2^s * d, d odd, and
@@ -101,6 +101,22 @@ struct FnModEq { using R = int; static constexpr int kFn = FC_FN_MOD_EQ;
     const unsigned q = __builtin_amdgcn_alignbit(p, p, s.m[1]);     // rotate right
     return ((unsigned)x >= (unsigned)s.i[1] && q <= s.m[2]) ? 1 : 0; } };
 
+// i / d for 0 <= i < 2^31 and a divisor that is fixed for the launch, without a
+// division: with L = ceil(log2 d) and M = ceil(2^(31+L) / d) < 2^32 the quotient is
+// (i * M) >> (31 + L) (division by an invariant integer through multiplication).
+// The index functions divide every element index by a row length; the compiler
+// turns a division by a run-time value into some forty instructions.
+inline void div_constants(Slot &s, int d) {
+  unsigned L = 0;
+  while ((1ull << L) < (unsigned long long)(d > 0 ? d : 1)) ++L;
+  const unsigned long long two = 1ull << (31 + L), dd = (unsigned long long)(d > 0 ? d : 1);
+  s.m[0] = (unsigned)((two + dd - 1) / dd);
+  s.m[1] = 31 + L;
+}
+__device__ __forceinline__ int fast_div(const Slot &s, int i) {
+  return (int)(((unsigned long long)(unsigned)i * s.m[0]) >> s.m[1]);
+}
+
 // element functions whose result is 0 or 1
 template <class E> struct YieldsZeroOne { static constexpr bool value = false; };
 
@@ -112,12 +128,12 @@ struct GenIotaRev { static constexpr int kFn = FC_FN_IOTA_REV;
 struct GenClampShift2D { static constexpr int kFn = FC_FN_CLAMP_SHIFT_2D;
   static __device__ __forceinline__ int apply(const Slot &s, const KArgs &, int i) {
     const int h = s.ext[0], w = s.ext[1];
-    int r = i / w, c = i - r * w;
+    int r = fast_div(s, i), c = i - r * w;
     r = min(max(r + s.i[0], 0), h - 1);
     c = min(max(c + s.i[1], 0), w - 1);
     return r * w + c; } };
 struct GenRowOf2D { static constexpr int kFn = FC_FN_ROW_OF_2D;
-  static __device__ __forceinline__ int apply(const Slot &s, const KArgs &, int i) { return i / s.ext[1]; } };
+  static __device__ __forceinline__ int apply(const Slot &s, const KArgs &, int i) { return fast_div(s, i); } };
 struct GenConst { static constexpr int kFn = FC_FN_CONST_I32;
   static __device__ __forceinline__ int apply(const Slot &s, const KArgs &, int) { return s.i[0]; } };
 

@@ -44,6 +44,7 @@ struct Builder {
     s.i[0] = nd.iparam[0]; s.i[1] = nd.iparam[1];
     s.ext[0] = (int)nd.shape[0]; s.ext[1] = (int)nd.shape[1];
     if (nd.kind == FC_MAP && nd.fn == FC_FN_MOD_EQ) mod_eq_constants(s);
+    if (nd.kind == FC_GENERATE && (nd.fn == FC_FN_CLAMP_SHIFT_2D || nd.fn == FC_FN_ROW_OF_2D)) div_constants(s, s.ext[1]);
     return true;
   }
 
