@@ -60,6 +60,21 @@ unsigned resident_workgroups(void (*kernel)(P...), int threads) {
   return r;
 }
 
+// compute units of the current device (0 if the runtime cannot tell)
+inline int device_compute_units() {
+  static std::mutex mu;
+  static std::map<int, int> known;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = known.find(dev);
+  if (it != known.end()) return it->second;
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+  known[dev] = cus;
+  return cus;
+}
+
 const std::vector<Instance> &registry();
 // first instance with this signature whose accept() (if any) passes
 const Instance *find_instance(const std::string &sig, const KArgs &a);
