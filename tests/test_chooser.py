@@ -11,6 +11,7 @@ Several partitions may tie, so costs are compared, never partitions.
 in prose only); reads is pinned by brute force on the definition alone.
 """
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -33,6 +34,26 @@ def clusters_of(part, graph):
 
 
 # ------------------------------------------------------------------ outcomes the paper states
+def golden_clusterings():
+    rows = []
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_clusterings.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, cost, clusters, where = [x.strip() for x in line.split("|", 3)]
+        rows.append((name, cost, [sorted(c.split()) for c in clusters.split(" / ")], where))
+    return rows
+
+
+@pytest.mark.parametrize("name,cost,want,where", golden_clusterings())
+def test_clusterings_the_paper_states(name, cost, want, where):
+    g = PG.ALL[name]()
+    assert clusters_of(fc.fc_plan(g, cost), g) == want, where
+    # and the brute-force oracle agrees that this clustering is an optimum of that cost function
+    idx = g.index()
+    _, optima = OC.optimum(g, cost)
+    assert sorted(sorted(idx[m] for m in c) for c in want) in [sorted(sorted(b) for b in o) for o in optima], where
+
+
 def test_scatter_example_prefers_fusing_into_the_scatter():
     g = PG.scatter_example()
     legal = OC.legal_partitions(g)
