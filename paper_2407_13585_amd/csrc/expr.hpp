@@ -144,8 +144,11 @@ struct In {
   using R = T;
   static constexpr int kNodes = 1;
   static constexpr bool kMirror = false;
-  template <int Base> static __device__ __forceinline__ T eval(const KArgs &a, int i) {
-    return static_cast<const T *>(a.in[K])[i];
+  // Stream: the element is read once, in order (non-temporal: it does not displace
+  // gathered arrays from the caches); a gather turns it off for its source
+  template <int Base, bool Stream = false> static __device__ __forceinline__ T eval(const KArgs &a, int i) {
+    const T *p = static_cast<const T *>(a.in[K]) + i;
+    return Stream ? __builtin_nontemporal_load(p) : *p;
   }
   template <int Base> static __device__ __forceinline__ Vec4<T> eval4(const KArgs &a, int i) {
     using V = T __attribute__((ext_vector_type(4)));
@@ -166,12 +169,12 @@ struct Map {
   using R = typename F::R;
   static constexpr int kNodes = 1 + (E::kNodes + ... + 0);
   static constexpr bool kMirror = (E::kMirror || ... || false);
-  template <int Base, int... K>
+  template <int Base, bool Stream, int... K>
   static __device__ __forceinline__ R eval_(const KArgs &a, int i, std::integer_sequence<int, K...>) {
-    return F::apply(a.p[Base], E::template eval<ChildBase<Base + 1, K, E...>::value>(a, i)...);
+    return F::apply(a.p[Base], E::template eval<ChildBase<Base + 1, K, E...>::value, Stream>(a, i)...);
   }
-  template <int Base> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
-    return eval_<Base>(a, i, std::make_integer_sequence<int, sizeof...(E)>());
+  template <int Base, bool Stream = false> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
+    return eval_<Base, Stream>(a, i, std::make_integer_sequence<int, sizeof...(E)>());
   }
   template <int Base, int... K>
   static __device__ __forceinline__ Vec4<R> eval4_(const KArgs &a, int i, std::integer_sequence<int, K...>) {
@@ -199,7 +202,7 @@ struct Gen {
   using R = int;
   static constexpr int kNodes = 1;
   static constexpr bool kMirror = false;
-  template <int Base> static __device__ __forceinline__ int eval(const KArgs &a, int i) {
+  template <int Base, bool Stream = false> static __device__ __forceinline__ int eval(const KArgs &a, int i) {
     return G::apply(a.p[Base], a, i);
   }
   template <int Base> static __device__ __forceinline__ Vec4<int> eval4(const KArgs &a, int i) {
@@ -216,7 +219,7 @@ struct AlwaysOne {
   using R = int;
   static constexpr int kNodes = 0;
   static constexpr bool kMirror = false;
-  template <int Base> static __device__ __forceinline__ int eval(const KArgs &, int) { return 1; }
+  template <int Base, bool Stream = false> static __device__ __forceinline__ int eval(const KArgs &, int) { return 1; }
   template <int Base> static __device__ __forceinline__ Vec4<int> eval4(const KArgs &, int) { return Vec4<int>{{1, 1, 1, 1}}; }
   static void sig(std::string &s) { s += "1"; }
 };
@@ -227,8 +230,8 @@ struct Gather {
   using R = typename ES::R;
   static constexpr int kNodes = 1 + EI::kNodes + ES::kNodes;
   static constexpr bool kMirror = EI::kMirror || ES::kMirror;
-  template <int Base> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
-    int j = EI::template eval<Base + 1>(a, i);
+  template <int Base, bool Stream = false> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
+    int j = EI::template eval<Base + 1, Stream>(a, i);
     return ES::template eval<Base + 1 + EI::kNodes>(a, j);
   }
   template <int Base> static __device__ __forceinline__ Vec4<R> eval4(const KArgs &a, int i) {
@@ -256,8 +259,8 @@ struct Gather<Gen<GenIotaRev>, ES> {
   using EI = Gen<GenIotaRev>;
   static constexpr int kNodes = 1 + EI::kNodes + ES::kNodes;
   static constexpr bool kMirror = true;
-  template <int Base> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
-    int j = EI::template eval<Base + 1>(a, i);
+  template <int Base, bool Stream = false> static __device__ __forceinline__ R eval(const KArgs &a, int i) {
+    int j = EI::template eval<Base + 1, Stream>(a, i);
     return ES::template eval<Base + 1 + EI::kNodes>(a, j);
   }
   template <int Base> static __device__ __forceinline__ Vec4<R> eval4(const KArgs &a, int i) {

@@ -61,6 +61,33 @@ template <class Op, class E> hipError_t launch_foldseg(const KArgs &a, const Lau
   if (a.aux == 0) return hipSuccess;
   return launch_k(&foldseg_kernel<Op, E>, grid_for(a.aux, kBlock / 16, kMaxGrid * 8), c.stream, a);
 }
+// ---- column-blocked segmented fold: for tables of more than one and at most four L2s ----
+constexpr size_t kL2Bytes = 4u << 20;                 // L2 of one XCD
+template <int KT> size_t blocked_table_bytes(const KArgs &a) {
+  // the table is the last leaf of Map<F, EV, Gather<EI, In<KT>>>; its slot holds its extents
+  for (int k = kMaxSlots - 1; k >= 0; --k)
+    if (a.p[k].ext[0] != 0) return (size_t)a.p[k].ext[0] * (size_t)a.p[k].ext[1] * 4;
+  return 0;
+}
+template <int KT> bool foldseg_blocked_accept(const KArgs &a) {
+  const size_t table = blocked_table_bytes<KT>(a);
+  const size_t units = ((size_t)a.aux + kBlockedRows - 1) / kBlockedRows;
+  return a.n > 0 && (unsigned long long)a.n * 4 < (1ull << 31) && table > kL2Bytes && table <= kQuarters * kL2Bytes && units >= 64 &&
+         units * kQuarters <= kMaxTiles;
+}
+size_t foldseg_blocked_workspace(const KArgs &a) { return (size_t)kQuarters * (size_t)a.aux * sizeof(unsigned long long); }
+template <class Op, class F, int KV, int KI, int KT>
+hipError_t launch_foldseg_blocked(const KArgs &a, const LaunchCtx &c) {
+  if (!c.workspace) return hipErrorInvalidValue;
+  const unsigned units = ((unsigned)a.aux + kBlockedRows - 1) / kBlockedRows;
+  unsigned grid = resident_grid(&foldseg_blocked_kernel<Op, F, KV, KI, KT>) / 8 * 8;   // whole rounds of the eight XCDs
+  grid = std::max(8u, std::min(grid, units * kQuarters / 8 * 8));
+  const size_t elems = blocked_table_bytes<KT>(a) / 4;
+  const int range_len = (int)(((elems + kQuarters - 1) / kQuarters + 31) / 32 * 32);    // whole 128-byte lines
+  return launch_k(&foldseg_blocked_kernel<Op, F, KV, KI, KT>, grid, c.stream, a, c.ctl, c.partials, c.status,
+                  static_cast<unsigned long long *>(c.workspace), range_len);
+}
+
 template <class EX, class EV, int Mode, bool Reverse = false> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {
   long long tiles = std::max<long long>(1, ((long long)a.n + kScanTile - 1) / kScanTile);
   if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
@@ -230,6 +257,15 @@ std::vector<Instance> build_registry() {
   // ---- fused clusters ----
   r.push_back(fold_<AddF32, ReverseDot>());
   r.push_back(fold_<AddF32, PermGather>());
+  {
+    // SpMV-shaped cluster over a table of one to four L2s: column blocked (first match wins)
+    Instance blocked = foldseg_<AddF32, SpmvTerm>();
+    blocked.launch = &launch_foldseg_blocked<AddF32, FnMul2, 0, 1, 2>;
+    blocked.accept = &foldseg_blocked_accept<2>;
+    blocked.workspace = &foldseg_blocked_workspace;
+    blocked.variant = "column-blocked";
+    r.push_back(blocked);
+  }
   r.push_back(foldseg_<AddF32, SpmvTerm>());
   r.push_back(scan_<ModFlag, I0, kScatter | kCount>());
   r.push_back(scan_<ModFlag, I0, kScatter>());

@@ -239,6 +239,205 @@ __global__ __launch_bounds__(kBlock) void foldseg_kernel(const KArgs a) {
   }
 }
 
+// ------------------------------------------------------------------ segmented fold over a gathered table, column blocked
+// y[r] = fold(+, F(values[k], table[index[k]]) for k in segment r) where the table
+// is too large for the L2 of one XCD (4 MiB) but not for four of them.  Random
+// 4-byte gathers that miss L2 cost a whole request each on the memory side, and
+// the rate of those (about 52 G requests/s on this chip, whatever their size), not
+// bandwidth, bounds the plain kernel; gathers that hit L2 run four times faster.
+// So the table is cut into kQuarters column ranges and every XCD works for one
+// range only: workgroup b takes range b % 4 (workgroups go to the eight XCDs in
+// turn, so XCDs q and q + 4 serve range q and keep it in their L2), reads the whole
+// index and value streams of its rows and accumulates the terms whose index falls
+// into its range.
+//  * The streams must not push the table out of L2 and should cost as few requests
+//    as possible: a unit's stretch of both arrays is read with 128-bit buffer loads
+//    at agent scope (sc1: served by the memory side, not allocated in L2; whole
+//    lines per request; reads past the end of the array return zero).  Measured with
+//    4-byte reads: non-temporal 958 us (27 % of the gathers missed L2), agent scope
+//    800 us.
+//  * A thread keeps the elements it has read in registers, gathers for those whose
+//    index falls into its range -- one gather instruction per element position,
+//    issued for the lanes that have such an element only (the address unit takes a
+//    cycle per lane of a gather, hit or not), all in flight together -- and puts the
+//    terms (the identity for the other ranges) into LDS.  Then sixteen lanes per row
+//    add up the row's terms from LDS.
+//  * The four workgroups 4i .. 4i+3 walk the same units of kBlockedRows rows.  For
+//    unit u the one of range u % 4 combines: the other three pass their partial row
+//    sums through memory (tagged words, then a tagged flag per unit), the combiner
+//    adds the four partials in range order, so the result does not depend on timing.
+//    Combining lags one unit behind, so nobody sits waiting for a partner.
+// The streams are read four times over: 2.1 GB in whole lines instead of 7.5 GB of
+// gathered lines.
+constexpr int kQuarters = 4;
+constexpr int kBlockedRows = kBlock;                  // rows of a unit: one per thread at the exchange
+constexpr int kUnitCap = 4608;                        // elements of a unit staged in LDS (a unit of 16-element rows has 4096)
+constexpr int kUnitVecs = (kUnitCap / kVec + kBlock - 1) / kBlock;   // 128-bit reads per thread and array
+
+template <class Op, class F, int KV, int KI, int KT>
+__global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, Control *ctl, unsigned long long *partials,
+                                                                 unsigned long long *flags, unsigned long long *work, int range_len) {
+  using T = typename Op::T;
+  using Raw = int __attribute__((ext_vector_type(4)));
+  static_assert(sizeof(T) == 4, "partials travel as 32-bit words");
+  __shared__ T sums_of[2][kBlockedRows];            // double buffered: a unit is combined one unit later
+  __shared__ int row_start[kBlockedRows + 1];
+  __shared__ T term_of[kUnitCap];                   // the unit's terms of this range, the identity elsewhere
+  const int *off = static_cast<const int *>(a.in[kMaxIn - 1]);
+  const int *index = static_cast<const int *>(a.in[KI]);
+  const T *values = static_cast<const T *>(a.in[KV]);
+  const T *table = static_cast<const T *>(a.in[KT]);
+  T *y = static_cast<T *>(a.out[0]);
+  const unsigned rows = (unsigned)a.aux;
+  const unsigned n_units = (rows + kBlockedRows - 1) / kBlockedRows;
+  const unsigned q = blockIdx.x % kQuarters, team = blockIdx.x / kQuarters, teams = gridDim.x / kQuarters;
+  const unsigned sub = threadIdx.x & 15u, which = threadIdx.x / 16;
+  const unsigned lo_col = q * (unsigned)range_len;
+  const unsigned epoch = load_agent(&ctl->epoch);
+  const unsigned tag = tag_of_epoch(epoch);
+  // raw buffer views of the two streams: byte offsets, range checked against the array's size
+  const __amdgpu_buffer_rsrc_t index_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(index), 0, a.n * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t value_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(values), 0, a.n * 4, 0x00020000);
+  constexpr int kAgentScope = 0x12;                 // cache policy of the buffer loads: sc1
+
+  // Adds the partials of the four ranges of unit `unit` in range order and stores its rows;
+  // `own` holds this workgroup's partials of that unit.
+  auto combine = [&](unsigned unit, const T *own) {
+    if (threadIdx.x < kQuarters && threadIdx.x != q)
+      (void)wait_word(&flags[(size_t)unit * kQuarters + threadIdx.x], tag, ctl);
+    __syncthreads();
+    const unsigned r = unit * kBlockedRows + threadIdx.x;
+    if (r < rows) {
+      T v = Op::identity();
+#pragma unroll
+      for (unsigned p = 0; p < (unsigned)kQuarters; ++p) {
+        T part = own[threadIdx.x];
+        if (p != q) {
+          // the flags live in the control block, which starts out as zeros, so a flag of this
+          // launch means that the partials have been stored; the tag of each word covers the
+          // case that a word becomes visible after its flag
+          const unsigned long long w = wait_word(work + (size_t)p * rows + r, tag, ctl);
+          part = w ? from_bits<T>((int)(unsigned)(w >> 32)) : Op::identity();
+        }
+        v = Op::apply(v, part);
+      }
+      y[r] = v;
+    }
+  };
+
+  unsigned iter = 0, prev = ~0u;
+  for (unsigned u = team; u < n_units; u += teams, ++iter) {
+    T *sums = sums_of[iter & 1];
+    // the unit's row offsets, read once and coalesced (rows past the end are empty)
+    {
+      const unsigned r = u * kBlockedRows + threadIdx.x;
+      // agent scope, like the streams: nothing but the table should settle in L2
+      const unsigned *offu = reinterpret_cast<const unsigned *>(off);
+      row_start[threadIdx.x] = (int)load_agent(offu + (r < rows ? r : rows));
+      if (threadIdx.x == 0)
+        row_start[kBlockedRows] = (int)load_agent(offu + (u * kBlockedRows + kBlockedRows < rows ? u * kBlockedRows + kBlockedRows : rows));
+    }
+    __syncthreads();
+    // the unit's stretch of both streams, from the 16-byte boundary below its first element:
+    // read, gather, multiply, and leave the terms in LDS
+    const int base = row_start[0] & ~(kVec - 1);
+    const int staged = min(row_start[kBlockedRows] - base, kUnitCap);
+    {
+      Raw ci[kUnitVecs], cv[kUnitVecs];
+#pragma unroll
+      for (int i = 0; i < kUnitVecs; ++i) {
+        const int e = ((int)threadIdx.x + i * kBlock) * kVec;
+        ci[i] = Raw{-1, -1, -1, -1};                 // -1 is in no range
+        cv[i] = Raw{0, 0, 0, 0};
+        if (e < staged) {
+          ci[i] = __builtin_amdgcn_raw_buffer_load_b128(index_buf, (base + e) * 4, 0, kAgentScope);
+          cv[i] = __builtin_amdgcn_raw_buffer_load_b128(value_buf, (base + e) * 4, 0, kAgentScope);
+        }
+      }
+      // the values wait in LDS (where the terms will stand) while the gathers are in flight:
+      // fewer registers per thread, more workgroups per compute unit
+#pragma unroll
+      for (int i = 0; i < kUnitVecs; ++i) {
+        const int e = ((int)threadIdx.x + i * kBlock) * kVec;
+        if (e < staged) *reinterpret_cast<Raw *>(&term_of[e]) = cv[i];
+      }
+      // which of this thread's elements fall into the range: one bit each, tested once
+      unsigned mine = 0;
+#pragma unroll
+      for (int i = 0; i < kUnitVecs; ++i)
+#pragma unroll
+        for (int c = 0; c < kVec; ++c) mine |= (unsigned)((unsigned)ci[i][c] - lo_col < (unsigned)range_len) << (i * kVec + c);
+      T x[kUnitVecs][kVec];
+#pragma unroll
+      for (int i = 0; i < kUnitVecs; ++i)
+#pragma unroll
+        for (int c = 0; c < kVec; ++c) {
+          x[i][c] = Op::identity();
+          if (mine >> (i * kVec + c) & 1u) x[i][c] = table[ci[i][c]];
+        }
+#pragma unroll
+      for (int i = 0; i < kUnitVecs; ++i) {
+        const int e = ((int)threadIdx.x + i * kBlock) * kVec;
+        if (e < staged) {
+          using TV = T __attribute__((ext_vector_type(4)));
+          const TV v = *reinterpret_cast<const TV *>(&term_of[e]);        // this thread's own store above
+          Vec4<T> t;
+#pragma unroll
+          for (int c = 0; c < kVec; ++c)
+            t.v[c] = (mine >> (i * kVec + c) & 1u) ? F::apply(a.p[0], v[c], x[i][c]) : Op::identity();
+          store4(&term_of[e], t);
+        }
+      }
+    }
+    __syncthreads();
+    // four lanes per row add up its terms (64 rows at a time), then the quad combines; a
+    // unit with more than kUnitCap elements takes the rest from memory
+    constexpr int kRowsPerStep4 = kBlock / 4;
+    const unsigned ql = threadIdx.x & 3u;
+    for (unsigned step = 0; step < kBlockedRows / kRowsPerStep4; ++step) {
+      const unsigned local = step * kRowsPerStep4 + threadIdx.x / 4;
+      const int lo = row_start[local], hi = row_start[local + 1];
+      T acc = Op::identity();
+      for (int k = lo + (int)ql; k < hi; k += 4) {
+        const int e = k - base;
+        if (e < kUnitCap) {
+          acc = Op::apply(acc, term_of[e]);
+        } else {
+          const int c = In<KI, int>::template eval<0, true>(a, k);
+          if ((unsigned)c - lo_col < (unsigned)range_len)
+            acc = Op::apply(acc, F::apply(a.p[0], In<KV, T>::template eval<0, true>(a, k), table[c]));
+        }
+      }
+      acc = Op::apply(acc, dpp_move<0xB1>(Op::identity(), acc));    // quad_perm [1,0,3,2]
+      acc = Op::apply(acc, dpp_move<0x4E>(Op::identity(), acc));    // quad_perm [2,3,0,1]
+      if (ql == 0) sums[local] = acc;
+    }
+    __syncthreads();
+    // The workgroup of range u % 4 combines unit u; the other three publish their partials:
+    // every partial as a tagged word (value and tag travel in one 64-bit store, so a reader
+    // can tell a word of this launch from whatever lay there before), then, once the stores
+    // of all threads are out, the unit's flag.
+    if (q != u % kQuarters) {
+      const unsigned r = u * kBlockedRows + threadIdx.x;
+      if (r < rows) store_agent64(work + (size_t)q * rows + r, pack_word((unsigned)as_bits(sums[threadIdx.x]), tag, 1u));
+      __syncthreads();
+      if (threadIdx.x == 0) store_agent64(&flags[(size_t)u * kQuarters + q], pack_word(1u, tag, 1u));
+    }
+    // Combining lags one unit behind: by now the partials of the previous unit have long
+    // been published, so the combiner does not sit waiting for its three partners.
+    if (prev != ~0u && q == prev % kQuarters) combine(prev, sums_of[(iter & 1) ^ 1]);
+    prev = u;
+  }
+  if (prev != ~0u && q == prev % kQuarters) combine(prev, sums_of[(iter & 1) ^ 1]);
+  // every workgroup has taken its tag once its word is out; the last one then moves the epoch on
+  if (threadIdx.x == 0) store_agent64(&partials[blockIdx.x], pack_word(0u, tag, 1u));
+  if (blockIdx.x == gridDim.x - 1) {
+    for (unsigned k = threadIdx.x; k < gridDim.x; k += kBlock) (void)wait_word(&partials[k], tag, ctl);
+    __syncthreads();
+    if (threadIdx.x == 0) store_agent(&ctl->epoch, epoch + 1u);
+  }
+}
+
 // ------------------------------------------------------------------ single-pass scan / compaction
 // Exclusive (+) scan of the int32 stream EX in one pass over the data (section
 // 2: a scan inside a cluster must be a single pass; the chained scan is one of

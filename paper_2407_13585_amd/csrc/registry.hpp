@@ -22,6 +22,7 @@ struct LaunchCtx {
   unsigned long long *partials;             // DEVICE: per-workgroup partial results of a fold
   unsigned long long *status;     // DEVICE: tile status words of the single-pass scan
   size_t max_tiles;
+  void *workspace;                // DEVICE: what Instance::workspace asked for (256-byte aligned), or NULL
 };
 
 using Launcher = hipError_t (*)(const KArgs &, const LaunchCtx &);
@@ -31,6 +32,7 @@ struct Instance {
   Launcher launch;
   bool (*accept)(const KArgs &) = nullptr;   // extra conditions on parameters / extents
   const char *variant = "";                  // distinguishes instances that share a signature
+  size_t (*workspace)(const KArgs &) = nullptr;   // bytes of scratch beyond the control block a launch needs
 };
 
 // Workgroups of `threads` threads of a kernel that are resident on the current

@@ -265,12 +265,24 @@ std::vector<std::vector<int>> clusters_of(const Model &m, const Clustering &c) {
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// the clusters run one after the other, so they share one workspace: the largest any of them asks for
+static size_t workspace_bytes_for(const Model &m, const Clustering &c) {
+  size_t most = 0;
+  for (const auto &members : clusters_of(m, c)) {
+    ClusterLaunch cl;
+    std::string err;
+    if (plan_cluster(m, c, members, cl, err) != FC_OK || cl.kind != ClusterLaunch::Kernel || !cl.instance->workspace) continue;
+    most = std::max(most, cl.instance->workspace(cl.args));
+  }
+  return most;
+}
+
 size_t scratch_bytes_for(const Model &m, const Clustering &c) {
   size_t total = FC_SCRATCH_CONTROL_BYTES;
   for (int a = 0; a < m.n; ++a)
     if (!m.is_input(a) && !c.fused_away[a] && m.nodes[a].kind != FC_SCATTER && m.nodes[a].kind != FC_FORCE)
       total += align_up(std::max<size_t>((size_t)m.bytes(a), 4), 256);
-  return total;
+  return total + align_up(workspace_bytes_for(m, c), 256);
 }
 
 int prepare_run(PreparedRun &r, std::string &err) {
@@ -330,6 +342,8 @@ int run_prepared(const PreparedRun &r, const fc_buffer *bufs, void *scratch, siz
   ctx.partials = reinterpret_cast<unsigned long long *>(static_cast<char *>(scratch) + kPartialsOffset);
   ctx.status = reinterpret_cast<unsigned long long *>(static_cast<char *>(scratch) + kStatusOffset);
   ctx.max_tiles = kMaxTiles;
+  // what is left of scratch after the intermediates is the clusters' common workspace
+  const size_t workspace_at = align_up(cursor, 256);
 
   for (ClusterLaunch cl : r.launches) {
     if (cl.kind == ClusterLaunch::Alias) {
@@ -350,6 +364,12 @@ int run_prepared(const PreparedRun &r, const fc_buffer *bufs, void *scratch, siz
         cl.args.out[k] = ptr[cl.out_nodes[k]];
         if (!cl.args.out[k]) { err = "array " + std::to_string(cl.out_nodes[k]) + " has no buffer"; return FC_E_UNBOUND; }
       }
+    ctx.workspace = nullptr;
+    if (cl.instance->workspace) {
+      const size_t need = cl.instance->workspace(cl.args);
+      if (workspace_at + need > scratch_bytes) { err = "scratch too small for the workspace of " + cl.sig; return FC_E_SCRATCH; }
+      ctx.workspace = static_cast<char *>(scratch) + workspace_at;
+    }
     hipError_t e = cl.instance->launch(cl.args, ctx);
     if (e != hipSuccess) {
       int count = -1, dev = -1;

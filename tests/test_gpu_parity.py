@@ -174,6 +174,36 @@ def test_spmv_skewed_rows():
     run_all_modes(3, C.spmv(lengths=lengths, seed=78, ncols=5000))
 
 
+@pytest.mark.parametrize("rows,ncols,mean_len", [(20000, 1200000, 8.0), (16384 + 77, (1 << 22) - 5, 5.0),
+                                                  (70001, 3000001, 3.0)])
+def test_spmv_column_blocked(rows, ncols, mean_len):
+    # a gathered table of more than one and at most four L2s takes the column-blocked kernel:
+    # four workgroups per unit of 256 rows, partial row sums handed over through memory.
+    # Row counts off the unit size, empty rows, a table that is not a multiple of the range.
+    rng = np.random.default_rng(rows)
+    lengths = rng.poisson(mean_len, size=rows)
+    lengths[rng.integers(0, rows, size=rows // 50)] = 0
+    lengths[rng.integers(0, rows, size=20)] = 3000            # a few long rows
+    w = C.spmv(lengths=lengths, seed=rows + 1, ncols=ncols)
+    env = evaluate(w.graph, w.inputs)
+    g, part = plan(w.graph, False)
+    prog = device_program(g, w.inputs, part)
+    assert "column-blocked" in prog.kernels()[0], prog.kernels()
+    for k in range(3):                                        # flags and workspace are reused launch after launch
+        if k:
+            # other values every time: a partial row sum left over from the launch before
+            # would now be a wrong one
+            w.inputs["vals"] = rng.uniform(-1.0, 1.0, size=w.inputs["vals"].shape).astype(F32)
+            w.inputs["x"] = rng.uniform(-1.0, 1.0, size=w.inputs["x"].shape).astype(F32)
+            prog.upload("vals", w.inputs["vals"])
+            prog.upload("x", w.inputs["x"])
+            env = evaluate(w.graph, w.inputs)
+        prog.run()
+        compare(3, w, env, prog, w.graph.outputs(), "column-blocked")
+        assert prog.control_words()[1] == 0
+    run_all_modes(3, w, env)
+
+
 @pytest.mark.parametrize("hw", [(1, 4), (1, 8), (2, 4), (3, 3), (1, 1), (5, 7), (33, 248), (34, 252), (64, 256),
                                 (65, 1000), (7, 1004), (100, 2048), (31, 996)])
 def test_stencil_shapes(hw):
