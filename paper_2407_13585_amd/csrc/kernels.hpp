@@ -242,9 +242,9 @@ __global__ __launch_bounds__(kBlock) void foldseg_kernel(const KArgs a) {
 // ------------------------------------------------------------------ segmented fold over a gathered table, column blocked
 // y[r] = fold(+, F(values[k], table[index[k]]) for k in segment r) where the table
 // is too large for the L2 of one XCD (4 MiB) but not for four of them.  Random
-// 4-byte gathers that miss L2 cost a whole request each on the memory side, and
-// the rate of those (about 52 G requests/s on this chip, whatever their size), not
-// bandwidth, bounds the plain kernel; gathers that hit L2 run four times faster.
+// 4-byte gathers that miss L2 cost a 128-byte line each from the memory side, and
+// the rate of those (about 52 G lines/s on this chip: its bandwidth in lines) bounds
+// the plain kernel; gathers that hit L2 run four times faster.
 // So the table is cut into kQuarters column ranges and every XCD works for one
 // range only: workgroup b takes range b % 4 (workgroups go to the eight XCDs in
 // turn, so XCDs q and q + 4 serve range q and keep it in their L2), reads the whole
@@ -252,23 +252,27 @@ __global__ __launch_bounds__(kBlock) void foldseg_kernel(const KArgs a) {
 // into its range.
 //  * The streams must not push the table out of L2 and should cost as few requests
 //    as possible: a unit's stretch of both arrays is read with 128-bit buffer loads
-//    at agent scope (sc1: served by the memory side, not allocated in L2; whole
-//    lines per request; reads past the end of the array return zero).  Measured with
-//    4-byte reads: non-temporal 958 us (27 % of the gathers missed L2), agent scope
-//    800 us.
+//    marked agent scope and non-temporal (sc1 nt: whole lines per request, not kept
+//    in L2; reads past the end of the array return zero).  Measured: 4-byte
+//    non-temporal reads 958 us, 27 % of the gathers missing L2; 128-bit reads with
+//    sc1 alone 35 % missing, with sc1 nt 16 %.
 //  * A thread keeps the elements it has read in registers, gathers for those whose
 //    index falls into its range -- one gather instruction per element position,
 //    issued for the lanes that have such an element only (the address unit takes a
 //    cycle per lane of a gather, hit or not), all in flight together -- and puts the
-//    terms (the identity for the other ranges) into LDS.  Then sixteen lanes per row
-//    add up the row's terms from LDS.
+//    terms (the identity for the other ranges) into LDS.  Then four lanes per row add
+//    up the row's terms from LDS.  Every element is looked at by four workgroups, so
+//    the arithmetic per element counts: the range test is done once per element and
+//    kept as a bit, and the row sums take two DPP steps per 64 rows (sixteen lanes per
+//    row and a row scan took 880 us, this form 745 us).
 //  * The four workgroups 4i .. 4i+3 walk the same units of kBlockedRows rows.  For
 //    unit u the one of range u % 4 combines: the other three pass their partial row
 //    sums through memory (tagged words, then a tagged flag per unit), the combiner
 //    adds the four partials in range order, so the result does not depend on timing.
 //    Combining lags one unit behind, so nobody sits waiting for a partner.
-// The streams are read four times over: 2.1 GB in whole lines instead of 7.5 GB of
-// gathered lines.
+// The streams are read four times over: 2.1 GB in whole lines, and 1.3 GB of gathered
+// lines that still miss (the quarter is as large as the L2 it should stay in), instead
+// of 7.5 GB.
 constexpr int kQuarters = 4;
 constexpr int kBlockedRows = kBlock;                  // rows of a unit: one per thread at the exchange
 constexpr int kUnitCap = 4608;                        // elements of a unit staged in LDS (a unit of 16-element rows has 4096)
@@ -291,14 +295,13 @@ __global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, 
   const unsigned rows = (unsigned)a.aux;
   const unsigned n_units = (rows + kBlockedRows - 1) / kBlockedRows;
   const unsigned q = blockIdx.x % kQuarters, team = blockIdx.x / kQuarters, teams = gridDim.x / kQuarters;
-  const unsigned sub = threadIdx.x & 15u, which = threadIdx.x / 16;
   const unsigned lo_col = q * (unsigned)range_len;
   const unsigned epoch = load_agent(&ctl->epoch);
   const unsigned tag = tag_of_epoch(epoch);
   // raw buffer views of the two streams: byte offsets, range checked against the array's size
   const __amdgpu_buffer_rsrc_t index_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(index), 0, a.n * 4, 0x00020000);
   const __amdgpu_buffer_rsrc_t value_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(values), 0, a.n * 4, 0x00020000);
-  constexpr int kAgentScope = 0x12;                 // cache policy of the buffer loads: sc1
+  constexpr int kAgentScope = 0x12;                 // cache policy of the buffer loads: sc1 | nt
 
   // Adds the partials of the four ranges of unit `unit` in range order and stores its rows;
   // `own` holds this workgroup's partials of that unit.
