@@ -192,7 +192,8 @@ int fc_duplicate(const fc_graph *g, fc_node *out_nodes, int32_t capacity, int32_
 /* ---------------------------------------------------------------- execution (device work) */
 
 /* Bytes of device scratch fc_run_* needs for this graph and clustering
- * (p == NULL: the unfused clustering). */
+ * (p == NULL: the unfused clustering): the control block, the manifest
+ * intermediates, and the workspace of the cluster kernel that asks for the most. */
 int fc_scratch_bytes(const fc_graph *g, const fc_partition *p, size_t *bytes);
 
 /* Execute the program cluster by cluster, one kernel launch per cluster, on
