@@ -132,6 +132,40 @@ def test_scratch_bytes_and_kernel_names():
     assert not trivial.fused_away.any()
 
 
+def test_workspace_of_the_column_blocked_segmented_fold_is_part_of_scratch():
+    # graph only, no data: an SpMV-shaped cluster over a 6 MiB table takes the column-blocked
+    # kernel, which hands partial row sums over through 32 bytes of scratch per row
+    rows, ncols, nnz = 100000, 1500000, 800000
+    g = Graph()
+    g.add("x", "input", "f32", (ncols,))
+    g.add("col", "input", "i32", (nnz,))
+    g.add("vals", "input", "f32", (nnz,))
+    g.add("off", "input", "i32", (rows + 1,))
+    g.add("g", "gather", "f32", (nnz,), args=("col", "x"))
+    g.add("p", "map", "f32", (nnz,), fn="mul2", args=("vals", "g"))
+    g.add("y", "foldseg", "f32", (rows,), fn="add", args=("p", "off"), output=True)
+    part = fc.fc_plan(g, "bytes")
+    assert part.n_clusters == 1 and "column-blocked" in fc.fc_cluster_kernel(g, part, 0)
+    need = fc.fc_scratch_bytes(g, part)
+    assert need >= B.FC_SCRATCH_CONTROL_BYTES + 32 * rows
+    fake = (0x10000000, 1 << 30)
+    bufs = {n.name: fake for n in g.nodes if n.kind == "input" or n.output}
+    expect("FC_E_SCRATCH", fc.fc_run_fused, g, part, bufs, (0x10000000, B.FC_SCRATCH_CONTROL_BYTES + 32 * rows - 256))
+    # a table that fits one L2 keeps the plain kernel and needs no workspace
+    g2 = Graph()
+    g2.add("x", "input", "f32", (1000,))
+    g2.add("col", "input", "i32", (nnz,))
+    g2.add("vals", "input", "f32", (nnz,))
+    g2.add("off", "input", "i32", (rows + 1,))
+    g2.add("g", "gather", "f32", (nnz,), args=("col", "x"))
+    g2.add("p", "map", "f32", (nnz,), fn="mul2", args=("vals", "g"))
+    g2.add("y", "foldseg", "f32", (rows,), fn="add", args=("p", "off"), output=True)
+    part2 = fc.fc_plan(g2, "bytes")
+    assert "column-blocked" not in fc.fc_cluster_kernel(g2, part2, 0)
+    # (the figure allows for an output the caller leaves unbound, nothing more)
+    assert fc.fc_scratch_bytes(g2, part2) == need - 32 * rows
+
+
 def test_duplicate_keeps_program_meaning():
     from oracle.interp import evaluate
     for cfg in (1, 5):
