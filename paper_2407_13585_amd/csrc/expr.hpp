@@ -306,4 +306,42 @@ template <class EI, class ES> struct KeepLoads<Gather<EI, ES>> {
   using type = Gather<typename KeepLoads<EI>::type, typename KeepLoads<ES>::type>;
 };
 
+// GatherChain<E> describes an element program that is a chain of one-argument maps over one
+// gather whose index is an external array read in order and whose source is again a chain of
+// one-argument maps over one external array (the table).  Its value at a position depends on
+// the index found there and on nothing else, which lets a commutative consumer visit the
+// positions in any order.  leaf() reads the table, from_leaf<Base>() applies the maps to what
+// was read, so a kernel can issue many table reads before it uses the first.
+template <class E> struct GatherChain;            // only the shapes below
+template <int K, class T> struct GatherChain<In<K, T>> {
+  using Leaf = T;
+  static constexpr int kTable = K;
+  static constexpr int kIndex = -1;               // no gather at or below this node
+  template <int Base> static constexpr int source_slot() { return -1; }
+  static __device__ __forceinline__ T leaf(const KArgs &a, int j) { return static_cast<const T *>(a.in[K])[j]; }
+  template <int Base> static __device__ __forceinline__ T from_leaf(const KArgs &, T x) { return x; }
+};
+template <class F, class E0> struct GatherChain<Map<F, E0>> {
+  using Inner = GatherChain<E0>;
+  using Leaf = typename Inner::Leaf;
+  static constexpr int kTable = Inner::kTable;
+  static constexpr int kIndex = Inner::kIndex;
+  template <int Base> static constexpr int source_slot() { return Inner::template source_slot<Base + 1>(); }
+  static __device__ __forceinline__ Leaf leaf(const KArgs &a, int j) { return Inner::leaf(a, j); }
+  template <int Base> static __device__ __forceinline__ typename F::R from_leaf(const KArgs &a, Leaf x) {
+    return F::apply(a.p[Base], Inner::template from_leaf<Base + 1>(a, x));
+  }
+};
+template <int KI, class ES> struct GatherChain<Gather<In<KI, int>, ES>> {
+  using Inner = GatherChain<ES>;
+  using Leaf = typename Inner::Leaf;
+  static constexpr int kTable = Inner::kTable;
+  static constexpr int kIndex = KI;
+  template <int Base> static constexpr int source_slot() { return Base + 2; }     // gather, its index, then its source
+  static __device__ __forceinline__ Leaf leaf(const KArgs &a, int j) { return Inner::leaf(a, j); }
+  template <int Base> static __device__ __forceinline__ typename ES::R from_leaf(const KArgs &a, Leaf x) {
+    return Inner::template from_leaf<Base + 2>(a, x);
+  }
+};
+
 }  // namespace fc

@@ -88,6 +88,36 @@ hipError_t launch_foldseg_blocked(const KArgs &a, const LaunchCtx &c) {
                   static_cast<unsigned long long *>(c.workspace), range_len);
 }
 
+// ---- fold over a gathered table of one to sixteen L2s: indices sorted by table range first ----
+template <class E> size_t binned_table_elems(const KArgs &a) {
+  constexpr int slot = GatherChain<E>::template source_slot<0>();
+  return (size_t)a.p[slot].ext[0] * (size_t)a.p[slot].ext[1];
+}
+inline size_t binned_tiles(const KArgs &a) { return ((size_t)(a.n & ~3) + kBinTile - 1) / kBinTile; }
+inline size_t binned_counts_bytes(const KArgs &a) { return (binned_tiles(a) * kBins * sizeof(int) + 255) / 256 * 256; }
+template <class E> bool fold_binned_accept(const KArgs &a) {
+  const size_t bytes = binned_table_elems<E>(a) * 4;
+  // ranges of at most half an L2; below two million positions the direct kernel is over
+  // before two launches would be
+  return a.n >= (1 << 21) && bytes > kL2Bytes && bytes <= kBins * (kL2Bytes / 2) &&
+         binned_tiles(a) * kBins * kBinCap * sizeof(int) < (1ull << 31);
+}
+size_t fold_binned_workspace(const KArgs &a) { return binned_counts_bytes(a) + binned_tiles(a) * kBins * kBinCap * sizeof(int); }
+template <class Op, class E> hipError_t launch_fold_binned(const KArgs &a, const LaunchCtx &c) {
+  if (!c.workspace) return hipErrorInvalidValue;
+  const unsigned tiles = (unsigned)binned_tiles(a);
+  int *counts = static_cast<int *>(c.workspace);
+  int *entries = reinterpret_cast<int *>(static_cast<char *>(c.workspace) + binned_counts_bytes(a));
+  const size_t range_len = (binned_table_elems<E>(a) + kBins - 1) / kBins;
+  const unsigned inv_range = (unsigned)(((1ull << 32) + range_len - 1) / range_len);
+  const unsigned first = std::min(tiles, std::min<unsigned>(resident_grid(&bin_indices_kernel<Op, E>), kMaxPartials / 2));
+  hipError_t e = launch_k(&bin_indices_kernel<Op, E>, first, c.stream, a, c.ctl, c.partials, counts, entries, tiles, inv_range);
+  if (e != hipSuccess) return e;
+  const unsigned second = std::max(8u, std::min<unsigned>(resident_grid(&fold_binned_kernel<Op, E>), kMaxPartials / 2) / 8 * 8);
+  return launch_k(&fold_binned_kernel<Op, E>, second, c.stream, a, c.ctl, c.partials, static_cast<const int *>(counts),
+                  static_cast<const int *>(entries), tiles, first);
+}
+
 template <class EX, class EV, int Mode, bool Reverse = false> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {
   long long tiles = std::max<long long>(1, ((long long)a.n + kScanTile - 1) / kScanTile);
   if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
@@ -256,6 +286,15 @@ std::vector<Instance> build_registry() {
   r.push_back(scatter_<I0, F1, I2>());
   // ---- fused clusters ----
   r.push_back(fold_<AddF32, ReverseDot>());
+  {
+    // the gathered table does not fit one L2: indices binned by table range first (first match wins)
+    Instance binned = fold_<AddF32, PermGather>();
+    binned.launch = &launch_fold_binned<AddF32, PermGather>;
+    binned.accept = &fold_binned_accept<PermGather>;
+    binned.workspace = &fold_binned_workspace;
+    binned.variant = "binned";
+    r.push_back(binned);
+  }
   r.push_back(fold_<AddF32, PermGather>());
   {
     // SpMV-shaped cluster over a table of one to four L2s: column blocked (first match wins)

@@ -141,20 +141,22 @@ __global__ __launch_bounds__(kBlock) void store2_kernel(const KArgs a) {
 // reduction, one partial per workgroup; the workgroup that finishes last
 // combines the partials in index order, so the result does not depend on
 // scheduling.  fold is one stage of a multi-stage parallel reduction (section 2, fold).
+// `earlier` partials, at the front of `partials`, were left there under the same tag
+// by a kernel that ran before this one on the stream; they are combined first.
 template <class Op>
 __device__ __forceinline__ void fold_finish(typename Op::T acc, const KArgs &a, int out_slot, Control *ctl,
-                                            unsigned long long *partials) {
+                                            unsigned long long *partials, unsigned earlier = 0) {
   using T = typename Op::T;
   __shared__ T lds[kWavesPerBlock + 1];
   const unsigned epoch = load_agent(&ctl->epoch);
   const unsigned tag = tag_of_epoch(epoch);
   T r = block_reduce<Op>(acc, lds);
-  if (threadIdx.x == 0) store_agent64(&partials[blockIdx.x], pack_word((unsigned)as_bits(r), tag, 1u));
+  if (threadIdx.x == 0) store_agent64(&partials[earlier + blockIdx.x], pack_word((unsigned)as_bits(r), tag, 1u));
   // the workgroup with the highest index is dispatched last; it waits for the
   // partials of all others and combines them in index order
   if (blockIdx.x == gridDim.x - 1) {
     T s = Op::identity();
-    for (unsigned k = threadIdx.x; k < gridDim.x; k += kBlock) {
+    for (unsigned k = threadIdx.x; k < earlier + gridDim.x; k += kBlock) {
       unsigned long long w = wait_word(&partials[k], tag, ctl);
       s = Op::apply(s, w ? from_bits<T>((int)(unsigned)(w >> 32)) : Op::identity());
     }
@@ -211,6 +213,211 @@ __global__ __launch_bounds__(kBlock) void store_fold_kernel(const KArgs a, Contr
     acc = Op::apply(acc, EF::template eval<ES::kNodes>(a, i));
   }
   fold_finish<Op>(acc, a, 1, ctl, partials);
+}
+
+// ------------------------------------------------------------------ fold over a gathered table, indices binned first
+// r = fold(Op, f(table[index[i]])) for a table of more than one L2 (4 MiB per XCD) and
+// indices in no particular order.  Read directly, nearly every gather misses L2 and costs
+// a 128-byte line from the memory side, whose rate (about 52 G lines/s on this chip) then
+// bounds the kernel; gathers that hit L2 run four times faster.  A fold with a commutative
+// operator may visit the positions in any order (the order of evaluation inside a fold is
+// not part of its meaning: section 2, fold), and this element program depends on a
+// position only through the index found there.  So the launch takes two kernels:
+//
+//  1. bin_indices_kernel cuts the table into kBins ranges and sorts every tile of
+//     kBinTile indices by range.  The entries of (range, tile) go to a slot of kBinCap
+//     words at a fixed place, their number to counts[range][tile]: no workgroup waits
+//     for another.  Uniformly spread indices put kBinTile / kBins = 256 entries into a
+//     slot, give or take 16; the few that a slot cannot take are evaluated on the spot.
+//  2. fold_binned_kernel: every XCD takes the ranges r with r % 8 equal to its number,
+//     one after the other, and reads all slots of the range.  Its gathers go to one
+//     range of at most half an L2 and hit (with ranges of a whole L2 a third of them
+//     still missed); the slots are read past L2 (agent scope, read once), so that they
+//     do not displace the table.
+//
+// The indices are read once and written and read once more as entries: three times their
+// bytes instead of a line of 128 bytes for each.
+constexpr int kBins = 32;
+constexpr int kBinItems = 16;                          // indices per thread and pass
+constexpr int kBinPasses = 2;                          // passes of kBlock * kBinItems indices that fill one tile's slots
+constexpr int kBinPass = kBlock * kBinItems;
+constexpr int kBinTile = kBinPass * kBinPasses;
+constexpr int kBinGroups = 5;                          // a slot holds this many entries per lane of the wave that reads it
+constexpr int kBinCap = kBinGroups * kWave;            // 320 = 256 + 4 standard deviations of a uniform spread
+static_assert(kBins <= kWave, "one thread of the first wave per range");
+
+// range of table position `j`: j / range_len, as a multiplication (the host passes
+// ceil(2^32 / range_len)); a quotient that comes out one too high at a boundary only
+// moves the boundary, the same for every position.  Positions outside the table land
+// in the last range.
+__device__ __forceinline__ unsigned bin_of(int j, unsigned inv_range) {
+  const unsigned b = __umulhi((unsigned)j, inv_range);
+  return b < kBins ? b : kBins - 1;
+}
+
+template <class Op, class E>
+__global__ __launch_bounds__(kBlock) void bin_indices_kernel(const KArgs a, Control *ctl, unsigned long long *partials,
+                                                             int *counts, int *entries, unsigned tiles, unsigned inv_range) {
+  using T = typename Op::T;
+  using C = GatherChain<E>;
+  using Index = In<C::kIndex, int>;
+  __shared__ unsigned wave_count[kWavesPerBlock][kBins];
+  __shared__ unsigned wave_first[kWavesPerBlock][kBins];   // start of a wave's elements of a range in `staged`
+  __shared__ unsigned range_first[kBins];                   // start of a range in `staged`
+  __shared__ unsigned range_count[kBins];                   // elements of a range in this pass
+  __shared__ unsigned slot_filled[kBins];                   // entries of the tile's slot before this pass
+  __shared__ int staged[kBinPass];                          // the indices of a pass, sorted by range
+  __shared__ T lds[kWavesPerBlock + 1];
+  const unsigned n = (unsigned)a.n, n4 = n & ~3u;
+  const unsigned wave = (unsigned)wave_id(), lane = (unsigned)lane_id();
+  constexpr unsigned kNone = 0xffu;                    // range of a position past the end
+  T acc = Op::identity();
+  for (unsigned tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    unsigned filled = 0;                               // thread b < kBins: entries in slot (b, tile) so far
+    for (unsigned pass = 0; pass < (unsigned)kBinPasses; ++pass) {
+      const unsigned first = tile * kBinTile + pass * kBinPass;
+      const unsigned base = first + threadIdx.x * kVec;
+      int index[kBinItems];
+      unsigned range[kBinItems], rank[kBinItems];
+      if (first + kBinPass <= n4) {
+#pragma unroll
+        for (int u = 0; u < kBinItems / kVec; ++u) {
+          Vec4<int> v = Index::template eval4<0>(a, (int)(base + u * (kBlock * kVec)));
+#pragma unroll
+          for (int c = 0; c < kVec; ++c) { index[u * kVec + c] = v.v[c]; range[u * kVec + c] = bin_of(v.v[c], inv_range); }
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < kBinItems / kVec; ++u) {
+          const unsigned i = base + u * (kBlock * kVec);
+          Vec4<int> v = {{0, 0, 0, 0}};
+          if (i < n4) v = Index::template eval4<0>(a, (int)i);
+#pragma unroll
+          for (int c = 0; c < kVec; ++c) {
+            index[u * kVec + c] = v.v[c];
+            range[u * kVec + c] = i < n4 ? bin_of(v.v[c], inv_range) : kNone;
+          }
+        }
+      }
+      // rank of every element among the wave's elements of its range in this pass: a
+      // counter per wave and range in LDS, one add per element (the waves do not share
+      // counters, and LDS operations of one wave take effect in program order)
+      if (lane < (unsigned)kBins) wave_count[wave][lane] = 0;
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int s = 0; s < kBinItems; ++s) {
+        rank[s] = 0;
+        if (range[s] != kNone)
+          rank[s] = __hip_atomic_fetch_add(&wave_count[wave][range[s]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      }
+      __syncthreads();
+      // the first wave lays the pass out: ranges one after the other, inside a range the waves in order
+      if (wave == 0) {
+        unsigned total = 0;
+        if (lane < (unsigned)kBins) {
+#pragma unroll
+          for (int w = 0; w < kWavesPerBlock; ++w) total += wave_count[w][lane];
+        }
+        const unsigned start = (unsigned)wave_scan_inclusive<AddI32>((int)total) - total;
+        if (lane < (unsigned)kBins) {
+          unsigned run = start;
+#pragma unroll
+          for (int w = 0; w < kWavesPerBlock; ++w) { wave_first[w][lane] = run; run += wave_count[w][lane]; }
+          range_first[lane] = start;
+          range_count[lane] = total;
+          slot_filled[lane] = filled;
+          filled += total;
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < kBinItems; ++s)
+        if (range[s] != kNone) staged[wave_first[wave][range[s]] + rank[s]] = index[s];
+      __syncthreads();
+      // every wave copies a quarter of the ranges to their slots, consecutive lanes to consecutive
+      // words; what a slot cannot take is evaluated here
+      for (unsigned b = wave; b < (unsigned)kBins; b += kWavesPerBlock) {
+        const unsigned count = range_count[b], from = range_first[b], to = slot_filled[b];
+        int *slot = entries + ((size_t)b * tiles + tile) * kBinCap;
+        for (unsigned j = lane; j < count; j += kWave) {
+          const int v = staged[from + j];
+          if (to + j < (unsigned)kBinCap)
+            slot[to + j] = v;
+          else
+            acc = Op::apply(acc, C::template from_leaf<0>(a, C::leaf(a, v)));
+        }
+      }
+    }
+    if (threadIdx.x < kBins) counts[(size_t)threadIdx.x * tiles + tile] = (int)(filled < (unsigned)kBinCap ? filled : (unsigned)kBinCap);
+  }
+  if (blockIdx.x == 0 && threadIdx.x < n - n4) acc = Op::apply(acc, E::template eval<0>(a, (int)(n4 + threadIdx.x)));
+  // one partial per workgroup; the second kernel combines them with its own
+  const unsigned tag = tag_of_epoch(load_agent(&ctl->epoch));
+  T r = block_reduce<Op>(acc, lds);
+  if (threadIdx.x == 0) store_agent64(&partials[blockIdx.x], pack_word((unsigned)as_bits(r), tag, 1u));
+}
+
+template <class Op, class E>
+__global__ __launch_bounds__(kBlock) void fold_binned_kernel(const KArgs a, Control *ctl, unsigned long long *partials,
+                                                             const int *counts, const int *entries, unsigned tiles,
+                                                             unsigned earlier) {
+  using T = typename Op::T;
+  using C = GatherChain<E>;
+  using Leaf = typename C::Leaf;
+  constexpr unsigned kXcds = 8;                        // workgroup b runs on XCD b % 8
+  constexpr int kPastL2 = 0x12;                        // cache policy of the buffer loads: sc1 | nt
+  const unsigned xcd = blockIdx.x % kXcds, team = blockIdx.x / kXcds, teams = gridDim.x / kXcds;
+  const unsigned wave = (unsigned)wave_id(), lane = (unsigned)lane_id();
+  // raw buffer views: byte offsets, and an offset past the end reads as zero without a memory access
+  const unsigned slots = kBins * tiles;
+  const __amdgpu_buffer_rsrc_t count_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(counts), 0, (int)(slots * 4u), 0x00020000);
+  const __amdgpu_buffer_rsrc_t entry_buf =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(entries), 0, (int)(slots * (unsigned)kBinCap * 4u), 0x00020000);
+  const unsigned items = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;     // a wave per slot
+  T acc = Op::identity();
+  struct Slot5 { int count; int e[kBinGroups]; };
+  for (unsigned bin = xcd; bin < (unsigned)kBins; bin += kXcds) {
+    auto fetch = [&](unsigned item) {
+      Slot5 s;
+      const unsigned t = item * kWavesPerBlock + wave;
+      const bool there = item < items && t < tiles;
+      const unsigned slot = bin * tiles + t;
+      s.count = __builtin_amdgcn_raw_buffer_load_b32(count_buf, there ? slot * 4u : 0xffffffffu, 0, 0);
+#pragma unroll
+      for (int k = 0; k < kBinGroups; ++k)
+        s.e[k] = __builtin_amdgcn_raw_buffer_load_b32(entry_buf, there ? (slot * (unsigned)kBinCap + k * kWave + lane) * 4u : 0xffffffffu,
+                                                      0, kPastL2);
+      return s;
+    };
+    // Works on slot `use` and, once its gathers are on their way, starts the reads of the
+    // wave's next slot into `fill`: the memory counter retires in order, so a read issued
+    // before the gathers would have to land before the first gathered value can be used.
+    auto step = [&](const Slot5 &use, Slot5 &fill, unsigned item) {
+      const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(use.count);
+      Leaf x[kBinGroups];
+#pragma unroll
+      for (int k = 0; k < kBinGroups; ++k) {
+        x[k] = Leaf();
+        if ((unsigned)(k * kWave) < count)               // the same for the whole wave
+          if (k * kWave + lane < count) x[k] = C::leaf(a, use.e[k]);
+      }
+      fill = fetch(item + teams);
+#pragma unroll
+      for (int k = 0; k < kBinGroups; ++k)
+        if ((unsigned)(k * kWave) < count) {
+          const T v = C::template from_leaf<0>(a, x[k]);
+          if (k * kWave + lane < count) acc = Op::apply(acc, v);
+        }
+    };
+    // two slots in turn, so that no register has to be copied while its read is in flight;
+    // a slot past the end reads as empty
+    Slot5 even = fetch(team), odd;
+    for (unsigned item = team; item < items; item += 2 * teams) {
+      step(even, odd, item);
+      step(odd, even, item + teams);
+    }
+  }
+  fold_finish<Op>(acc, a, 0, ctl, partials, earlier);
 }
 
 // ------------------------------------------------------------------ segmented fold

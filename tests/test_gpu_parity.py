@@ -204,6 +204,41 @@ def test_spmv_column_blocked(rows, ncols, mean_len):
     run_all_modes(3, w, env)
 
 
+@pytest.mark.parametrize("table,m,spread", [(2200003, 2200003, "permutation"), (3000000, (1 << 21) + 4099, "uniform"),
+                                            (2000001, (1 << 21) + 8197, "skewed"), (1 << 22, (1 << 21) + 2, "one")])
+def test_perm_gather_binned(table, m, spread):
+    # a fold over a gather from a table of more than one L2 sorts the indices by table range
+    # first (two kernels, the entries in scratch).  A permutation, repeated indices, indices
+    # that crowd into one range or one position (more than a slot takes: the remainder is
+    # evaluated on the spot), lengths off the tile and off the 128-bit group.
+    rng = np.random.default_rng(table + m)
+    xs = rng.standard_normal(size=table).astype(F32)
+    if spread == "permutation":
+        idx = rng.permutation(table).astype(np.int32)
+    elif spread == "uniform":
+        idx = rng.integers(0, table, size=m, dtype=np.int32)
+    elif spread == "skewed":
+        idx = np.where(rng.random(m) < 0.9, rng.integers(0, 5000, size=m), rng.integers(0, table, size=m)).astype(np.int32)
+    else:
+        idx = np.full(m, table - 1, dtype=np.int32)
+    w = C.perm_gather_fold(xs=xs, idx=idx)
+    env = evaluate(w.graph, w.inputs)
+    g, part = plan(w.graph, False)
+    prog = device_program(g, w.inputs, part)
+    assert "binned" in prog.kernels()[0], prog.kernels()
+    for k in range(3):                                        # counts and entries are rewritten launch after launch
+        if k:
+            w.inputs["xs"] = rng.standard_normal(size=table).astype(F32)
+            w.inputs["idx"] = np.ascontiguousarray(w.inputs["idx"][::-1])
+            prog.upload("xs", w.inputs["xs"])
+            prog.upload("idx", w.inputs["idx"])
+            env = evaluate(w.graph, w.inputs)
+        prog.run()
+        compare(2, w, env, prog, w.graph.outputs(), "binned")
+        assert prog.control_words()[1] == 0
+    run_all_modes(2, w, env)
+
+
 @pytest.mark.parametrize("hw", [(1, 4), (1, 8), (2, 4), (3, 3), (1, 1), (5, 7), (33, 248), (34, 252), (64, 256),
                                 (65, 1000), (7, 1004), (100, 2048), (31, 996)])
 def test_stencil_shapes(hw):
