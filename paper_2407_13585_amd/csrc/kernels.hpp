@@ -373,49 +373,66 @@ __global__ __launch_bounds__(kBlock) void fold_binned_kernel(const KArgs a, Cont
   const __amdgpu_buffer_rsrc_t count_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(counts), 0, (int)(slots * 4u), 0x00020000);
   const __amdgpu_buffer_rsrc_t entry_buf =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(entries), 0, (int)(slots * (unsigned)kBinCap * 4u), 0x00020000);
-  const unsigned items = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;     // a wave per slot
-  T acc = Op::identity();
+  // A wave per slot.  Step q of a workgroup: range xcd + 8 * (q / per), tiles 4 * item .. 4 * item + 3
+  // with item = team + teams * (q % per); the ranges follow each other without a gap in the reads.
+  const unsigned items = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+  const unsigned per = (items + teams - 1) / teams;
+  const unsigned steps = per * (kBins / kXcds);
+  constexpr unsigned kNoSlot = 0xffffffffu;
+  auto slot_of = [&](unsigned q) {
+    const unsigned item = team + teams * (q % per), t = item * kWavesPerBlock + wave;
+    return q < steps && item < items && t < tiles ? (xcd + kXcds * (q / per)) * tiles + t : kNoSlot;
+  };
+  // a slot that does not exist reads as empty: an offset past the end of the buffer yields zero
+  auto fetch_count = [&](unsigned q) {
+    const unsigned slot = slot_of(q);
+    return __builtin_amdgcn_raw_buffer_load_b32(count_buf, slot != kNoSlot ? slot * 4u : kNoSlot, 0, 0);
+  };
   struct Slot5 { int count; int e[kBinGroups]; };
-  for (unsigned bin = xcd; bin < (unsigned)kBins; bin += kXcds) {
-    auto fetch = [&](unsigned item) {
-      Slot5 s;
-      const unsigned t = item * kWavesPerBlock + wave;
-      const bool there = item < items && t < tiles;
-      const unsigned slot = bin * tiles + t;
-      s.count = __builtin_amdgcn_raw_buffer_load_b32(count_buf, there ? slot * 4u : 0xffffffffu, 0, 0);
+  auto fetch_entries = [&](unsigned q, Slot5 &s) {
+    const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(s.count);
+    const unsigned at = (slot_of(q) * (unsigned)kBinCap + lane) * 4u;
+    // every read is issued, the ones past the count with an offset past the end (no memory access):
+    // reads that are issued only sometimes cannot be waited for one by one
 #pragma unroll
-      for (int k = 0; k < kBinGroups; ++k)
-        s.e[k] = __builtin_amdgcn_raw_buffer_load_b32(entry_buf, there ? (slot * (unsigned)kBinCap + k * kWave + lane) * 4u : 0xffffffffu,
-                                                      0, kPastL2);
-      return s;
-    };
-    // Works on slot `use` and, once its gathers are on their way, starts the reads of the
-    // wave's next slot into `fill`: the memory counter retires in order, so a read issued
-    // before the gathers would have to land before the first gathered value can be used.
-    auto step = [&](const Slot5 &use, Slot5 &fill, unsigned item) {
-      const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(use.count);
-      Leaf x[kBinGroups];
+    for (int k = 0; k < kBinGroups; ++k)
+      s.e[k] = __builtin_amdgcn_raw_buffer_load_b32(entry_buf, (unsigned)(k * kWave) < count ? at + k * kWave * 4u : kNoSlot, 0, kPastL2);
+  };
+  T acc = Op::identity();
+  // Works on slot `use` (step q).  Once its gathers are on their way it starts the reads of the
+  // entries of step q + 1 into `fill`, whose count the step before asked for, and asks for the
+  // count of step q + 2.  The memory counter retires in order: a read issued before the gathers
+  // would have to land before the first gathered value can be used.
+  auto step = [&](Slot5 &use, Slot5 &fill, unsigned q) {
+    // All reads so far were issued a step ago; with every one of them landed no gather below has
+    // to wait for an entry, which (in-order counter again) would mean waiting for the gathers
+    // issued before it.
+    __builtin_amdgcn_s_waitcnt(0x0f70);                  // vmcnt(0), the other counters left alone
+    const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(use.count);
+    Leaf x[kBinGroups];
 #pragma unroll
-      for (int k = 0; k < kBinGroups; ++k) {
-        x[k] = Leaf();
-        if ((unsigned)(k * kWave) < count)               // the same for the whole wave
-          if (k * kWave + lane < count) x[k] = C::leaf(a, use.e[k]);
-      }
-      fill = fetch(item + teams);
-#pragma unroll
-      for (int k = 0; k < kBinGroups; ++k)
-        if ((unsigned)(k * kWave) < count) {
-          const T v = C::template from_leaf<0>(a, x[k]);
-          if (k * kWave + lane < count) acc = Op::apply(acc, v);
-        }
-    };
-    // two slots in turn, so that no register has to be copied while its read is in flight;
-    // a slot past the end reads as empty
-    Slot5 even = fetch(team), odd;
-    for (unsigned item = team; item < items; item += 2 * teams) {
-      step(even, odd, item);
-      step(odd, even, item + teams);
+    for (int k = 0; k < kBinGroups; ++k) {
+      x[k] = Leaf();
+      if ((unsigned)(k * kWave) < count)                 // the same for the whole wave
+        if (k * kWave + lane < count) x[k] = C::leaf(a, use.e[k]);
     }
+    use.count = fetch_count(q + 2);
+    fetch_entries(q + 1, fill);
+#pragma unroll
+    for (int k = 0; k < kBinGroups; ++k)
+      if ((unsigned)(k * kWave) < count) {
+        const T v = C::template from_leaf<0>(a, x[k]);
+        if (k * kWave + lane < count) acc = Op::apply(acc, v);
+      }
+  };
+  // two slots in turn, so that no register has to be copied while its read is in flight
+  Slot5 even, odd;
+  even.count = fetch_count(0);
+  odd.count = fetch_count(1);
+  fetch_entries(0, even);
+  for (unsigned q = 0; q < steps; q += 2) {
+    step(even, odd, q);
+    step(odd, even, q + 1);
   }
   fold_finish<Op>(acc, a, 0, ctl, partials, earlier);
 }
