@@ -388,15 +388,21 @@ __global__ __launch_bounds__(kBlock) void fold_binned_kernel(const KArgs a, Cont
     const unsigned slot = slot_of(q);
     return __builtin_amdgcn_raw_buffer_load_b32(count_buf, slot != kNoSlot ? slot * 4u : kNoSlot, 0, 0);
   };
-  struct Slot5 { int count; int e[kBinGroups]; };
+  // Lane l takes entries 4l .. 4l+3 of the slot in one 128-bit read, and entry 256 + l if the
+  // slot has that many: the cache asks L2 for 128 bytes at a time on behalf of 128-bit reads and
+  // for 64 on behalf of 32-bit ones, and a compute unit holds only so many requests in flight;
+  // read word by word, the entries took as long as all the gathers together.
+  static_assert(kBinGroups == kVec + 1, "a 128-bit read per lane and a last group");
+  using Raw = int __attribute__((ext_vector_type(4)));
+  struct Slot5 { int count; Raw e; int last; };
   auto fetch_entries = [&](unsigned q, Slot5 &s) {
     const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(s.count);
-    const unsigned at = (slot_of(q) * (unsigned)kBinCap + lane) * 4u;
-    // every read is issued, the ones past the count with an offset past the end (no memory access):
-    // reads that are issued only sometimes cannot be waited for one by one
-#pragma unroll
-    for (int k = 0; k < kBinGroups; ++k)
-      s.e[k] = __builtin_amdgcn_raw_buffer_load_b32(entry_buf, (unsigned)(k * kWave) < count ? at + k * kWave * 4u : kNoSlot, 0, kPastL2);
+    const unsigned at = slot_of(q) * (unsigned)kBinCap * 4u;
+    // both reads are always issued, the second with an offset past the end (no memory access) when
+    // the slot ends before it: reads that are issued only sometimes cannot be waited for one by one
+    s.e = __builtin_amdgcn_raw_buffer_load_b128(entry_buf, count ? at + lane * 16u : kNoSlot, 0, kPastL2);
+    s.last = __builtin_amdgcn_raw_buffer_load_b32(entry_buf, count > (unsigned)(kVec * kWave) ? at + (kVec * kWave + lane) * 4u : kNoSlot,
+                                                  0, kPastL2);
   };
   T acc = Op::identity();
   // Works on slot `use` (step q).  Once its gathers are on their way it starts the reads of the
@@ -410,19 +416,22 @@ __global__ __launch_bounds__(kBlock) void fold_binned_kernel(const KArgs a, Cont
     __builtin_amdgcn_s_waitcnt(0x0f70);                  // vmcnt(0), the other counters left alone
     const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(use.count);
     Leaf x[kBinGroups];
+    bool mine[kBinGroups];
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) mine[k] = lane * kVec + k < count;
+    mine[kVec] = kVec * kWave + lane < count;
 #pragma unroll
     for (int k = 0; k < kBinGroups; ++k) {
       x[k] = Leaf();
-      if ((unsigned)(k * kWave) < count)                 // the same for the whole wave
-        if (k * kWave + lane < count) x[k] = C::leaf(a, use.e[k]);
+      if (mine[k]) x[k] = C::leaf(a, k < kVec ? use.e[k] : use.last);
     }
     use.count = fetch_count(q + 2);
     fetch_entries(q + 1, fill);
 #pragma unroll
     for (int k = 0; k < kBinGroups; ++k)
-      if ((unsigned)(k * kWave) < count) {
+      if (__builtin_amdgcn_ballot_w64(mine[k]) != 0) {   // the same for the whole wave
         const T v = C::template from_leaf<0>(a, x[k]);
-        if (k * kWave + lane < count) acc = Op::apply(acc, v);
+        if (mine[k]) acc = Op::apply(acc, v);
       }
   };
   // two slots in turn, so that no register has to be copied while its read is in flight
