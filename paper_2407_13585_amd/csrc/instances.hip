@@ -113,7 +113,12 @@ template <class Op, class E> hipError_t launch_fold_binned(const KArgs &a, const
   const unsigned first = std::min(tiles, std::min<unsigned>(resident_grid(&bin_indices_kernel<Op, E>), kMaxPartials / 2));
   hipError_t e = launch_k(&bin_indices_kernel<Op, E>, first, c.stream, a, c.ctl, c.partials, counts, entries, tiles, inv_range);
   if (e != hipSuccess) return e;
-  const unsigned second = std::max(8u, std::min<unsigned>(resident_grid(&fold_binned_kernel<Op, E>), kMaxPartials / 2) / 8 * 8);
+  // One workgroup per compute unit for the second kernel.  A compute unit's vector cache returns
+  // data in request order, so its gathers (L2 hits) queue behind the entry reads (from memory) of
+  // whichever wave issued some: with eight workgroups per unit the kernel took 130 us where the
+  // gathers alone take 66 and the entry reads alone 27; with one or two it takes their sum.
+  const int cus = device_compute_units();
+  const unsigned second = std::max(8u, (unsigned)(cus > 0 ? cus : 256) / 8 * 8);
   return launch_k(&fold_binned_kernel<Op, E>, second, c.stream, a, c.ctl, c.partials, static_cast<const int *>(counts),
                   static_cast<const int *>(entries), tiles, first);
 }

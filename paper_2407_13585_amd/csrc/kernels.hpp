@@ -244,6 +244,7 @@ constexpr int kBinPass = kBlock * kBinItems;
 constexpr int kBinTile = kBinPass * kBinPasses;
 constexpr int kBinGroups = 5;                          // a slot holds this many entries per lane of the wave that reads it
 constexpr int kBinCap = kBinGroups * kWave;            // 320 = 256 + 4 standard deviations of a uniform spread
+constexpr unsigned kBinAtOnce = 2;                     // slots a wave of the second kernel works on at a time
 static_assert(kBins <= kWave, "one thread of the first wave per range");
 
 // range of table position `j`: j / range_len, as a multiplication (the host passes
@@ -373,71 +374,85 @@ __global__ __launch_bounds__(kBlock) void fold_binned_kernel(const KArgs a, Cont
   const __amdgpu_buffer_rsrc_t count_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(counts), 0, (int)(slots * 4u), 0x00020000);
   const __amdgpu_buffer_rsrc_t entry_buf =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(entries), 0, (int)(slots * (unsigned)kBinCap * 4u), 0x00020000);
-  // A wave per slot.  Step q of a workgroup: range xcd + 8 * (q / per), tiles 4 * item .. 4 * item + 3
-  // with item = team + teams * (q % per); the ranges follow each other without a gap in the reads.
-  const unsigned items = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+  // A wave takes kBinAtOnce slots per step.  Step q of a workgroup: range xcd + 8 * (q / per), tiles
+  // 4 * kBinAtOnce * item and following with item = team + teams * (q % per); the ranges follow each
+  // other without a gap in the reads.
+  constexpr unsigned kPerItem = kWavesPerBlock * kBinAtOnce;
+  const unsigned items = (tiles + kPerItem - 1) / kPerItem;
   const unsigned per = (items + teams - 1) / teams;
   const unsigned steps = per * (kBins / kXcds);
   constexpr unsigned kNoSlot = 0xffffffffu;
-  auto slot_of = [&](unsigned q) {
-    const unsigned item = team + teams * (q % per), t = item * kWavesPerBlock + wave;
+  auto slot_of = [&](unsigned q, unsigned sub) {
+    const unsigned item = team + teams * (q % per), t = (item * kBinAtOnce + sub) * kWavesPerBlock + wave;
     return q < steps && item < items && t < tiles ? (xcd + kXcds * (q / per)) * tiles + t : kNoSlot;
   };
-  // a slot that does not exist reads as empty: an offset past the end of the buffer yields zero
-  auto fetch_count = [&](unsigned q) {
-    const unsigned slot = slot_of(q);
-    return __builtin_amdgcn_raw_buffer_load_b32(count_buf, slot != kNoSlot ? slot * 4u : kNoSlot, 0, 0);
-  };
-  // Lane l takes entries 4l .. 4l+3 of the slot in one 128-bit read, and entry 256 + l if the
-  // slot has that many: the cache asks L2 for 128 bytes at a time on behalf of 128-bit reads and
-  // for 64 on behalf of 32-bit ones, and a compute unit holds only so many requests in flight;
-  // read word by word, the entries took as long as all the gathers together.
+  // Lane l takes entries 4l .. 4l+3 of a slot in one 128-bit read, and entry 256 + l if the slot
+  // has that many (the cache asks L2 for 128 bytes at a time on behalf of 128-bit reads, for 64 on
+  // behalf of 32-bit ones).
   static_assert(kBinGroups == kVec + 1, "a 128-bit read per lane and a last group");
   using Raw = int __attribute__((ext_vector_type(4)));
   struct Slot5 { int count; Raw e; int last; };
-  auto fetch_entries = [&](unsigned q, Slot5 &s) {
-    const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(s.count);
-    const unsigned at = slot_of(q) * (unsigned)kBinCap * 4u;
-    // both reads are always issued, the second with an offset past the end (no memory access) when
-    // the slot ends before it: reads that are issued only sometimes cannot be waited for one by one
-    s.e = __builtin_amdgcn_raw_buffer_load_b128(entry_buf, count ? at + lane * 16u : kNoSlot, 0, kPastL2);
-    s.last = __builtin_amdgcn_raw_buffer_load_b32(entry_buf, count > (unsigned)(kVec * kWave) ? at + (kVec * kWave + lane) * 4u : kNoSlot,
-                                                  0, kPastL2);
+  struct Batch { Slot5 s[kBinAtOnce]; };
+  // a slot that does not exist reads as empty: an offset past the end of the buffer yields zero
+  auto fetch_counts = [&](unsigned q, Batch &b) {
+#pragma unroll
+    for (unsigned sub = 0; sub < kBinAtOnce; ++sub) {
+      const unsigned slot = slot_of(q, sub);
+      b.s[sub].count = __builtin_amdgcn_raw_buffer_load_b32(count_buf, slot != kNoSlot ? slot * 4u : kNoSlot, 0, 0);
+    }
+  };
+  auto fetch_entries = [&](unsigned q, Batch &b) {
+#pragma unroll
+    for (unsigned sub = 0; sub < kBinAtOnce; ++sub) {
+      Slot5 &s = b.s[sub];
+      const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(s.count);
+      const unsigned at = slot_of(q, sub) * (unsigned)kBinCap * 4u;
+      // both reads are always issued, the second with an offset past the end (no memory access) when
+      // the slot ends before it: reads that are issued only sometimes cannot be waited for one by one
+      s.e = __builtin_amdgcn_raw_buffer_load_b128(entry_buf, count ? at + lane * 16u : kNoSlot, 0, kPastL2);
+      s.last = __builtin_amdgcn_raw_buffer_load_b32(entry_buf, count > (unsigned)(kVec * kWave) ? at + (kVec * kWave + lane) * 4u : kNoSlot,
+                                                    0, kPastL2);
+    }
   };
   T acc = Op::identity();
-  // Works on slot `use` (step q).  Once its gathers are on their way it starts the reads of the
-  // entries of step q + 1 into `fill`, whose count the step before asked for, and asks for the
-  // count of step q + 2.  The memory counter retires in order: a read issued before the gathers
-  // would have to land before the first gathered value can be used.
-  auto step = [&](Slot5 &use, Slot5 &fill, unsigned q) {
+  // Works on the slots in `use` (step q).  Once their gathers are on their way it starts the reads
+  // of the entries of step q + 1 into `fill`, whose counts the step before asked for, and asks for
+  // the counts of step q + 2.  The memory counter retires in order: a read issued before the
+  // gathers would have to land before the first gathered value can be used.
+  auto step = [&](Batch &use, Batch &fill, unsigned q) {
     // All reads so far were issued a step ago; with every one of them landed no gather below has
     // to wait for an entry, which (in-order counter again) would mean waiting for the gathers
     // issued before it.
     __builtin_amdgcn_s_waitcnt(0x0f70);                  // vmcnt(0), the other counters left alone
-    const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(use.count);
-    Leaf x[kBinGroups];
-    bool mine[kBinGroups];
+    Leaf x[kBinAtOnce][kBinGroups];
+    bool mine[kBinAtOnce][kBinGroups];
 #pragma unroll
-    for (int k = 0; k < kVec; ++k) mine[k] = lane * kVec + k < count;
-    mine[kVec] = kVec * kWave + lane < count;
+    for (unsigned sub = 0; sub < kBinAtOnce; ++sub) {
+      const unsigned count = (unsigned)__builtin_amdgcn_readfirstlane(use.s[sub].count);
 #pragma unroll
-    for (int k = 0; k < kBinGroups; ++k) {
-      x[k] = Leaf();
-      if (mine[k]) x[k] = C::leaf(a, k < kVec ? use.e[k] : use.last);
+      for (int k = 0; k < kVec; ++k) mine[sub][k] = lane * kVec + k < count;
+      mine[sub][kVec] = kVec * kWave + lane < count;
+#pragma unroll
+      for (int k = 0; k < kBinGroups; ++k) {
+        x[sub][k] = Leaf();
+        if (mine[sub][k]) x[sub][k] = C::leaf(a, k < kVec ? use.s[sub].e[k] : use.s[sub].last);
+      }
     }
-    use.count = fetch_count(q + 2);
+    fetch_counts(q + 2, use);
     fetch_entries(q + 1, fill);
 #pragma unroll
-    for (int k = 0; k < kBinGroups; ++k)
-      if (__builtin_amdgcn_ballot_w64(mine[k]) != 0) {   // the same for the whole wave
-        const T v = C::template from_leaf<0>(a, x[k]);
-        if (mine[k]) acc = Op::apply(acc, v);
-      }
+    for (unsigned sub = 0; sub < kBinAtOnce; ++sub)
+#pragma unroll
+      for (int k = 0; k < kBinGroups; ++k)
+        if (__builtin_amdgcn_ballot_w64(mine[sub][k]) != 0) {   // the same for the whole wave
+          const T v = C::template from_leaf<0>(a, x[sub][k]);
+          if (mine[sub][k]) acc = Op::apply(acc, v);
+        }
   };
-  // two slots in turn, so that no register has to be copied while its read is in flight
-  Slot5 even, odd;
-  even.count = fetch_count(0);
-  odd.count = fetch_count(1);
+  // two batches in turn, so that no register has to be copied while its read is in flight
+  Batch even, odd;
+  fetch_counts(0, even);
+  fetch_counts(1, odd);
   fetch_entries(0, even);
   for (unsigned q = 0; q < steps; q += 2) {
     step(even, odd, q);
