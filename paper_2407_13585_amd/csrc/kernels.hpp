@@ -267,6 +267,7 @@ __global__ __launch_bounds__(kBlock) void bin_indices_kernel(const KArgs a, Cont
   __shared__ unsigned range_first[kBins];                   // start of a range in `staged`
   __shared__ unsigned range_count[kBins];                   // elements of a range in this pass
   __shared__ unsigned slot_filled[kBins];                   // entries of the tile's slot before this pass
+  __shared__ unsigned any_crowded;
   __shared__ int staged[kBinPass];                          // the indices of a pass, sorted by range
   __shared__ T lds[kWavesPerBlock + 1];
   const unsigned n = (unsigned)a.n, n4 = n & ~3u;
@@ -279,13 +280,13 @@ __global__ __launch_bounds__(kBlock) void bin_indices_kernel(const KArgs a, Cont
       const unsigned first = tile * kBinTile + pass * kBinPass;
       const unsigned base = first + threadIdx.x * kVec;
       int index[kBinItems];
-      unsigned range[kBinItems], rank[kBinItems];
+      unsigned place[kBinItems];                       // range << 16 | rank among the wave's elements of that range
       if (first + kBinPass <= n4) {
 #pragma unroll
         for (int u = 0; u < kBinItems / kVec; ++u) {
           Vec4<int> v = Index::template eval4<0>(a, (int)(base + u * (kBlock * kVec)));
 #pragma unroll
-          for (int c = 0; c < kVec; ++c) { index[u * kVec + c] = v.v[c]; range[u * kVec + c] = bin_of(v.v[c], inv_range); }
+          for (int c = 0; c < kVec; ++c) { index[u * kVec + c] = v.v[c]; place[u * kVec + c] = bin_of(v.v[c], inv_range) << 16; }
         }
       } else {
 #pragma unroll
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(kBlock) void bin_indices_kernel(const KArgs a, Cont
 #pragma unroll
           for (int c = 0; c < kVec; ++c) {
             index[u * kVec + c] = v.v[c];
-            range[u * kVec + c] = i < n4 ? bin_of(v.v[c], inv_range) : kNone;
+            place[u * kVec + c] = (i < n4 ? bin_of(v.v[c], inv_range) : kNone) << 16;
           }
         }
       }
@@ -307,9 +308,8 @@ __global__ __launch_bounds__(kBlock) void bin_indices_kernel(const KArgs a, Cont
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int s = 0; s < kBinItems; ++s) {
-        rank[s] = 0;
-        if (range[s] != kNone)
-          rank[s] = __hip_atomic_fetch_add(&wave_count[wave][range[s]], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        if ((place[s] >> 16) != kNone)
+          place[s] |= __hip_atomic_fetch_add(&wave_count[wave][place[s] >> 16], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
       }
       __syncthreads();
       // the first wave lays the pass out: ranges one after the other, inside a range the waves in order
@@ -329,23 +329,42 @@ __global__ __launch_bounds__(kBlock) void bin_indices_kernel(const KArgs a, Cont
           slot_filled[lane] = filled;
           filled += total;
         }
+        const unsigned long long over = __builtin_amdgcn_ballot_w64(lane < (unsigned)kBins && filled > (unsigned)kBinCap);
+        if (lane == 0) any_crowded = over != 0 ? 1u : 0u;
       }
       __syncthreads();
+      const bool crowded = any_crowded != 0;           // some slot of this tile is full: the same for the whole workgroup
 #pragma unroll
       for (int s = 0; s < kBinItems; ++s)
-        if (range[s] != kNone) staged[wave_first[wave][range[s]] + rank[s]] = index[s];
+        if ((place[s] >> 16) != kNone) staged[wave_first[wave][place[s] >> 16] + (place[s] & 0xffffu)] = index[s];
       __syncthreads();
-      // every wave copies a quarter of the ranges to their slots, consecutive lanes to consecutive
-      // words; what a slot cannot take is evaluated here
+      // every wave copies a quarter of the ranges to their slots, consecutive lanes to consecutive words
       for (unsigned b = wave; b < (unsigned)kBins; b += kWavesPerBlock) {
-        const unsigned count = range_count[b], from = range_first[b], to = slot_filled[b];
-        int *slot = entries + ((size_t)b * tiles + tile) * kBinCap;
-        for (unsigned j = lane; j < count; j += kWave) {
-          const int v = staged[from + j];
-          if (to + j < (unsigned)kBinCap)
-            slot[to + j] = v;
-          else
-            acc = Op::apply(acc, C::template from_leaf<0>(a, C::leaf(a, v)));
+        const unsigned from = range_first[b], to = slot_filled[b];
+        const unsigned room = to < (unsigned)kBinCap ? (unsigned)kBinCap - to : 0u;
+        const unsigned count = range_count[b] < room ? range_count[b] : room;
+        int *slot = entries + ((size_t)b * tiles + tile) * kBinCap + to;
+        for (unsigned j = lane; j < count; j += kWave) slot[j] = staged[from + j];
+      }
+      // what the slots cannot take (indices that crowd into few ranges) is evaluated here, by the
+      // whole workgroup and two gathers per lane at a time
+      constexpr int kOver = 2;
+      for (unsigned b = 0; crowded && b < (unsigned)kBins; ++b) {
+        const unsigned from = range_first[b], to = slot_filled[b], count = range_count[b];
+        const unsigned room = to < (unsigned)kBinCap ? (unsigned)kBinCap - to : 0u;
+        for (unsigned j0 = room; j0 < count; j0 += kBlock * kOver) {     // the same for the whole workgroup
+          typename C::Leaf x[kOver];
+#pragma unroll
+          for (int c = 0; c < kOver; ++c) {
+            const unsigned j = j0 + c * kBlock + threadIdx.x;
+            x[c] = typename C::Leaf();
+            if (j < count) x[c] = C::leaf(a, staged[from + j]);
+          }
+#pragma unroll
+          for (int c = 0; c < kOver; ++c) {
+            const T v = C::template from_leaf<0>(a, x[c]);
+            if (j0 + c * kBlock + threadIdx.x < count) acc = Op::apply(acc, v);
+          }
         }
       }
     }

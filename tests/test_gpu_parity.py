@@ -205,7 +205,8 @@ def test_spmv_column_blocked(rows, ncols, mean_len):
 
 
 @pytest.mark.parametrize("table,m,spread", [(2200003, 2200003, "permutation"), (3000000, (1 << 21) + 4099, "uniform"),
-                                            (2000001, (1 << 21) + 8197, "skewed"), (1 << 22, (1 << 21) + 2, "one")])
+                                            (2000001, (1 << 21) + 8197, "skewed"), (1 << 22, (1 << 21) + 2, "one"),
+                                            (3000017, (1 << 21) + 77, "middle")])
 def test_perm_gather_binned(table, m, spread):
     # a fold over a gather from a table of more than one L2 sorts the indices by table range
     # first (two kernels, the entries in scratch).  A permutation, repeated indices, indices
@@ -219,6 +220,9 @@ def test_perm_gather_binned(table, m, spread):
         idx = rng.integers(0, table, size=m, dtype=np.int32)
     elif spread == "skewed":
         idx = np.where(rng.random(m) < 0.9, rng.integers(0, 5000, size=m), rng.integers(0, table, size=m)).astype(np.int32)
+    elif spread == "middle":
+        idx = np.where(rng.random(m) < 0.7, rng.integers(table // 2, table // 2 + 70000, size=m),
+                       rng.integers(0, table, size=m)).astype(np.int32)
     else:
         idx = np.full(m, table - 1, dtype=np.int32)
     w = C.perm_gather_fold(xs=xs, idx=idx)
