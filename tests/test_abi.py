@@ -166,6 +166,35 @@ def test_workspace_of_the_column_blocked_segmented_fold_is_part_of_scratch():
     assert fc.fc_scratch_bytes(g2, part2) == need - 32 * rows
 
 
+def test_workspace_of_the_fold_over_sorted_gather_indices_is_part_of_scratch():
+    # graph only, no data: a fold over a gather from a 16 MiB table takes the kernel pair that sorts
+    # the indices by table range first; the sorted indices (320 words per 256) live in scratch
+    def program(table, m):
+        g = Graph()
+        g.add("xs", "input", "f32", (table,))
+        g.add("idx", "input", "i32", (m,))
+        g.add("ys", "map", "f32", (table,), fn="sin_x_mul_x", args=("xs",))
+        g.add("zs", "gather", "f32", (m,), args=("idx", "ys"))
+        g.add("ws", "map", "f32", (m,), fn="sq_plus_one", args=("zs",))
+        g.add("r", "fold", "f32", (1,), fn="add", args=("ws",), output=True)
+        return g
+    m = 1 << 22
+    g = program(1 << 22, m)
+    part = fc.fc_plan(g, "bytes")
+    assert part.n_clusters == 1 and "binned" in fc.fc_cluster_kernel(g, part, 0)
+    need = fc.fc_scratch_bytes(g, part)
+    assert need >= B.FC_SCRATCH_CONTROL_BYTES + 5 * m
+    fake = (0x10000000, 1 << 30)
+    bufs = {n.name: fake for n in g.nodes if n.kind == "input" or n.output}
+    expect("FC_E_SCRATCH", fc.fc_run_fused, g, part, bufs, (0x10000000, B.FC_SCRATCH_CONTROL_BYTES + 4 * m))
+    # a table that fits one L2, or few positions: gathered directly, no workspace
+    for table, count in ((1 << 20, m), (1 << 22, 1 << 20)):
+        small = program(table, count)
+        part = fc.fc_plan(small, "bytes")
+        assert "binned" not in fc.fc_cluster_kernel(small, part, 0)
+        assert fc.fc_scratch_bytes(small, part) < B.FC_SCRATCH_CONTROL_BYTES + 4096
+
+
 def test_duplicate_keeps_program_meaning():
     from oracle.interp import evaluate
     for cfg in (1, 5):
