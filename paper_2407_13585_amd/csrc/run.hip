@@ -1,5 +1,6 @@
 // Runner: maps every cluster of a clustering onto a kernel instance and
-// launches it.  One launch per cluster; no host synchronisation.
+// launches it.  One instance per cluster (an instance is one kernel, in one case two
+// kernels in a row); no host synchronisation.
 #include "run.hpp"
 
 #include <algorithm>
