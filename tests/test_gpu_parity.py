@@ -243,6 +243,22 @@ def test_perm_gather_binned(table, m, spread):
     run_all_modes(2, w, env)
 
 
+@pytest.mark.parametrize("table,m", [(1048600, 1 << 21), ((1 << 24), (1 << 21) + 8192), (5000000, (1 << 21) + 4096),
+                                     (1234567, (1 << 21) + 4100)])
+def test_perm_gather_binned_sizes(table, m):
+    # table sizes just above one L2 and at the largest the kernel pair takes; position counts that
+    # are whole tiles, whole passes, and a pass with four elements in it
+    rng = np.random.default_rng(table ^ m)
+    w = C.perm_gather_fold(xs=rng.standard_normal(size=table).astype(F32), idx=rng.integers(0, table, size=m, dtype=np.int32))
+    env = evaluate(w.graph, w.inputs)
+    g, part = plan(w.graph, False)
+    prog = device_program(g, w.inputs, part)
+    assert "binned" in prog.kernels()[0], prog.kernels()
+    prog.run()
+    compare(2, w, env, prog, w.graph.outputs(), "binned")
+    assert prog.control_words()[1] == 0
+
+
 @pytest.mark.parametrize("hw", [(1, 4), (1, 8), (2, 4), (3, 3), (1, 1), (5, 7), (33, 248), (34, 252), (64, 256),
                                 (65, 1000), (7, 1004), (100, 2048), (31, 996)])
 def test_stencil_shapes(hw):
