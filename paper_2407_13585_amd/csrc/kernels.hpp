@@ -231,9 +231,10 @@ __global__ __launch_bounds__(kBlock) void store_fold_kernel(const KArgs a, Contr
 //     slot, give or take 16; the few that a slot cannot take are evaluated on the spot.
 //  2. fold_binned_kernel: every XCD takes the ranges r with r % 8 equal to its number,
 //     one after the other, and reads all slots of the range.  Its gathers go to one
-//     range of at most half an L2 (the ranges of two rounds fit side by side while the
-//     workgroups of an XCD are not all in the same round) and hit; the slots are read
-//     past L2 (agent scope, read once), so that they do not displace the table.
+//     range, half an L2 or less for tables up to 64 MiB (the ranges of two rounds fit
+//     side by side while the workgroups of an XCD are not all in the same round), and
+//     hit; the slots are read past L2 (agent scope, read once), so that they do not
+//     displace the table.
 //
 // The indices are read once and written and read once more as entries: three times their
 // bytes instead of a line of 128 bytes for each.

@@ -244,9 +244,9 @@ def test_perm_gather_binned(table, m, spread):
 
 
 @pytest.mark.parametrize("table,m", [(1048600, 1 << 21), ((1 << 24), (1 << 21) + 8192), (5000000, (1 << 21) + 4096),
-                                     (1234567, (1 << 21) + 4100)])
+                                     (1234567, (1 << 21) + 4100), ((1 << 25) + 5, (1 << 21) + 1)])
 def test_perm_gather_binned_sizes(table, m):
-    # table sizes just above one L2 and at the largest the kernel pair takes; position counts that
+    # table sizes just above one L2, at 64 MiB and beyond (ranges larger than half an L2); position counts that
     # are whole tiles, whole passes, and a pass with four elements in it
     rng = np.random.default_rng(table ^ m)
     w = C.perm_gather_fold(xs=rng.standard_normal(size=table).astype(F32), idx=rng.integers(0, table, size=m, dtype=np.int32))
