@@ -46,7 +46,10 @@ typedef enum fc_kind {
   FC_GATHER   = 3,  /* ys[j] = src[idx[j]]; arg0 = idx (read in output order), arg1 = src (read in the gather's own order) */
   FC_FOLD     = 4,  /* shape (1): fold of the flattened argument; else fold of the innermost dimension */
   FC_FOLDSEG  = 5,  /* arg0 = flat values, arg1 = offsets[R+1] (infusible); y[r] = fold of values[off[r], off[r+1]) */
-  FC_SCANL    = 6,  /* exclusive prefix combine, identity seeded; traversal order 0; a rank-2 array is scanned row by row */
+  FC_SCANL    = 6,  /* exclusive prefix combine (+), identity seeded; traversal order 0; a rank-2 array is scanned row
+                       by row.  i32: exact.  f32: summed in a fixed tree order (the same bits on every launch), so
+                       a prefix differs from the sequentially rounded sum by rounding only; an f32 scan can be
+                       stored but not fused with a scatter or a fold (FC_E_UNSUPPORTED) */
   FC_SCANR    = 7,  /* exclusive suffix combine; traversal order 1 */
   FC_SCATTER  = 8,  /* arg0 = dest (infusible, updated in place), arg1 = index, arg2 = value, arg3 = flag (optional);
                        fn = OVERWRITE (kept indices distinct) or ADD (colliding indices combine: exact for i32,

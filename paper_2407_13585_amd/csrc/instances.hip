@@ -130,6 +130,11 @@ template <class EX, class EV, int Mode, bool Reverse = false> hipError_t launch_
   return launch_k(&scan_kernel<EX, EV, Mode, Reverse>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
 }
 // lanes per row by row length, as for the row folds
+template <class EX, bool Reverse = false> hipError_t launch_scan_f32(const KArgs &a, const LaunchCtx &c) {
+  long long tiles = std::max<long long>(1, ((long long)a.n + kScanFTile - 1) / kScanFTile);
+  if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
+  return launch_k(&scan_f32_kernel<EX, Reverse>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
+}
 template <class E, bool Reverse> hipError_t launch_rowscan(const KArgs &a, const LaunchCtx &c) {
   if (a.aux == 0 || a.w == 0) return hipSuccess;
   if (a.w <= 64)
@@ -183,6 +188,9 @@ template <class EX, class EV, int Mode, bool Reverse = false> Instance scan_() {
   if (Mode & kScatter) s += "+scatter[" + sig_of<EV>() + "]";
   if (Mode & kCount) s += "+count";
   return {s, &launch_scan<EX, EV, Mode, Reverse>};
+}
+template <class EX, bool Reverse = false> Instance scan_f32_() {
+  return {std::string(Reverse ? "scanr[" : "scan[") + sig_of<EX>() + "]+offs", &launch_scan_f32<EX, Reverse>};
 }
 template <class E, bool Reverse = false> Instance rowscan_() {
   return {std::string(Reverse ? "rowscanr[" : "rowscan[") + sig_of<E>() + "]+offs", &launch_rowscan<E, Reverse>};
@@ -288,6 +296,13 @@ std::vector<Instance> build_registry() {
   r.push_back(rowscan_<I0, true>());
   r.push_back(rowscan_<ModFlag>());
   r.push_back(rowscan_<ModFlag, true>());
+  // prefix sums of fp32 arrays, alone and with a producer fused in
+  r.push_back(scan_f32_<F0>());
+  r.push_back(scan_f32_<F0, true>());
+  r.push_back(scan_f32_<Map<FnAffine, F0>>());
+  r.push_back(scan_f32_<Map<FnMul2, F0, F1>>());
+  r.push_back(rowscan_<F0>());
+  r.push_back(rowscan_<F0, true>());
   r.push_back(scatter_<I0, I1, I2>());
   r.push_back(scatter_<I0, F1, I2>());
   // ---- fused clusters ----

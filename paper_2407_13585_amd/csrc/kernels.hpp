@@ -780,11 +780,11 @@ template <class F, class EV> struct FlagOfValue<Map<F, EV>, EV> {
 // yet published, or a stale line in this XCD's caches) is re-read at agent scope
 // until it does.  Agent-scope loads go to memory one lane at a time, so they are
 // kept for the few words that need them.
-template <int Threads = kScanBlock>
-__device__ __forceinline__ int sum_tagged_words(const unsigned long long *p, unsigned count, unsigned tag,
-                                                Control *ctl) {
+template <int Threads = kScanBlock, class T = int>
+__device__ __forceinline__ T sum_tagged_words(const unsigned long long *p, unsigned count, unsigned tag,
+                                              Control *ctl) {
   using Pair = unsigned long long __attribute__((ext_vector_type(2)));
-  int sum = 0;
+  T sum = T();
   for (unsigned k = 2 * (threadIdx.x % Threads); k < count; k += 2 * Threads) {
     Pair w = *reinterpret_cast<const Pair *>(p + k);
 #pragma unroll
@@ -793,7 +793,7 @@ __device__ __forceinline__ int sum_tagged_words(const unsigned long long *p, uns
       unsigned long long v = j ? w.y : w.x;
       unsigned lo = (unsigned)v;
       if ((lo >> 2) != tag || (lo & 3u) == 0u) v = wait_word(p + k + j, tag, ctl);
-      sum += (int)(unsigned)(v >> 32);
+      sum += from_bits<T>((int)(unsigned)(v >> 32));
     }
   }
   return sum;
@@ -862,7 +862,8 @@ struct ScanPayload {
   // of a lane covers elements base + j*256 + lane*4 .. +3 (fully coalesced).
   // A tile that lies wholly inside the array takes a path without any
   // per-lane condition, so that its 128-bit reads are issued back to back and
-  // are all in flight together; the last tile (and scanr) takes the guarded path.
+  // are all in flight together; the last tile (and scanr of a length that is not a
+  // multiple of four) takes the guarded path.
   __device__ __forceinline__ void load(const KArgs &a, unsigned tile, unsigned n) {
     const unsigned wbase = tile * kScanTile + wave_id() * (kWave * kScanItems);
     bits = 0u;
@@ -890,6 +891,19 @@ struct ScanPayload {
 #pragma unroll
           for (int c = 0; c < 4; ++c) set(j, c, v[j].v[c]);
       }
+      return;
+    }
+    if (Reverse && !kScat && (n & 3u) == 0u && (unsigned long long)(tile + 1) * kScanTile <= n) {
+      // scanr of a whole tile: the group at position i of the pass is elements n-4-i .. n-1-i
+      // taken backwards, one 128-bit read when the length is a multiple of four
+      Vec4<int> v[kScanAcc];
+#pragma unroll
+      for (int j = 0; j < kScanAcc; ++j)
+        v[j] = EX::template eval4<0>(a, (int)(n - 4 - (wbase + j * (kWave * kVec) + lane_id() * kVec)));
+#pragma unroll
+      for (int j = 0; j < kScanAcc; ++j)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) set(j, c, v[j].v[3 - c]);
       return;
     }
 #pragma unroll
@@ -1063,6 +1077,8 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
         int *offs = static_cast<int *>(a.out[1]);
         if (!Reverse && i + 3 < n) {
           store4(offs + i, Vec4<int>{{o[0], o[1], o[2], o[3]}});
+        } else if (Reverse && (n & 3u) == 0u && i + 3 < n) {
+          store4(offs + (n - 4 - i), Vec4<int>{{o[3], o[2], o[1], o[0]}});
         } else {
 #pragma unroll
           for (int c = 0; c < 4; ++c) if (i + c < n) offs[Reverse ? n - 1 - (i + c) : i + c] = o[c];
@@ -1077,6 +1093,122 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
   }
 }
 
+// ------------------------------------------------------------------ single-pass scan of an fp32 stream
+// Exclusive (+) scan of the fp32 stream EX, stored; the same cross-tile scheme as
+// scan_kernel (aggregates and group totals as tagged words, no tile waits for a
+// prefix), the values travelling as their bit patterns.  The sums are taken in a
+// fixed order (four elements of a 128-bit group, the lanes of a wave, the waves of
+// a tile, the tiles of a group, the groups), so a launch gives the same bits every
+// time; the order is not the sequential one, so a prefix differs from the
+// sequential fp32 sum by rounding, within the bound of any summation order.
+constexpr int kScanFItems = 16;                       // per lane: four 128-bit accesses
+constexpr int kScanFAcc = kScanFItems / kVec;
+constexpr int kScanFTile = kScanBlock * kScanFItems;  // 8192 elements
+
+__device__ __forceinline__ float scan_block_sum_f32(float v, float *lds) {
+  float w = wave_reduce<AddF32>(v);
+  __syncthreads();
+  if (lane_id() == 0) lds[wave_id()] = w;
+  __syncthreads();
+  float r = 0.0f;
+#pragma unroll
+  for (int k = 0; k < kScanWaves; ++k) r += lds[k];
+  return r;
+}
+
+template <class EX, bool Reverse>
+__global__ __launch_bounds__(kScanBlock) void scan_f32_kernel(const KArgs a, Control *ctl, unsigned long long *status,
+                                                              unsigned n_tiles) {
+  static_assert(std::is_same<typename EX::R, float>::value, "fp32 stream");
+  __shared__ float lds_wave[kScanWaves];
+  __shared__ float lds_sum[kScanWaves];
+  const unsigned n = (unsigned)a.n;
+  const int lane = lane_id(), wave = wave_id();
+  const unsigned epoch = load_agent(&ctl->epoch);
+  const unsigned tag = tag_of_epoch(epoch);
+  unsigned long long *group_word = status + ((n_tiles + 15) / 16) * 16;
+  float *offs = static_cast<float *>(a.out[1]);
+  const unsigned tile = blockIdx.x;
+  const unsigned wbase = tile * kScanFTile + wave * (kWave * kScanFItems);
+  // position i of the pass is element i, for scanr element n - 1 - i; positions past the end read 0
+  // a whole tile is read and written in 128-bit groups; for scanr the group at position i is
+  // elements n-4-i .. n-1-i taken backwards, which is a group only if n is a multiple of four
+  const bool whole = (size_t)(tile + 1) * kScanFTile <= n && (!Reverse || (n & 3u) == 0u);
+  float x[kScanFAcc][kVec];
+  if (whole) {
+#pragma unroll
+    for (int j = 0; j < kScanFAcc; ++j) {
+      const unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
+      const Vec4<float> v = EX::template eval4<0>(a, (int)(Reverse ? n - 4 - i : i));
+#pragma unroll
+      for (int c = 0; c < kVec; ++c) x[j][c] = v.v[Reverse ? 3 - c : c];
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < kScanFAcc; ++j)
+#pragma unroll
+      for (int c = 0; c < kVec; ++c) {
+        const unsigned i = wbase + j * (kWave * kVec) + lane * kVec + c;
+        x[j][c] = i < n ? EX::template eval<0>(a, (int)(Reverse ? n - 1 - i : i)) : 0.0f;
+      }
+  }
+  // exclusive prefix of each access inside the wave
+  float excl[kScanFAcc];
+  float carry = 0.0f;
+#pragma unroll
+  for (int j = 0; j < kScanFAcc; ++j) {
+    const float s = (x[j][0] + x[j][1]) + (x[j][2] + x[j][3]);
+    const float inc = wave_scan_inclusive<AddF32>(s);
+    excl[j] = carry + lane_prev(0.0f, inc);
+    carry += from_bits<float>(__builtin_amdgcn_readlane(as_bits(inc), kWave - 1));
+  }
+  if (lane == 0) lds_wave[wave] = carry;
+  __syncthreads();
+  float wave_excl = 0.0f, aggregate = 0.0f;
+#pragma unroll
+  for (int k = 0; k < kScanWaves; ++k) {
+    const float t = lds_wave[k];
+    if (k < wave) wave_excl += t;
+    aggregate += t;
+  }
+  if (threadIdx.x == 0) store_agent64(&status[tile], pack_word((unsigned)as_bits(aggregate), tag, 1u));
+  const unsigned group = tile / kScanGroup, first = group * kScanGroup;
+  const unsigned n_mine = tile - first;            // earlier tiles of my group
+  // gate: one lane waits for the word that is published last among those this tile needs
+  if (threadIdx.x == 0 && tile > 0)
+    (void)wait_word(n_mine > 0 ? &status[tile - 1] : &group_word[group - 1], tag, ctl);
+  __syncthreads();
+  float sum_group = sum_tagged_words<kScanBlock, float>(status + first, n_mine, tag, ctl);
+  if (n_mine == kScanGroup - 1) {
+    // last tile of a full group: publish the group total before waiting for anything else
+    sum_group = scan_block_sum_f32(sum_group, lds_sum);
+    if (threadIdx.x == 0) store_agent64(&group_word[group], pack_word((unsigned)as_bits(sum_group + aggregate), tag, 1u));
+    if (threadIdx.x != 0) sum_group = 0.0f;        // counted once in the sum below
+  }
+  const float sum_before = sum_group + sum_tagged_words<kScanBlock, float>(group_word, group, tag, ctl);
+  const float tile_excl = scan_block_sum_f32(sum_before, lds_sum);
+  if (tile == n_tiles - 1 && threadIdx.x == 0) store_agent(&ctl->epoch, epoch + 1u);
+#pragma unroll
+  for (int j = 0; j < kScanFAcc; ++j) {
+    const unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
+    Vec4<float> o;
+    o.v[0] = tile_excl + (wave_excl + excl[j]);
+    o.v[1] = o.v[0] + x[j][0];
+    o.v[2] = o.v[1] + x[j][1];
+    o.v[3] = o.v[2] + x[j][2];
+    if (whole) {
+      if (Reverse)
+        store4(offs + (n - 4 - i), Vec4<float>{{o.v[3], o.v[2], o.v[1], o.v[0]}});
+      else
+        store4(offs + i, o);
+    } else {
+#pragma unroll
+      for (int c = 0; c < kVec; ++c)
+        if (i + c < n) offs[Reverse ? n - 1 - (i + c) : i + c] = o.v[c];
+    }
+  }
+}
+
 // ------------------------------------------------------------------ row scans
 // scanl / scanr of a two-dimensional array scan every row on its own (section 2:
 // in a multidimensional array the scan is performed over each row).  A row is one
@@ -1086,41 +1218,50 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
 template <class E, bool Reverse, int L>
 __global__ __launch_bounds__(kBlock) void rowscan_kernel(const KArgs a) {
   static_assert(L == 16 || L == kWave || L == kBlock, "lanes per row");
+  using T = typename E::R;
+  using Op = typename std::conditional<std::is_same<T, float>::value, AddF32, AddI32>::type;
   constexpr int kRows = kBlock / L;                     // rows a workgroup handles at a time
-  __shared__ int lds[kWavesPerBlock];
-  int *out = static_cast<int *>(a.out[1]);
+  __shared__ T lds[kWavesPerBlock];
+  T *out = static_cast<T *>(a.out[1]);
   const int rows = a.aux, w = a.w;
   const int sub = (int)threadIdx.x % L, which = (int)threadIdx.x / L;
   for (int r0 = (int)blockIdx.x * kRows; r0 < rows; r0 += (int)gridDim.x * kRows) {
     const int r = r0 + which;
-    int carry = 0;
+    T carry = T();
     // every lane runs the same number of steps, so DPP and the barriers stay converged
     for (int c0 = 0; c0 < w; c0 += L) {
       const int c = c0 + sub;
       const bool live = r < rows && c < w;
       const int e = r * w + (Reverse ? w - 1 - c : c);
-      const int x = live ? E::template eval<0>(a, e) : 0;
-      int inc, total;
+      const T x = live ? E::template eval<0>(a, e) : T();
+      // inclusive prefix over the L lanes, the exclusive one by moving it one lane on (a
+      // floating-point sum cannot give its last term back), and the step's total
+      T inc, exc, total;
       if (L == 16) {
-        inc = row_scan_inclusive<AddI32>(x);
+        inc = row_scan_inclusive<Op>(x);
+        exc = dpp_move<kRowShr1>(T(), inc);
         total = __shfl(inc, 15, 16);
       } else if (L == kWave) {
-        inc = wave_scan_inclusive<AddI32>(x);
-        total = __builtin_amdgcn_readlane(inc, kWave - 1);
+        inc = wave_scan_inclusive<Op>(x);
+        exc = lane_prev(T(), inc);
+        total = from_bits<T>(__builtin_amdgcn_readlane(as_bits(inc), kWave - 1));
       } else {
-        inc = wave_scan_inclusive<AddI32>(x);
+        inc = wave_scan_inclusive<Op>(x);
+        exc = lane_prev(T(), inc);
         __syncthreads();                                  // lds of the previous step has been read
         if (lane_id() == kWave - 1) lds[wave_id()] = inc;
         __syncthreads();
-        total = 0;
+        T before = T();
+        total = T();
 #pragma unroll
         for (int k = 0; k < kWavesPerBlock; ++k) {
-          const int t = lds[k];
-          if (k < wave_id()) inc += t;
+          const T t = lds[k];
+          if (k < wave_id()) before += t;
           total += t;
         }
+        exc = before + exc;
       }
-      if (live) out[e] = carry + inc - x;
+      if (live) out[e] = carry + exc;
       carry += total;
     }
   }

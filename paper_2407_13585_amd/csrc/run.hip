@@ -128,7 +128,8 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
       return unsupported("scan cluster shape");
     const int sc = scans[0];
     const int x = m.nodes[sc].arg[0];
-    if (m.nodes[sc].dtype != FC_I32) return unsupported("scan of f32");
+    if (m.nodes[sc].dtype != FC_I32 && (!scatters.empty() || !folds.empty() || c.fused_away[sc]))
+      return unsupported("a scan of f32 can only be stored");
     // a two-dimensional array is scanned row by row (one row: the same as one dimension)
     const bool by_rows = m.nodes[sc].rank == 2 && m.nodes[sc].shape[0] != 1;
     if (by_rows && (!scatters.empty() || !folds.empty() || c.fused_away[sc]))

@@ -109,7 +109,8 @@ def test_scan_then_gather_and_scanr():
     rng = np.random.default_rng(5)
     g = PG.scan_then_gather()
     check(g, random_inputs(g, rng, {"is": PG.N, "xs": 100}), exact=("bs",), expect_clusters=2)
-    for n in (1, 5, 4097, 100003):
+    # scanr reads whole tiles in mirrored 128-bit groups when the length is a multiple of four
+    for n in (1, 5, 4097, 100003, 100004, 3 * 12288, 12288 + 8):
         g = Graph()
         g.add("x", "input", "i32", (n,))
         g.add("z", "scanr", "i32", (n,), fn="add", args=("x",), output=True)
@@ -151,6 +152,73 @@ def test_scatter_add_fp32():
             got = prog.fetch("h").astype(np.float64)
             assert np.all(np.abs(got - env["h"]) <= 1e-5 * scale + 1e-30), (n, k)
             assert prog.kernels()[-1].startswith("scatter.add[")
+
+
+def prefix_scale(x, reverse):
+    """Sum of the magnitudes that go into every exclusive prefix (suffix) of the rows of x."""
+    a = np.abs(np.asarray(x, dtype=np.float64))
+    a = a.reshape(-1, a.shape[-1]) if a.ndim > 1 else a.reshape(1, -1)
+    if reverse:
+        a = a[:, ::-1]
+    sc = np.zeros_like(a)
+    np.cumsum(a[:, :-1], axis=1, out=sc[:, 1:])
+    return (sc[:, ::-1] if reverse else sc).reshape(np.asarray(x).shape)
+
+
+def test_scans_of_fp32():
+    # prefix sums of fp32 arrays: the same single pass with the aggregates travelling as bit
+    # patterns.  The kernel adds in a fixed tree order, the reference sums exactly and rounds once:
+    # every prefix within 1e-5 of the magnitudes summed (the bound of the folds).  Lengths around
+    # the tile (8192), the 128-bit group and the group of 256 tiles; scanr with a length that is
+    # and is not a multiple of four (mirrored 128-bit reads, or element by element).
+    rng = np.random.default_rng(12)
+    for n in (1, 3, 8191, 8192, 8193, 100003, 100004, (1 << 21) + 8192 * 3 + 5, 1 << 22):
+        g = Graph()
+        g.add("x", "input", "f32", (n,))
+        g.add("l", "scanl", "f32", (n,), fn="add", args=("x",), output=True)
+        g.add("r", "scanr", "f32", (n,), fn="add", args=("x",), output=True)
+        ins = {"x": rng.standard_normal(n).astype(F32)}
+        env = evaluate(g, ins)
+        prog = device_program(g, ins, fc().fc_partition_trivial(g))
+        for _ in range(2):                                       # the status words are reused
+            prog.run()
+            for name, rev in (("l", False), ("r", True)):
+                got = prog.fetch(name).astype(np.float64)
+                tol = 1e-5 * prefix_scale(ins["x"], rev) + 1e-30
+                bad = np.flatnonzero(np.abs(got - env[name].astype(np.float64)) > tol)
+                assert bad.size == 0, (n, name, bad[:5], got[bad[:5]], env[name][bad[:5]])
+            assert prog.control_words()[1] == 0
+        assert sorted(prog.kernels()) == ["scan[in0:f32]+offs", "scanr[in0:f32]+offs"]
+    # positive terms of one size: the running sum grows to 2^22 times a term, the worst case for the
+    # rounding of a sequential sum; the tree order stays far inside the bound
+    n = 1 << 22
+    g = Graph()
+    g.add("x", "input", "f32", (n,))
+    g.add("y", "map", "f32", (n,), fn="affine", fparam=(0.5, 0.25), args=("x",))
+    g.add("l", "scanl", "f32", (n,), fn="add", args=("y",), output=True)
+    ins = {"x": rng.uniform(0.0, 1.0, size=n).astype(F32)}
+    env = evaluate(g, ins)
+    for part in (fc().fc_plan(g, "bytes"), None):
+        prog = device_program(g, ins, part)
+        prog.run()
+        got = prog.fetch("l").astype(np.float64)
+        assert np.all(np.abs(got - env["l"].astype(np.float64)) <= 1e-5 * prefix_scale(env["y"], False) + 1e-30)
+        if part is not None:
+            assert prog.kernels() == ["scan[map2(in0:f32)]+offs"], prog.kernels()
+    # two dimensions: row by row
+    for (rows, w) in ((3, 1), (37, 16), (300, 17), (65, 65), (40, 1000), (7, 1025), (2, 70001)):
+        g = Graph()
+        g.add("x", "input", "f32", (rows, w))
+        g.add("l", "scanl", "f32", (rows, w), fn="add", args=("x",), output=True)
+        g.add("r", "scanr", "f32", (rows, w), fn="add", args=("x",), output=True)
+        ins = {"x": rng.standard_normal((rows, w)).astype(F32)}
+        env = evaluate(g, ins)
+        prog = device_program(g, ins, fc().fc_partition_trivial(g))
+        prog.run()
+        for name, rev in (("l", False), ("r", True)):
+            got = prog.fetch(name).astype(np.float64)
+            assert np.all(np.abs(got - env[name].astype(np.float64)) <= 1e-5 * prefix_scale(ins["x"], rev) + 1e-30), (rows, w, name)
+        assert all(k.startswith("rowscan") for k in prog.kernels())
 
 
 def test_row_scans():

@@ -344,6 +344,53 @@ def test_scan_of_a_two_dimensional_array_scans_every_row():
     assert run(g1, {"a": a[:1]})["l"][0].tolist() == [sum(a[0].tolist()[:j]) for j in range(7)]
 
 
+def test_scan_of_fp32_is_the_exactly_summed_prefix_rounded_once():
+    # the reference of an fp32 (+) scan: every prefix summed without rounding error, then rounded
+    # to fp32 once.  Pinned by exact rational arithmetic on a short array, by inputs whose
+    # prefixes are representable (powers of two, ones), and by scanr = scanl of the mirror image.
+    from fractions import Fraction
+    rng = np.random.default_rng(33)
+    a = (rng.standard_normal(40) * 10.0 ** rng.integers(-6, 6, size=40)).astype(np.float32)
+    g = Graph()
+    g.add("a", "input", "f32", (40,))
+    g.add("l", "scanl", "f32", (40,), fn="add", args=("a",))
+    g.add("r", "scanr", "f32", (40,), fn="add", args=("a",))
+    env = run(g, {"a": a})
+    exact = [Fraction(float(v)) for v in a]
+    for i in range(40):
+        before, after = sum(exact[:i], Fraction(0)), sum(exact[i + 1:], Fraction(0))
+        # the double nearest to the rational sum, then the float nearest to that double: with 40
+        # terms of at most 24 bits the double is exact or one rounding away, which the fp32
+        # rounding absorbs except on a tie; allow the neighbouring float
+        for got, want in ((env["l"][i], before), (env["r"][i], after)):
+            assert abs(Fraction(float(got)) - want) <= Fraction(float(np.spacing(np.float32(abs(float(want)))))) / 2 + Fraction(1, 10 ** 40)
+    assert env["l"].dtype == np.float32 and env["l"][0] == 0.0 and env["r"][-1] == 0.0
+    halves = np.array([2.0 ** -k for k in range(24)], dtype=np.float32)
+    g2 = Graph()
+    g2.add("a", "input", "f32", (24,))
+    g2.add("l", "scanl", "f32", (24,), fn="add", args=("a",))
+    assert run(g2, {"a": halves})["l"].tolist() == [0.0] + [2.0 - 2.0 ** -(k - 1) for k in range(1, 24)]
+    ones = np.ones(5000, np.float32)
+    g3 = Graph()
+    g3.add("a", "input", "f32", (5000,))
+    g3.add("l", "scanl", "f32", (5000,), fn="add", args=("a",))
+    g3.add("r", "scanr", "f32", (5000,), fn="add", args=("a",))
+    env3 = run(g3, {"a": ones})
+    assert np.array_equal(env3["l"], np.arange(5000, dtype=np.float32))
+    assert np.array_equal(env3["r"], np.arange(5000, dtype=np.float32)[::-1])
+    # two dimensions: every row on its own
+    b = rng.standard_normal((3, 9)).astype(np.float32)
+    g4 = Graph()
+    g4.add("a", "input", "f32", (3, 9))
+    g4.add("l", "scanl", "f32", (3, 9), fn="add", args=("a",))
+    l4 = run(g4, {"a": b})["l"]
+    for i in range(3):
+        g5 = Graph()
+        g5.add("a", "input", "f32", (9,))
+        g5.add("l", "scanl", "f32", (9,), fn="add", args=("a",))
+        assert np.array_equal(l4[i], run(g5, {"a": b[i]})["l"])
+
+
 def test_compaction_invariants():
     w = C.compaction(n=50021, seed=21)
     env = evaluate(w.graph, w.inputs)
