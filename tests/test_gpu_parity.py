@@ -288,6 +288,49 @@ def test_repeated_runs_share_scratch():
         assert words[0] == 4            # one tagged launch per run
 
 
+def test_step_replays_from_a_hip_graph():
+    # fc_run_fused only enqueues kernels (no allocation, no host synchronisation, no memset), so a
+    # caller can capture a step into a HIP graph.  Captured here: the five pipelines at small sizes
+    # plus the two kernels that hand data over through scratch (column-blocked SpMV, fold over sorted
+    # gather indices).  Every replay runs on other input values, with eager copies and
+    # synchronisations in between, and is checked against the oracle.
+    import torch
+    rng = np.random.default_rng(77)
+    items = []
+    for cfg in (1, 2, 3, 4, 5):
+        items.append((cfg, build(cfg, small=True), True))
+    lengths = rng.poisson(8.0, size=20000)
+    items.append((3, C.spmv(lengths=lengths, seed=5, ncols=1200000), False))
+    big = 2200003
+    items.append((2, C.perm_gather_fold(xs=rng.standard_normal(size=big).astype(F32), idx=rng.permutation(big).astype(np.int32)), False))
+    progs = []
+    for cfg, w, dup in items:
+        g, part = plan(w.graph, dup)
+        progs.append(device_program(g, w.inputs, part))
+    assert "column-blocked" in progs[5].kernels()[0] and "binned" in progs[6].kernels()[0]
+    for p in progs:                                           # first launches outside the capture
+        p.run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        for p in progs:
+            p.run()
+    for rep in range(3):
+        for (cfg, w, dup), p in zip(items, progs):
+            for name, a in list(w.inputs.items()):
+                if a.dtype == F32:                            # other values every time
+                    w.inputs[name] = (a * F32(0.5) + rng.uniform(-0.1, 0.1, size=a.shape).astype(F32)).astype(F32)
+                p.upload(name, w.inputs[name])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (cfg, w, dup), p in zip(items, progs):
+            env = evaluate(w.graph, w.inputs)
+            compare(cfg, w, env, p, w.graph.outputs(), f"replay{rep}")
+            assert p.control_words()[1] == 0
+
+
 def test_fusion_rule_clusters_execute():
     """`simple1`, `simple2`, reverse and a diagonal cluster, each as one kernel."""
     rng = np.random.default_rng(9)
