@@ -143,6 +143,11 @@ typedef enum fc_cost {
 
 /* plan flags */
 #define FC_PLAN_NO_SPLIT 1u  /* keep the raw ILP solution (skip the connected-component split) */
+#define FC_PLAN_EXECUTABLE 2u /* choose among the clusterings fc_run_fused has kernels for: the kernels are a fixed
+                                 set of cluster shapes, and the optimum of the ILP may contain a legal cluster that
+                                 is not among them (fc_run_fused would answer FC_E_UNSUPPORTED).  With this flag the
+                                 result is the cheapest clustering that runs; FC_E_UNSUPPORTED if there is none,
+                                 i.e. some combinator has no kernel even on its own */
 
 typedef struct fc_buffer {
   void   *ptr;    /* DEVICE pointer, 16-byte aligned; NULL = not bound */

@@ -30,6 +30,7 @@ FN = {"": 0, "ident": 1, "affine": 2, "sin_x_mul_x": 3, "sq_plus_one": 4, "mul2"
 OP = {"add": 64, "max": 65, "mul": 66, "overwrite": 67}
 COST = {"clusters": 0, "fused_edges": 1, "arrays": 2, "reads": 3, "reads_writes": 4, "bytes": 5}
 FC_PLAN_NO_SPLIT = 1
+FC_PLAN_EXECUTABLE = 2
 FC_NODE_OUTPUT = 1
 
 ERRORS = {-1: "FC_E_BADGRAPH", -2: "FC_E_ILLEGAL_PARTITION", -3: "FC_E_UNSUPPORTED", -4: "FC_E_UNBOUND",
@@ -204,11 +205,16 @@ def fc_num_edges(graph) -> int:
     return n.value
 
 
-def fc_plan(graph, cost: str = "bytes", no_split: bool = False) -> Partition:
+def _plan_flags(no_split: bool, executable: bool) -> int:
+    return (FC_PLAN_NO_SPLIT if no_split else 0) | (FC_PLAN_EXECUTABLE if executable else 0)
+
+
+def fc_plan(graph, cost: str = "bytes", no_split: bool = False, executable: bool = False) -> Partition:
+    """executable: choose among the clusterings the library has kernels for (FC_PLAN_EXECUTABLE)."""
     g = _cg(graph)
     part = Partition.empty(len(g.names), g.n_edges)
     cp = part._c()
-    _check(lib().fc_plan(g.ref(), COST[cost], FC_PLAN_NO_SPLIT if no_split else 0, C.byref(cp)))
+    _check(lib().fc_plan(g.ref(), COST[cost], _plan_flags(no_split, executable), C.byref(cp)))
     return _finish(part, cp)
 
 
@@ -226,11 +232,11 @@ def _weights(weights) -> "C.Array":
     return (C.c_double * len(COST))(*vec)
 
 
-def fc_plan_weighted(graph, weights, no_split: bool = False) -> Partition:
+def fc_plan_weighted(graph, weights, no_split: bool = False, executable: bool = False) -> Partition:
     g = _cg(graph)
     part = Partition.empty(len(g.names), g.n_edges)
     cp = part._c()
-    _check(lib().fc_plan_weighted(g.ref(), _weights(weights), FC_PLAN_NO_SPLIT if no_split else 0, C.byref(cp)))
+    _check(lib().fc_plan_weighted(g.ref(), _weights(weights), _plan_flags(no_split, executable), C.byref(cp)))
     return _finish(part, cp)
 
 
@@ -248,13 +254,13 @@ def cost_vector(graph, pi: Sequence[int]) -> np.ndarray:
     return out
 
 
-def fc_plan_greedy(graph, direction: str, cost: str = "bytes", no_split: bool = False) -> Partition:
+def fc_plan_greedy(graph, direction: str, cost: str = "bytes", no_split: bool = False, executable: bool = False) -> Partition:
     """direction: 'top_down' or 'bottom_up'."""
     g = _cg(graph)
     part = Partition.empty(len(g.names), g.n_edges)
     cp = part._c()
     d = {"top_down": 0, "bottom_up": 1}[direction]
-    _check(lib().fc_plan_greedy(g.ref(), d, COST[cost], FC_PLAN_NO_SPLIT if no_split else 0, C.byref(cp)))
+    _check(lib().fc_plan_greedy(g.ref(), d, COST[cost], _plan_flags(no_split, executable), C.byref(cp)))
     return _finish(part, cp)
 
 

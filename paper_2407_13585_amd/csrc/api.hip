@@ -79,6 +79,19 @@ int fc_num_edges(const fc_graph *g, int32_t *n_edges) {
   });
 }
 
+// FC_PLAN_EXECUTABLE: only clusterings every cluster of which has a kernel instance
+static fc::Admissible executable_only(const fc::Model &m, uint32_t flags) {
+  if (!(flags & FC_PLAN_EXECUTABLE)) return fc::Admissible();
+  return [&m](const fc::Clustering &c) {
+    for (const auto &members : fc::clusters_of(m, c)) {
+      fc::ClusterLaunch cl;
+      std::string why;
+      if (fc::plan_cluster(m, c, members, cl, why) != FC_OK) return false;
+    }
+    return true;
+  };
+}
+
 int fc_plan(const fc_graph *g, int cost_fn, uint32_t flags, fc_partition *out) {
   return guarded([&]() {
     fc::Model m;
@@ -88,7 +101,7 @@ int fc_plan(const fc_graph *g, int cost_fn, uint32_t flags, fc_partition *out) {
     fc::Clustering c;
     int n_clusters = 0;
     double cost = 0;
-    rc = fc::choose_clustering(m, cost_fn, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err);
+    rc = fc::choose_clustering(m, cost_fn, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err, executable_only(m, flags));
     if (rc != FC_OK) return fail(rc, err);
     return fill_partition(m, c, n_clusters, cost, out);
   });
@@ -104,7 +117,8 @@ int fc_plan_weighted(const fc_graph *g, const double *weights, uint32_t flags, f
     fc::Clustering c;
     int n_clusters = 0;
     double cost = 0;
-    rc = fc::choose_clustering_weighted(m, weights, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err);
+    rc = fc::choose_clustering_weighted(m, weights, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err,
+                                        executable_only(m, flags));
     if (rc != FC_OK) return fail(rc, err);
     return fill_partition(m, c, n_clusters, cost, out);
   });
@@ -120,7 +134,8 @@ int fc_plan_greedy(const fc_graph *g, int direction, int cost_fn, uint32_t flags
     fc::Clustering c;
     int n_clusters = 0;
     double cost = 0;
-    rc = fc::choose_greedy(m, direction, cost_fn, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err);
+    rc = fc::choose_greedy(m, direction, cost_fn, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err,
+                           executable_only(m, flags));
     if (rc != FC_OK) return fail(rc, err);
     return fill_partition(m, c, n_clusters, cost, out);
   });

@@ -35,6 +35,8 @@ struct Search {
   bool aborted = false;
   std::vector<int> forced;         // per node: representative of the set it must share a cluster with
   bool stop_at_first = false;      // feasibility question only
+  const Admissible *admissible = nullptr;   // extra condition on complete clusterings
+  bool split = true;                        // it is judged after the connected-component split
   // block graph: adj[b] = bitmask of blocks that must run strictly after b
   std::vector<uint64_t> adj;
 
@@ -120,7 +122,14 @@ struct Search {
     std::string err;
     if (derive_and_check(m, pi, c, err) != FC_OK) return;
     double cost = objective(c);
-    if (cost < best) { best = cost; best_pi = pi; }
+    if (!(cost < best)) return;
+    if (admissible && *admissible) {
+      Clustering shaped = c, again;
+      if (split) split_components(m, shaped); else renumber_levels(m, shaped);
+      if (derive_and_check(m, shaped.pi, again, err) != FC_OK || !(*admissible)(again)) return;
+    }
+    best = cost;
+    best_pi = pi;
     if (stop_at_first) aborted = true;
   }
 
@@ -202,15 +211,15 @@ void unit_weights(int cost_fn, double *w) {
 }  // namespace
 
 int choose_clustering(const Model &m, int cost_fn, bool split, Clustering &out, int &n_clusters, double &cost,
-                      std::string &err) {
+                      std::string &err, const Admissible &admissible) {
   if (cost_fn < FC_COST_CLUSTERS || cost_fn > FC_COST_BYTES) { err = "unknown cost function"; return FC_E_ARG; }
   double w[kCosts];
   unit_weights(cost_fn, w);
-  return choose_clustering_weighted(m, w, split, out, n_clusters, cost, err);
+  return choose_clustering_weighted(m, w, split, out, n_clusters, cost, err, admissible);
 }
 
 int choose_clustering_weighted(const Model &m, const double *weights, bool split, Clustering &out, int &n_clusters,
-                               double &cost, std::string &err) {
+                               double &cost, std::string &err, const Admissible &admissible) {
   bool any = false;
   for (int k = 0; k < kCosts; ++k) {
     if (!(weights[k] >= 0) || weights[k] > 1e300) { err = "cost weights must be finite and not negative"; return FC_E_ARG; }
@@ -221,9 +230,15 @@ int choose_clustering_weighted(const Model &m, const double *weights, bool split
   for (int a = 0; a < m.n; ++a) non_input += !m.is_input(a);
   if (non_input > 64) { err = "the exact chooser handles at most 64 combinators"; return FC_E_LIMIT; }
   Search s(m, weights, 200000000LL);
+  s.admissible = &admissible;
+  s.split = split;
   s.go(0);
   if (s.aborted) { err = "search limit reached before optimality was proven"; return FC_E_LIMIT; }
-  if (s.best_pi.empty() && non_input > 0) { err = "no feasible clustering"; return FC_E_ILLEGAL_PARTITION; }
+  if (s.best_pi.empty() && non_input > 0) {
+    if (admissible) { err = "no clustering passes the extra condition"; return FC_E_UNSUPPORTED; }
+    err = "no feasible clustering";
+    return FC_E_ILLEGAL_PARTITION;
+  }
   std::vector<int> pi = s.best_pi.empty() ? std::vector<int>(m.n, 0) : s.best_pi;
   int rc = derive_and_check(m, pi, out, err);
   if (rc != FC_OK) return rc;
@@ -239,7 +254,7 @@ int choose_clustering_weighted(const Model &m, const double *weights, bool split
 
 // --------------------------------------------------------------------------- greedy
 int choose_greedy(const Model &m, int direction, int cost_fn, bool split, Clustering &out, int &n_clusters, double &cost,
-                  std::string &err) {
+                  std::string &err, const Admissible &admissible) {
   if (cost_fn < FC_COST_CLUSTERS || cost_fn > FC_COST_BYTES) { err = "unknown cost function"; return FC_E_ARG; }
   int non_input = 0;
   for (int a = 0; a < m.n; ++a) non_input += !m.is_input(a);
@@ -259,6 +274,8 @@ int choose_greedy(const Model &m, int direction, int cost_fn, bool split, Cluste
     Search s(m, w, 200000000LL);
     for (auto &p : accepted) s.force_together(p.first, p.second);
     s.stop_at_first = first_only;
+    s.admissible = &admissible;
+    s.split = split;
     return s;
   };
   for (int e : edges) {
@@ -272,6 +289,7 @@ int choose_greedy(const Model &m, int direction, int cost_fn, bool split, Cluste
   }
   Search s = make_search(false);
   s.go(0);
+  if (s.best_pi.empty() && !s.aborted && admissible) { err = "no clustering passes the extra condition"; return FC_E_UNSUPPORTED; }
   if (s.aborted || s.best_pi.empty()) { err = "greedy search failed"; return FC_E_LIMIT; }
   int rc = derive_and_check(m, s.best_pi, out, err);
   if (rc != FC_OK) return rc;

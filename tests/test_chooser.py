@@ -483,3 +483,79 @@ def test_fit_of_cost_coefficients_recovers_a_linear_model():
     assert w["clusters"] == pytest.approx(6.0, rel=0.1) and w["bytes"] == pytest.approx(2e-7, rel=0.1)
     with pytest.raises(ValueError):
         tune.fit_weights(costs, np.zeros(40))
+
+
+# ------------------------------------------------------------------ clusterings the library can execute
+def unsupported_optimum_graphs():
+    """Programs whose cheapest legal clustering has a cluster no kernel is built for."""
+    out = {}
+    n = 1000
+    g = Graph()                                  # a predicate that is stored and scanned: one diagonal cluster
+    g.add("v", "input", "i32", (n,))
+    g.add("flags", "map", "i32", (n,), fn="mod_eq", iparam=(3, 0), args=("v",), output=True)
+    g.add("offs", "scanl", "i32", (n,), fn="add", args=("flags",), output=True)
+    out["stored predicate + scan"] = g
+    g = Graph()                                  # prefix sums and the total of an fp32 array in one pass
+    g.add("x", "input", "f32", (n,))
+    g.add("y", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("x",))
+    g.add("l", "scanl", "f32", (n,), fn="add", args=("y",), output=True)
+    g.add("t", "fold", "f32", (1,), fn="add", args=("y",), output=True)
+    out["fp32 scan + total"] = g
+    g = Graph()                                  # three stored arrays from one input
+    g.add("x", "input", "f32", (n,))
+    g.add("a", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("x",), output=True)
+    g.add("b", "map", "f32", (n,), fn="sq_plus_one", args=("x",), output=True)
+    g.add("c", "map", "f32", (n,), fn="exp_neg", args=("x",), output=True)
+    out["three stores"] = g
+    return out
+
+
+def runs(g, part):
+    try:
+        for i in range(part.n_clusters):
+            fc.fc_cluster_kernel(g, part, i)
+        return True
+    except fc.FcError as e:
+        assert e.name == "FC_E_UNSUPPORTED"
+        return False
+
+
+@pytest.mark.parametrize("name", sorted(unsupported_optimum_graphs()))
+def test_executable_plan_is_the_cheapest_clustering_with_kernels(name):
+    g = unsupported_optimum_graphs()[name]
+    nodes = [i for i, nd in enumerate(g.nodes) if nd.kind != "input"]
+    for cost in ("bytes", "clusters", "reads_writes"):
+        free = fc.fc_plan(g, cost, no_split=True)
+        tied = fc.fc_plan(g, cost, no_split=True, executable=True)
+        assert runs(g, tied)
+        # brute force: every legal clustering, kept if every cluster of it has a kernel
+        best = float("inf")
+        for blocks in OC.set_partitions(nodes):
+            v = OC.judge(g, blocks)
+            if not v.legal:
+                continue
+            pi = [0] * len(g.nodes)
+            for pos, c in enumerate(v.sequence):
+                for a in blocks[c]:
+                    pi[a] = pos + 1
+            if runs(g, fc.fc_partition_check(g, pi)):
+                best = min(best, OC.cost(g, blocks, v, cost))
+        assert tied.cost == pytest.approx(best), (name, cost)
+        assert tied.cost >= free.cost - 1e-9
+        if cost == "bytes":
+            assert not runs(g, free) and tied.cost > free.cost, name    # the flag made a difference
+    # with the split (the default) the result still runs
+    assert runs(g, fc.fc_plan(g, "bytes", executable=True))
+    assert runs(g, fc.fc_plan_greedy(g, "top_down", "bytes", executable=True))
+    assert runs(g, fc.fc_plan_weighted(g, {"clusters": 1.0, "bytes": 1e-4}, executable=True))
+
+
+def test_executable_plan_changes_nothing_where_the_optimum_already_runs():
+    for name in ("single_loop", "greedy_top_down_bad", "scatter_example", "simple5"):
+        g = PG.ALL[name]()
+        a, b = fc.fc_plan(g, "bytes"), fc.fc_plan(g, "bytes", executable=True)
+        assert runs(g, a) and a.cost == b.cost and clusters_of(a, g) == clusters_of(b, g)
+    for cfg in (1, 2, 3, 4, 5):
+        g = build(cfg, small=True).graph
+        a, b = fc.fc_plan(g, "bytes"), fc.fc_plan(g, "bytes", executable=True)
+        assert runs(g, a) and a.cost == b.cost

@@ -221,6 +221,32 @@ def test_scans_of_fp32():
         assert all(k.startswith("rowscan") for k in prog.kernels())
 
 
+def test_programs_whose_optimum_has_no_kernel_run_with_an_executable_plan():
+    # the cheapest legal clustering of these programs contains a cluster the library has no
+    # kernel for; planned with FC_PLAN_EXECUTABLE they run fused as far as the kernels go
+    from test_chooser import unsupported_optimum_graphs
+    rng = np.random.default_rng(14)
+    for name, g in unsupported_optimum_graphs().items():
+        ins = {n.name: (rng.integers(0, 2 ** 31, size=n.shape, dtype=np.int32) if n.dtype == "i32"
+                        else rng.uniform(0.0, 1.0, size=n.shape).astype(F32)) for n in g.nodes if n.kind == "input"}
+        env = evaluate(g, ins)
+        with pytest.raises(fc().FcError):
+            device_program(g, ins, fc().fc_plan(g, "bytes")).run()
+        part = fc().fc_plan(g, "bytes", executable=True)
+        prog = device_program(g, ins, part)
+        prog.run()
+        for out in g.outputs():
+            got, ref = prog.fetch(out), env[out]
+            if g[out].dtype == "i32":
+                P.assert_bit_exact(got, ref, f"{name}/{out}")
+            elif g[out].kind in ("scanl", "fold"):
+                scale = prefix_scale(env["y"], False) if g[out].kind == "scanl" else np.abs(env["y"].astype(np.float64)).sum()
+                assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= 1e-5 * scale + 1e-30), (name, out)
+            else:
+                P.assert_ulp(got, np.asarray(ref, dtype=np.float64).astype(F32), 4, f"{name}/{out}")
+        assert prog.control_words()[1] == 0
+
+
 def test_row_scans():
     # scans of two-dimensional arrays run row by row; row lengths on both sides of the
     # 16-lane / wave / workgroup variants, ragged against their step, with and without a fused producer
