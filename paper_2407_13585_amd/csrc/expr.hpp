@@ -56,6 +56,27 @@ inline void mod_eq_constants(Slot &s) {
   s.m[2] = 0xffffffffu / k;
 }
 
+// The element programs of a cluster once more, as code for the interpreting kernel
+// (interp_kernel), which runs clusters that no compiled instance matches.  A stack
+// machine in post-order: a value per array read, generated or computed, consumed by the
+// map, store or fold above it; a gather evaluates its index, then its source with the
+// index as the position (kCodeEnter / kCodeLeave).
+constexpr int kMaxCode = 64;
+constexpr int kInterpDepth = 4;       // values below the top of the interpreter's stack
+constexpr int kInterpGathers = 3;     // nesting of gathers it follows
+enum : unsigned char {
+  kCodeEnd = 0,
+  kCodeIn,      // a = external array: push its element at the position
+  kCodeGen,     // a = index function, b = slot: push its value at the position
+  kCodeMap,     // a = element function, b = slot, c = number of arguments: replace them by the result
+  kCodeEnter,   // pop an index and make it the position
+  kCodeLeave,   // back to the position before the matching kCodeEnter
+  kCodeStore,   // a = output array: pop a value into it at the element's own position (c = 1: leave it on the stack)
+  kCodeFold     // a = output array, b = reducer (kFold...): pop a value into the accumulator
+};
+enum : unsigned char { kFoldAddF32 = 0, kFoldMaxF32, kFoldMulF32, kFoldAddI32, kFoldMaxI32 };
+struct Code { unsigned char op, a, b, c; };
+
 struct KArgs {    // arguments of one cluster launch
   const void *in[kMaxIn];   // external arrays read by the cluster
   void *out[kMaxOut];       // arrays the cluster writes
@@ -64,6 +85,7 @@ struct KArgs {    // arguments of one cluster launch
   int h;                    // outer extent
   int aux;                  // skeleton specific (rows of a segmented fold, ...)
   Slot p[kMaxSlots];
+  Code code[kMaxCode];      // elementwise clusters only; kCodeEnd after the last instruction
 };
 
 template <class T> struct Vec4 { T v[4]; };

@@ -384,6 +384,18 @@ const std::vector<Instance> &registry() {
   return r;
 }
 
+static hipError_t launch_interp(const KArgs &a, const LaunchCtx &c) {
+  return launch_k(&interp_kernel, grid_for(a.n, kBlock * kVec, resident_grid(&interp_kernel)), c.stream, a, c.ctl, c.partials);
+}
+const Instance *interpreter_instance() {
+  static const Instance inst = [] {
+    Instance i{"", &launch_interp};
+    i.variant = "interpreted";
+    return i;
+  }();
+  return &inst;
+}
+
 const Instance *find_instance(const std::string &sig, const KArgs &a) {
   for (const Instance &i : registry())
     if (i.sig == sig && (!i.accept || i.accept(a))) return &i;

@@ -215,6 +215,182 @@ __global__ __launch_bounds__(kBlock) void store_fold_kernel(const KArgs a, Contr
   fold_finish<Op>(acc, a, 1, ctl, partials);
 }
 
+// ------------------------------------------------------------------ interpreted elementwise clusters
+// Any cluster of maps, generates and gathers that ends in up to kMaxOut stored arrays
+// or in stored arrays and one fold, for which no kernel was compiled: the element
+// programs are run from KArgs::code, four elements per lane at a time.  The top of the
+// value stack stays in registers, what lies below in LDS (a column per lane: registers
+// cannot be indexed by a run-time number); the positions that gathers suspend are at most
+// kInterpGathers deep and stay in registers.  Every branch depends on the code only, which
+// is the same for all lanes.  Results are the same as a compiled instance's: the same
+// element functions, applied in the same order.  A fallback: several times the
+// instructions of a compiled instance per element, 4-byte accesses.
+// x[k][e]: argument k of element e; the function is picked once for the V elements
+template <int V>
+__device__ __forceinline__ void interp_map(int fn, const Slot &s, const unsigned (&x)[5][V], unsigned (&r)[V]) {
+  auto f = [&](int k, int e) { return from_bits<float>((int)x[k][e]); };
+  auto bits = [](float v) { return (unsigned)as_bits(v); };
+#define FC_EACH(expr) _Pragma("unroll") for (int e = 0; e < V; ++e) r[e] = (expr); break
+  switch (fn) {
+    case FC_FN_IDENT: FC_EACH(x[0][e]);
+    case FC_FN_AFFINE: FC_EACH(bits(FnAffine::apply(s, f(0, e))));
+    case FC_FN_SIN_X_MUL_X: FC_EACH(bits(FnSinXMulX::apply(s, f(0, e))));
+    case FC_FN_SQ_PLUS_ONE: FC_EACH(bits(FnSqPlusOne::apply(s, f(0, e))));
+    case FC_FN_MUL2: FC_EACH(bits(FnMul2::apply(s, f(0, e), f(1, e))));
+    case FC_FN_ADD2: FC_EACH(bits(FnAdd2::apply(s, f(0, e), f(1, e))));
+    case FC_FN_ADD3: FC_EACH(bits(FnAdd3::apply(s, f(0, e), f(1, e), f(2, e))));
+    case FC_FN_ADD5: FC_EACH(bits(FnAdd5::apply(s, f(0, e), f(1, e), f(2, e), f(3, e), f(4, e))));
+    case FC_FN_EXP_NEG: FC_EACH(bits(FnExpNeg::apply(s, f(0, e))));
+    case FC_FN_MOD_EQ: FC_EACH((unsigned)FnModEq::apply(s, (int)x[0][e]));
+    default: FC_EACH(0u);
+  }
+}
+template <int V>
+__device__ __forceinline__ void interp_gen(int fn, const Slot &s, const KArgs &a, const int (&at)[V], unsigned (&r)[V]) {
+  switch (fn) {
+    case FC_FN_IOTA: FC_EACH((unsigned)GenIota::apply(s, a, at[e]));
+    case FC_FN_IOTA_REV: FC_EACH((unsigned)GenIotaRev::apply(s, a, at[e]));
+    case FC_FN_CLAMP_SHIFT_2D: FC_EACH((unsigned)GenClampShift2D::apply(s, a, at[e]));
+    case FC_FN_ROW_OF_2D: FC_EACH((unsigned)GenRowOf2D::apply(s, a, at[e]));
+    case FC_FN_CONST_I32: FC_EACH((unsigned)GenConst::apply(s, a, at[e]));
+    default: FC_EACH(0u);
+  }
+}
+#undef FC_EACH
+__device__ __forceinline__ unsigned interp_fold(int op, unsigned acc, unsigned v) {
+  switch (op) {
+    case kFoldAddF32: return (unsigned)as_bits(AddF32::apply(from_bits<float>((int)acc), from_bits<float>((int)v)));
+    case kFoldMaxF32: return (unsigned)as_bits(MaxF32::apply(from_bits<float>((int)acc), from_bits<float>((int)v)));
+    case kFoldMulF32: return (unsigned)as_bits(MulF32::apply(from_bits<float>((int)acc), from_bits<float>((int)v)));
+    case kFoldAddI32: return (unsigned)AddI32::apply((int)acc, (int)v);
+    default: return (unsigned)MaxI32::apply((int)acc, (int)v);
+  }
+}
+__device__ __forceinline__ unsigned interp_identity(int op) {
+  switch (op) {
+    case kFoldAddF32: return (unsigned)as_bits(AddF32::identity());
+    case kFoldMaxF32: return (unsigned)as_bits(MaxF32::identity());
+    case kFoldMulF32: return (unsigned)as_bits(MulF32::identity());
+    case kFoldAddI32: return (unsigned)AddI32::identity();
+    default: return (unsigned)MaxI32::identity();
+  }
+}
+
+// Runs the cluster's code for the V consecutive elements that start at `first` (V = 4: a
+// 128-bit group, `first` a multiple of four; V = 1: one element), so that the cost of
+// reading and decoding an instruction is shared by four elements.  `below` is this
+// lane's column of the value stack.
+template <int V>
+__device__ __forceinline__ void interp_run(const KArgs &a, unsigned first, unsigned (*below)[kVec][kBlock], unsigned &acc) {
+  using Raw = unsigned __attribute__((ext_vector_type(4)));
+  int at[V];                                           // the positions element programs read at
+  int suspended[kInterpGathers][V];
+  unsigned top[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) { at[e] = (int)first + e; top[e] = 0u; }
+  int gathers = 0, count = 0;                          // the same in every lane
+  auto push_room = [&]() {
+    if (count > 0) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) below[count - 1][e][threadIdx.x] = top[e];
+    }
+    ++count;
+  };
+  auto pop = [&]() {
+    --count;
+    if (count > 0) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) top[e] = below[count - 1][e][threadIdx.x];
+    }
+  };
+  for (int pc = 0; pc < kMaxCode; ++pc) {
+    const Code c = a.code[pc];
+    if (c.op == kCodeEnd) break;
+    switch (c.op) {
+      case kCodeIn: {
+        push_room();
+        const unsigned *p = static_cast<const unsigned *>(a.in[c.a]);
+        if (V == 4 && gathers == 0) {                  // the elements' own positions: one 128-bit read
+          const Raw v = *reinterpret_cast<const Raw *>(p + first);
+          top[0] = v.x; if (V > 1) { top[1 % V] = v.y; top[2 % V] = v.z; top[3 % V] = v.w; }
+        } else {
+#pragma unroll
+          for (int e = 0; e < V; ++e) top[e] = p[at[e]];
+        }
+        break;
+      }
+      case kCodeGen:
+        push_room();
+        interp_gen<V>(c.a, a.p[c.b], a, at, top);
+        break;
+      case kCodeMap: {
+        const int nargs = c.c;
+        // the last argument is the top of the stack, the others lie below it in order
+        unsigned x[5][V];
+#pragma unroll
+        for (int k = 0; k < 5; ++k)
+#pragma unroll
+          for (int e = 0; e < V; ++e)
+            x[k][e] = k >= nargs ? 0u : k == nargs - 1 ? top[e] : below[count - nargs + k][e][threadIdx.x];
+        count -= nargs - 1;
+        interp_map<V>(c.a, a.p[c.b], x, top);
+        break;
+      }
+      case kCodeEnter: {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          if (gathers == 0) suspended[0][e] = at[e]; else if (gathers == 1) suspended[1][e] = at[e]; else suspended[2][e] = at[e];
+          at[e] = (int)top[e];
+        }
+        ++gathers;
+        pop();
+        break;
+      }
+      case kCodeLeave:
+        --gathers;
+#pragma unroll
+        for (int e = 0; e < V; ++e) at[e] = gathers == 0 ? suspended[0][e] : gathers == 1 ? suspended[1][e] : suspended[2][e];
+        break;
+      case kCodeStore: {
+        unsigned *p = static_cast<unsigned *>(a.out[c.a]) + first;
+        if (V == 4) {
+          *reinterpret_cast<Raw *>(p) = Raw{top[0], top[1 % V], top[2 % V], top[3 % V]};
+        } else {
+          p[0] = top[0];
+        }
+        if (!c.c) pop();                                // c = 1: the value stays for the fold that follows
+        break;
+      }
+      default:                                          // kCodeFold
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc = interp_fold(c.b, acc, top[e]);
+        pop();
+        break;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void interp_kernel(const KArgs a, Control *ctl, unsigned long long *partials) {
+  __shared__ unsigned below[kInterpDepth][kVec][kBlock];
+  const unsigned n = (unsigned)a.n, n4 = n & ~3u;
+  // the fold of the cluster, if it has one (at most one)
+  int fold_op = -1, fold_out = 0;
+  for (int pc = 0; pc < kMaxCode && a.code[pc].op != kCodeEnd; ++pc)
+    if (a.code[pc].op == kCodeFold) { fold_op = a.code[pc].b; fold_out = a.code[pc].a; }
+  unsigned acc = fold_op >= 0 ? interp_identity(fold_op) : 0u;
+  for (unsigned i = (blockIdx.x * kBlock + threadIdx.x) * kVec; i < n4; i += gridDim.x * kBlock * kVec)
+    interp_run<kVec>(a, i, below, acc);
+  if (blockIdx.x == 0 && threadIdx.x < n - n4) interp_run<1>(a, n4 + threadIdx.x, below, acc);
+  switch (fold_op) {                                     // the same for the whole grid
+    case kFoldAddF32: fold_finish<AddF32>(from_bits<float>((int)acc), a, fold_out, ctl, partials); break;
+    case kFoldMaxF32: fold_finish<MaxF32>(from_bits<float>((int)acc), a, fold_out, ctl, partials); break;
+    case kFoldMulF32: fold_finish<MulF32>(from_bits<float>((int)acc), a, fold_out, ctl, partials); break;
+    case kFoldAddI32: fold_finish<AddI32>((int)acc, a, fold_out, ctl, partials); break;
+    case kFoldMaxI32: fold_finish<MaxI32>((int)acc, a, fold_out, ctl, partials); break;
+    default: break;
+  }
+}
+
 // ------------------------------------------------------------------ fold over a gathered table, indices binned first
 // r = fold(Op, f(table[index[i]])) for a table of more than one L2 (4 MiB per XCD) and
 // indices in no particular order.  Read directly, nearly every gather misses L2 and costs

@@ -78,6 +78,8 @@ inline int device_compute_units() {
 }
 
 const std::vector<Instance> &registry();
+// the kernel that interprets KArgs::code: takes elementwise clusters that no entry of the registry matches
+const Instance *interpreter_instance();
 // first instance with this signature whose accept() (if any) passes
 const Instance *find_instance(const std::string &sig, const KArgs &a);
 

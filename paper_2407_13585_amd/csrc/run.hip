@@ -23,6 +23,23 @@ struct Builder {
   KArgs args;
   int slots = 0;
   std::string err;
+  // the same element programs as code for the interpreting kernel (see expr.hpp, Code)
+  int n_code = 0, on_stack = 0, gathers = 0;
+  bool code_ok = true;               // fits kMaxCode, the value stack and the nesting of gathers
+
+  void emit(unsigned char op, int a = 0, int b = 0, int c = 0) {
+    if (n_code >= kMaxCode - 1) { code_ok = false; return; }   // the last entry stays kCodeEnd
+    args.code[n_code++] = Code{op, (unsigned char)a, (unsigned char)b, (unsigned char)c};
+    switch (op) {
+      case kCodeIn: case kCodeGen: ++on_stack; break;
+      case kCodeMap: on_stack -= c - 1; break;
+      case kCodeEnter: --on_stack; if (++gathers > kInterpGathers) code_ok = false; break;
+      case kCodeLeave: --gathers; break;
+      case kCodeStore: if (!c) --on_stack; break;              // c = 1: the value stays for a fold
+      default: --on_stack; break;                              // fold
+    }
+    if (on_stack > kInterpDepth + 1 || on_stack < 0) code_ok = false;
+  }
 
   Builder(const Model &m_, const Clustering &c_, const std::vector<int> &mem)
       : m(m_), c(c_), members(mem), in_cluster(mem.begin(), mem.end()) {
@@ -52,11 +69,13 @@ struct Builder {
   // element program that yields array `a` at the current iteration index
   bool expr(int a, std::string &sig) {
     const fc_node &nd = m.nodes[a];
+    const int slot = slots;
     if (!slot_for(a)) return false;
     if (!in_cluster.count(a)) {
       int k = external(a);
       if (k >= kMaxIn - 1) return fail("too many external arrays");
       sig += "in" + std::to_string(k) + (nd.dtype == FC_F32 ? ":f32" : ":i32");
+      emit(kCodeIn, k);
       return true;
     }
     switch (nd.kind) {
@@ -67,15 +86,19 @@ struct Builder {
           if (!expr(nd.arg[k], sig)) return false;
         }
         sig += ")";
+        emit(kCodeMap, nd.fn, slot, nd.nargs);
         return true;
       case FC_GENERATE:
         sig += "gen" + std::to_string(nd.fn);
+        emit(kCodeGen, nd.fn, slot);
         return true;
       case FC_GATHER:
         sig += "gather(";
         if (!expr(nd.arg[0], sig)) return false;
         sig += ",";
+        emit(kCodeEnter);
         if (!expr(nd.arg[1], sig)) return false;
+        emit(kCodeLeave);
         sig += ")";
         return true;
       default:
@@ -112,6 +135,12 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
   }
   std::string sig;
   int n = -1;
+  bool interpretable = false, reducer_ok = true;
+  auto reducer_code = [&](int fn, int dtype) {
+    if (dtype == FC_F32) return fn == FC_OP_ADD ? (int)kFoldAddF32 : fn == FC_OP_MAX ? (int)kFoldMaxF32 : (int)kFoldMulF32;
+    if (fn == FC_OP_MUL) reducer_ok = false;             // no compiled reducer either
+    return fn == FC_OP_ADD ? (int)kFoldAddI32 : (int)kFoldMaxI32;
+  };
   auto set_n = [&](int64_t v) { if (n >= 0 && n != (int)v) return false; n = (int)v; return true; };
   auto shape_from = [&](int a) { out.h = (int)m.nodes[a].shape[0]; out.w = (int)m.nodes[a].shape[1]; };
 
@@ -220,13 +249,19 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     }
     out.aux = n;
   } else {
-    if (stores.size() > 2 || folds.size() > 1 || (stores.empty() && folds.empty()) || (stores.size() == 2 && !folds.empty()))
+    // stored arrays and at most one fold; compiled instances exist for some of these shapes,
+    // the interpreting kernel takes the others
+    if (folds.size() > 1 || (stores.empty() && folds.empty()) || stores.size() + folds.size() > (size_t)kMaxOut)
       return unsupported("cluster with " + std::to_string(stores.size()) + " stored arrays and " + std::to_string(folds.size()) + " folds");
     for (size_t k = 0; k < stores.size(); ++k) {
       if (k) sig += "+";
       sig += "store[";
       if (!b.expr(stores[k], sig)) return unsupported("stored array");
       sig += "]";
+      // a stored array that is folded as well is computed once: the value stays on the stack
+      const bool folded = !folds.empty() && m.nodes[folds[0]].arg[0] == stores[k];
+      b.emit(kCodeStore, (int)k, 0, folded ? 1 : 0);
+      if (folded) b.emit(kCodeFold, (int)stores.size(), reducer_code(m.nodes[folds[0]].fn, m.nodes[folds[0]].dtype));
       if (!set_n(m.size(stores[k]))) return unsupported("iteration sizes differ inside a cluster");
       if (k == 0) shape_from(stores[0]);
       out.out_nodes[k] = stores[k];
@@ -235,12 +270,22 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
       const fc_node &f = m.nodes[folds[0]];
       if (!stores.empty()) sig += "+";
       sig += std::string("fold.") + op_name(f.fn, f.dtype) + "[";
+      const bool stored = std::find(stores.begin(), stores.end(), f.arg[0]) != stores.end();
+      const int code_before = b.n_code, stack_before = b.on_stack;
       if (!b.expr(f.arg[0], sig)) return unsupported("fold argument");
       sig += "]";
+      if (stored) {            // its code was emitted with the store (the signature and the slots keep both)
+        for (int k = code_before; k < b.n_code; ++k) b.args.code[k] = Code{kCodeEnd, 0, 0, 0};
+        b.n_code = code_before;
+        b.on_stack = stack_before;
+      } else {
+        b.emit(kCodeFold, (int)stores.size(), reducer_code(f.fn, f.dtype));
+      }
       if (!set_n(m.size(f.arg[0]))) return unsupported("iteration sizes differ inside a cluster");
       if (stores.empty()) shape_from(f.arg[0]);
-      out.out_nodes[stores.empty() ? 0 : 1] = folds[0];
+      out.out_nodes[stores.size()] = folds[0];
     }
+    interpretable = b.code_ok && b.on_stack == 0 && reducer_ok;
   }
   // every member must have been reached by an element program or be a root
   out.kind = ClusterLaunch::Kernel;
@@ -252,6 +297,7 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
   out.args.aux = out.aux;
   out.externals = b.externals;
   const Instance *inst = find_instance(sig, out.args);
+  if (!inst && interpretable) inst = interpreter_instance();
   if (!inst) return unsupported("no kernel instance for cluster " + sig);
   out.instance = inst;
   return FC_OK;

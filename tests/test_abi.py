@@ -100,7 +100,23 @@ def test_run_checks_come_before_any_launch():
 
 
 def test_unsupported_cluster_is_reported_not_executed():
-    # a legal clustering for which no kernel instance is compiled
+    # a legal clustering with a cluster no kernel is built for: a stored predicate scanned in its own loop
+    g = Graph()
+    g.add("v", "input", "i32", (64,))
+    g.add("flags", "map", "i32", (64,), fn="mod_eq", iparam=(3, 0), args=("v",), output=True)
+    g.add("offs", "scanl", "i32", (64,), fn="add", args=("flags",), output=True)
+    part = fc.fc_plan(g, "bytes")
+    assert part.n_clusters == 1
+    msg = expect("FC_E_UNSUPPORTED", fc.fc_cluster_kernel, g, part, 0)
+    assert "scan cluster shape" in msg
+    fake = (0x10000000, 1 << 30)
+    bufs = {n.name: fake for n in g.nodes}
+    expect("FC_E_UNSUPPORTED", fc.fc_run_fused, g, part, bufs, fake)
+
+
+def test_elementwise_cluster_without_a_compiled_kernel_is_interpreted():
+    # maps, generates and gathers ending in stored arrays and at most one fold always run: the
+    # element programs travel as code when no compiled instance has their shape
     g = Graph()
     g.add("a", "input", "f32", (64,))
     g.add("b", "input", "f32", (64,))
@@ -109,11 +125,21 @@ def test_unsupported_cluster_is_reported_not_executed():
     g.add("out", "map", "f32", (64,), fn="mul2", args=("ea", "sb"), output=True)
     part = fc.fc_plan(g, "bytes")
     assert part.n_clusters == 1
-    msg = expect("FC_E_UNSUPPORTED", fc.fc_cluster_kernel, g, part, 0)
-    assert "element program" in msg or "instance" in msg
-    fake = (0x10000000, 1 << 30)
-    bufs = {n.name: fake for n in g.nodes}
-    expect("FC_E_UNSUPPORTED", fc.fc_run_fused, g, part, bufs, fake)
+    assert fc.fc_cluster_kernel(g, part, 0) == "store[map5(map9(in0:f32),map3(in1:f32))] {interpreted}"
+    # a program of the benchmark keeps its compiled kernel
+    w = build(2, small=True)
+    assert "interpreted" not in fc.fc_cluster_kernel(w.graph, fc.fc_plan(w.graph, "bytes"), 0)
+    # too deep for the interpreter's stack of gathers: four gathers inside one another
+    g = Graph()
+    g.add("x", "input", "f32", (64,))
+    prev = "x"
+    for k in range(4):
+        g.add(f"i{k}", "input", "i32", (64,))
+        g.add(f"g{k}", "gather", "f32", (64,), args=(f"i{k}", prev), output=(k == 3))
+        prev = f"g{k}"
+    pi = [0, 0, 1, 0, 1, 0, 1, 0, 1]
+    part = fc.fc_partition_check(g, pi)
+    expect("FC_E_UNSUPPORTED", fc.fc_cluster_kernel, g, part, 0)
 
 
 def test_scratch_bytes_and_kernel_names():

@@ -501,12 +501,12 @@ def unsupported_optimum_graphs():
     g.add("l", "scanl", "f32", (n,), fn="add", args=("y",), output=True)
     g.add("t", "fold", "f32", (1,), fn="add", args=("y",), output=True)
     out["fp32 scan + total"] = g
-    g = Graph()                                  # three stored arrays from one input
+    g = Graph()                                  # sum and maximum of one computed array
     g.add("x", "input", "f32", (n,))
-    g.add("a", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("x",), output=True)
-    g.add("b", "map", "f32", (n,), fn="sq_plus_one", args=("x",), output=True)
-    g.add("c", "map", "f32", (n,), fn="exp_neg", args=("x",), output=True)
-    out["three stores"] = g
+    g.add("a", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("x",))
+    g.add("s", "fold", "f32", (1,), fn="add", args=("a",), output=True)
+    g.add("t", "fold", "f32", (1,), fn="max", args=("a",), output=True)
+    out["two folds"] = g
     return out
 
 

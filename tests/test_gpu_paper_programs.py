@@ -237,14 +237,145 @@ def test_programs_whose_optimum_has_no_kernel_run_with_an_executable_plan():
         prog.run()
         for out in g.outputs():
             got, ref = prog.fetch(out), env[out]
-            if g[out].dtype == "i32":
+            node = g[out]
+            if node.dtype == "i32":
                 P.assert_bit_exact(got, ref, f"{name}/{out}")
-            elif g[out].kind in ("scanl", "fold"):
-                scale = prefix_scale(env["y"], False) if g[out].kind == "scanl" else np.abs(env["y"].astype(np.float64)).sum()
+            elif node.kind == "scanl":
+                scale = prefix_scale(env[node.args[0]], False)
                 assert np.all(np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= 1e-5 * scale + 1e-30), (name, out)
+            elif node.kind == "fold" and node.fn == "add":
+                scale = np.abs(env[node.args[0]].astype(np.float64)).sum()
+                assert abs(float(got[0]) - float(ref[0])) <= 1e-5 * scale, (name, out)
+            elif node.kind == "fold":
+                P.assert_bit_exact(got, ref, f"{name}/{out}")        # a maximum of exactly computed values
             else:
                 P.assert_ulp(got, np.asarray(ref, dtype=np.float64).astype(F32), 4, f"{name}/{out}")
         assert prog.control_words()[1] == 0
+
+
+def random_element_program(rng, n, n_stores, with_fold):
+    """A cluster of maps, generates and gathers over a few inputs: every root a tree, so that the whole
+    program is one legal cluster."""
+    g = Graph()
+    ins = {}
+    count = [0]
+
+    def fresh(prefix):
+        count[0] += 1
+        return f"{prefix}{count[0]}"
+
+    pool = {"f32": [], "i32": []}                      # a handful of inputs, read from several places
+
+    def leaf_f32():
+        if len(pool["f32"]) == 4 or (pool["f32"] and rng.integers(0, 2)):
+            return pool["f32"][rng.integers(0, len(pool["f32"]))]
+        name = fresh("x")
+        g.add(name, "input", "f32", (n,))
+        ins[name] = rng.uniform(0.0, 1.0, size=n).astype(F32)
+        pool["f32"].append(name)
+        return name
+
+    def index(depth):
+        kind = rng.integers(0, 4 if depth > 0 else 3)
+        if kind == 0 and len(pool["i32"]) == 2:
+            return pool["i32"][rng.integers(0, 2)]
+        name = fresh("i")
+        if kind == 0:
+            g.add(name, "input", "i32", (n,))
+            ins[name] = rng.integers(0, n, size=n, dtype=np.int32)
+            pool["i32"].append(name)
+        elif kind == 1:
+            g.add(name, "generate", "i32", (n,), fn="iota_rev")
+        elif kind == 2:
+            g.add(name, "generate", "i32", (n,), fn="iota")
+        else:
+            g.add(name, "gather", "i32", (n,), args=(index(0), index(depth - 1)))
+        return name
+
+    def value(depth, root=False):
+        kind = rng.integers(1 if root else 0, 8) if depth > 0 else 0
+        if kind == 0:
+            return leaf_f32()
+        name = fresh("v")
+        if kind in (1, 2):
+            fn = ("affine", "sq_plus_one", "exp_neg", "sin_x_mul_x", "ident")[rng.integers(0, 5)]
+            kw = {"fparam": (float(rng.uniform(0.5, 1.5)), float(rng.uniform(-0.5, 0.5)))} if fn == "affine" else {}
+            g.add(name, "map", "f32", (n,), fn=fn, args=(value(depth - 1),), output=root, **kw)
+        elif kind in (3, 4):
+            g.add(name, "map", "f32", (n,), fn=("mul2", "add2")[rng.integers(0, 2)], args=(value(depth - 1), value(depth - 1)),
+                  output=root)
+        elif kind == 5:
+            g.add(name, "map", "f32", (n,), fn="add3", args=(value(depth - 1), value(0), value(depth - 1)), output=root)
+        else:
+            g.add(name, "gather", "f32", (n,), args=(index(1), value(depth - 1)), output=root)
+        return name
+
+    for _ in range(n_stores):
+        value(3, root=True)                            # a stored array is computed by the cluster
+    if with_fold:
+        g.add("total", "fold", "f32", (1,), fn=("add", "max")[rng.integers(0, 2)], args=(value(3),), output=True)
+    return g, ins
+
+
+def test_interpreted_clusters_match_the_compiled_kernels():
+    # random elementwise clusters run by the interpreting kernel as one cluster; the same
+    # programs run one compiled kernel per combinator must give the same bits (the same device
+    # functions in the same order); a fold within the bound of the folds
+    rng = np.random.default_rng(2024)
+    seen_interpreted = 0
+    for trial in range(40):
+        n = int(rng.choice([1, 255, 5000, 300001]))
+        n_stores = int(rng.integers(0, 4))
+        with_fold = bool(rng.integers(0, 2)) or n_stores == 0
+        g, ins = random_element_program(rng, n, n_stores, with_fold)
+        if sum(nd.kind != "input" for nd in g.nodes) > 20:
+            continue
+        pi = [0 if nd.kind == "input" else 1 for nd in g.nodes]
+        try:
+            part = fc().fc_partition_check(g, pi)
+            name = fc().fc_cluster_kernel(g, part, 0)
+        except fc().FcError:
+            continue                                   # too large for one element program
+        seen_interpreted += "interpreted" in name
+        env = evaluate(g, ins)
+        inter = [nd.name for nd in g.nodes if nd.kind != "input"]
+        fused, unfused = device_program(g, ins, part), device_program(g, ins, None, bind=inter)
+        fused.run()
+        unfused.run()
+        for out in g.outputs():
+            got = fused.fetch(out)
+            if g[out].kind == "fold":
+                arg = env[g[out].args[0]].astype(np.float64)
+                if g[out].fn == "add":
+                    assert abs(float(got[0]) - float(env[out][0])) <= 1e-5 * np.abs(arg).sum() + 1e-30, (trial, name)
+                else:
+                    P.assert_bit_exact(got, unfused.fetch(out), f"{trial}/{out}")
+            else:
+                P.assert_bit_exact(got, unfused.fetch(out), f"trial {trial} {name} {out}")
+                P.assert_close(got, env[out], 1e-4, f"{trial}/{out}", abs_=1e-5)
+        assert fused.control_words()[1] == 0
+    assert seen_interpreted >= 15
+    # an array that is stored and folded is computed once (the store leaves the value for the fold)
+    n = 100003
+    g = Graph()
+    for nm in "abc":
+        g.add(nm, "input", "f32", (n,))
+    g.add("i", "input", "i32", (n,))
+    g.add("t", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("a",))
+    g.add("u", "map", "f32", (n,), fn="mul2", args=("t", "b"))
+    g.add("gc", "gather", "f32", (n,), args=("i", "c"))
+    g.add("out", "map", "f32", (n,), fn="add2", args=("u", "gc"), output=True)
+    g.add("tot", "fold", "f32", (1,), fn="add", args=("out",), output=True)
+    ins = {k: rng.uniform(0, 1, n).astype(F32) for k in "abc"}
+    ins["i"] = rng.integers(0, n, size=n, dtype=np.int32)
+    env = evaluate(g, ins)
+    part = fc().fc_plan(g, "bytes")
+    fused = device_program(g, ins, part)
+    assert part.n_clusters == 1 and "interpreted" in fused.kernels()[0]
+    fused.run()
+    P.assert_bit_exact(fused.fetch("out"), env["out"], "stored and folded: out")
+    P.assert_fold(fused.fetch("tot"), env["tot"], "stored and folded: tot")
+    assert fused.control_words()[1] == 0
 
 
 def test_row_scans():
