@@ -29,10 +29,11 @@ extern "C" {
 #define FC_OK                   0
 #define FC_E_BADGRAPH          -1  /* cycle / arity / dtype / shape mismatch, unknown function  */
 #define FC_E_ILLEGAL_PARTITION -2  /* breaks a rule of section 3.4 or a constraint of Fig. "Total ILP formulation" */
-#define FC_E_UNSUPPORTED       -3  /* legal cluster, but no kernel is built for its shape.  Clusters of maps, generates
-                                      and gathers that end in up to four stored arrays, or in stored arrays and one
-                                      fold, always run (compiled for the shapes of the paper's programs, interpreted
-                                      otherwise); scans, scatters, segmented and row folds run in the compiled shapes */
+#define FC_E_UNSUPPORTED       -3  /* legal cluster, but no kernel is built for its combination of consumers (e.g. two
+                                      folds of one flattened array, a scan that also stores its input), or its element
+                                      programs exceed the limits (24 nodes, 7 external arrays, gathers nested 3 deep).
+                                      Element programs of maps, generates and gathers as such always run: compiled for
+                                      the shapes of the paper's programs, interpreted otherwise */
 #define FC_E_UNBOUND           -4  /* an input or manifest array has no device buffer, or it is too small / misaligned */
 #define FC_E_SCRATCH           -5  /* scratch missing, misaligned or smaller than fc_scratch_bytes() */
 #define FC_E_HIP               -6  /* a HIP runtime call failed (message holds hipGetErrorString) */

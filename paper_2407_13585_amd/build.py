@@ -18,7 +18,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfc.so")
 
-SOURCES = ["api.hip", "run.hip", "instances.hip", "model.cpp", "plan.cpp"]
+SOURCES = ["api.hip", "run.hip", "instances.hip", "generic_folds.hip", "generic_rows.hip", "generic_scans.hip", "model.cpp",
+           "plan.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

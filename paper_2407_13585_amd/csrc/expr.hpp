@@ -62,7 +62,8 @@ inline void mod_eq_constants(Slot &s) {
 // map, store or fold above it; a gather evaluates its index, then its source with the
 // index as the position (kCodeEnter / kCodeLeave).
 constexpr int kMaxCode = 64;
-constexpr int kInterpDepth = 4;       // values below the top of the interpreter's stack
+constexpr int kMaxRoots = 4;          // element programs of one cluster that yield a value each
+constexpr int kInterpDepth = 6;       // values below the top of the interpreter's stack
 constexpr int kInterpGathers = 3;     // nesting of gathers it follows
 enum : unsigned char {
   kCodeEnd = 0,
@@ -72,7 +73,8 @@ enum : unsigned char {
   kCodeEnter,   // pop an index and make it the position
   kCodeLeave,   // back to the position before the matching kCodeEnter
   kCodeStore,   // a = output array: pop a value into it at the element's own position (c = 1: leave it on the stack)
-  kCodeFold     // a = output array, b = reducer (kFold...): pop a value into the accumulator
+  kCodeFold,    // a = output array, b = reducer (kFold...): pop a value into the accumulator
+  kCodeYield    // the value on the stack is the result of this element program (Interp<K, T>)
 };
 enum : unsigned char { kFoldAddF32 = 0, kFoldMaxF32, kFoldMulF32, kFoldAddI32, kFoldMaxI32 };
 struct Code { unsigned char op, a, b, c; };
@@ -85,7 +87,8 @@ struct KArgs {    // arguments of one cluster launch
   int h;                    // outer extent
   int aux;                  // skeleton specific (rows of a segmented fold, ...)
   Slot p[kMaxSlots];
-  Code code[kMaxCode];      // elementwise clusters only; kCodeEnd after the last instruction
+  Code code[kMaxCode];      // kCodeEnd after the last instruction
+  unsigned char root[kMaxRoots];   // where element program K of a cluster with another consumer starts in `code`
 };
 
 template <class T> struct Vec4 { T v[4]; };

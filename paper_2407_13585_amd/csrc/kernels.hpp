@@ -280,8 +280,10 @@ __device__ __forceinline__ unsigned interp_identity(int op) {
 // 128-bit group, `first` a multiple of four; V = 1: one element), so that the cost of
 // reading and decoding an instruction is shared by four elements.  `below` is this
 // lane's column of the value stack.
-template <int V>
-__device__ __forceinline__ void interp_run(const KArgs &a, unsigned first, unsigned (*below)[kVec][kBlock], unsigned &acc) {
+// Starts at instruction `pc`; a kCodeYield ends the run with the program's values in `result`.
+template <int V, int Threads>
+__device__ __forceinline__ void interp_run(const KArgs &a, int pc, unsigned first, unsigned (*below)[kVec][Threads], unsigned &acc,
+                                           unsigned (&result)[V]) {
   using Raw = unsigned __attribute__((ext_vector_type(4)));
   int at[V];                                           // the positions element programs read at
   int suspended[kInterpGathers][V];
@@ -303,9 +305,14 @@ __device__ __forceinline__ void interp_run(const KArgs &a, unsigned first, unsig
       for (int e = 0; e < V; ++e) top[e] = below[count - 1][e][threadIdx.x];
     }
   };
-  for (int pc = 0; pc < kMaxCode; ++pc) {
+  for (; pc < kMaxCode; ++pc) {
     const Code c = a.code[pc];
     if (c.op == kCodeEnd) break;
+    if (c.op == kCodeYield) {
+#pragma unroll
+      for (int e = 0; e < V; ++e) result[e] = top[e];
+      break;
+    }
     switch (c.op) {
       case kCodeIn: {
         push_room();
@@ -370,6 +377,7 @@ __device__ __forceinline__ void interp_run(const KArgs &a, unsigned first, unsig
   }
 }
 
+template <class Tag = void>            // a template only so that every translation unit may see the definition
 __global__ __launch_bounds__(kBlock) void interp_kernel(const KArgs a, Control *ctl, unsigned long long *partials) {
   __shared__ unsigned below[kInterpDepth][kVec][kBlock];
   const unsigned n = (unsigned)a.n, n4 = n & ~3u;
@@ -378,9 +386,10 @@ __global__ __launch_bounds__(kBlock) void interp_kernel(const KArgs a, Control *
   for (int pc = 0; pc < kMaxCode && a.code[pc].op != kCodeEnd; ++pc)
     if (a.code[pc].op == kCodeFold) { fold_op = a.code[pc].b; fold_out = a.code[pc].a; }
   unsigned acc = fold_op >= 0 ? interp_identity(fold_op) : 0u;
+  unsigned none4[kVec], none1[1];
   for (unsigned i = (blockIdx.x * kBlock + threadIdx.x) * kVec; i < n4; i += gridDim.x * kBlock * kVec)
-    interp_run<kVec>(a, i, below, acc);
-  if (blockIdx.x == 0 && threadIdx.x < n - n4) interp_run<1>(a, n4 + threadIdx.x, below, acc);
+    interp_run<kVec, kBlock>(a, 0, i, below, acc, none4);
+  if (blockIdx.x == 0 && threadIdx.x < n - n4) interp_run<1, kBlock>(a, 0, n4 + threadIdx.x, below, acc, none1);
   switch (fold_op) {                                     // the same for the whole grid
     case kFoldAddF32: fold_finish<AddF32>(from_bits<float>((int)acc), a, fold_out, ctl, partials); break;
     case kFoldMaxF32: fold_finish<MaxF32>(from_bits<float>((int)acc), a, fold_out, ctl, partials); break;
@@ -390,6 +399,35 @@ __global__ __launch_bounds__(kBlock) void interp_kernel(const KArgs a, Control *
     default: break;
   }
 }
+
+// Element program K of a cluster as an expression node: evaluated by running its code
+// (KArgs::code from KArgs::root[K] to the kCodeYield).  With it every skeleton of this
+// file has an instance that takes any element program: what the matcher cannot pair with a
+// compiled element program runs through these.  Threads = threads of the workgroup (the
+// lanes' stack columns live in LDS).
+template <int Threads>
+__device__ __forceinline__ unsigned (*interp_stack())[kVec][Threads] {
+  __shared__ unsigned below[kInterpDepth][kVec][Threads];
+  return below;
+}
+template <int K, class T, int Threads = kBlock>
+struct Interp {
+  using R = T;
+  static constexpr int kNodes = 0;                     // the code names its parameter slots itself
+  static constexpr bool kMirror = false;
+  template <int Base, bool Stream = false> static __device__ __forceinline__ T eval(const KArgs &a, int i) {
+    unsigned r[1] = {0u}, none = 0u;
+    interp_run<1, Threads>(a, a.root[K], (unsigned)i, interp_stack<Threads>(), none, r);
+    return from_bits<T>((int)r[0]);
+  }
+  // i is a multiple of four (the callers read 128-bit groups)
+  template <int Base> static __device__ __forceinline__ Vec4<T> eval4(const KArgs &a, int i) {
+    unsigned r[kVec] = {0u, 0u, 0u, 0u}, none = 0u;
+    interp_run<kVec, Threads>(a, a.root[K], (unsigned)i, interp_stack<Threads>(), none, r);
+    return Vec4<T>{{from_bits<T>((int)r[0]), from_bits<T>((int)r[1]), from_bits<T>((int)r[2]), from_bits<T>((int)r[3])}};
+  }
+  static void sig(std::string &s) { s += std::string("*") + DtypeName<T>::s(); }
+};
 
 // ------------------------------------------------------------------ fold over a gathered table, indices binned first
 // r = fold(Op, f(table[index[i]])) for a table of more than one L2 (4 MiB per XCD) and

@@ -1,0 +1,224 @@
+// Launchers and instance builders shared by the translation units that fill the registry
+// (instances.hip: the instances compiled for particular element programs; generic_*.hip:
+// the instances that take any element program).  Everything here has internal linkage.
+#pragma once
+
+#include "kernels.hpp"
+#include "registry.hpp"
+
+#include <algorithm>
+#include <string>
+#include <tuple>
+#include <utility>
+#include <vector>
+
+namespace fc {
+
+// defined in generic_folds.hip, generic_rows.hip, generic_scans.hip
+void append_generic_fold_instances(std::vector<Instance> &r);
+void append_generic_row_instances(std::vector<Instance> &r);
+void append_generic_scan_instances(std::vector<Instance> &r);
+
+namespace {
+
+constexpr unsigned kMaxGrid = 2048;   // 256 CUs x 8 workgroups
+
+unsigned grid_for(int n, int tile, unsigned cap) {
+  long long g = ((long long)n + tile - 1) / tile;
+  return (unsigned)std::max<long long>(1, std::min<long long>(g, cap));
+}
+
+// ---- launchers ------------------------------------------------------------
+// Launch through hipLaunchKernel so that the status returned is that of this
+// launch (hipGetLastError would also report an error an earlier, unrelated call
+// left behind on the thread).
+template <class... P, size_t... I>
+hipError_t launch_impl(void (*k)(P...), dim3 grid, dim3 block, hipStream_t s, std::tuple<P...> &vals,
+                       std::index_sequence<I...>) {
+  void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))...};
+  return hipLaunchKernel(reinterpret_cast<const void *>(k), grid, block, ptrs, 0, s);
+}
+template <class... P>
+hipError_t launch_k(void (*k)(P...), unsigned grid, hipStream_t s, int block, P... a) {
+  std::tuple<P...> vals(a...);
+  return launch_impl(k, dim3(grid), dim3(block), s, vals, std::index_sequence_for<P...>());
+}
+template <class... P>
+hipError_t launch_k(void (*k)(P...), unsigned grid, hipStream_t s, P... a) {
+  return launch_k(k, grid, s, (int)kBlock, a...);
+}
+// the kernels that stride over tiles are launched with as many workgroups as are resident at once
+template <class... P>
+unsigned resident_grid(void (*k)(P...)) {
+  const unsigned r = resident_workgroups(k, kBlock);
+  return r ? std::min<unsigned>(r, kMaxPartials) : kMaxGrid;
+}
+
+template <class E> hipError_t launch_store(const KArgs &a, const LaunchCtx &c) {
+  if (a.n == 0) return hipSuccess;
+  return launch_k(&store_kernel<E>, grid_for(a.n, kTile, resident_grid(&store_kernel<E>)), c.stream, a);
+}
+template <class Op, class E> hipError_t launch_fold(const KArgs &a, const LaunchCtx &c) {
+  return launch_k(&fold_kernel<Op, E>, grid_for(a.n, kTile, resident_grid(&fold_kernel<Op, E>)), c.stream, a, c.ctl,
+                  c.partials);
+}
+template <class ES, class Op, class EF> hipError_t launch_store_fold(const KArgs &a, const LaunchCtx &c) {
+  return launch_k(&store_fold_kernel<ES, Op, EF>, grid_for(a.n, kTile, resident_grid(&store_fold_kernel<ES, Op, EF>)),
+                  c.stream, a, c.ctl, c.partials);
+}
+template <class Op, class E> hipError_t launch_foldseg(const KArgs &a, const LaunchCtx &c) {
+  if (a.aux == 0) return hipSuccess;
+  return launch_k(&foldseg_kernel<Op, E>, grid_for(a.aux, kBlock / 16, kMaxGrid * 8), c.stream, a);
+}
+// ---- column-blocked segmented fold: for tables of more than one and at most four L2s ----
+constexpr size_t kL2Bytes = 4u << 20;                 // L2 of one XCD
+template <int KT> size_t blocked_table_bytes(const KArgs &a) {
+  // the table is the last leaf of Map<F, EV, Gather<EI, In<KT>>>; its slot holds its extents
+  for (int k = kMaxSlots - 1; k >= 0; --k)
+    if (a.p[k].ext[0] != 0) return (size_t)a.p[k].ext[0] * (size_t)a.p[k].ext[1] * 4;
+  return 0;
+}
+template <int KT> bool foldseg_blocked_accept(const KArgs &a) {
+  const size_t table = blocked_table_bytes<KT>(a);
+  const size_t units = ((size_t)a.aux + kBlockedRows - 1) / kBlockedRows;
+  return a.n > 0 && (unsigned long long)a.n * 4 < (1ull << 31) && table > kL2Bytes && table <= kQuarters * kL2Bytes && units >= 64 &&
+         units * kQuarters <= kMaxTiles;
+}
+size_t foldseg_blocked_workspace(const KArgs &a) { return (size_t)kQuarters * (size_t)a.aux * sizeof(unsigned long long); }
+template <class Op, class F, int KV, int KI, int KT>
+hipError_t launch_foldseg_blocked(const KArgs &a, const LaunchCtx &c) {
+  if (!c.workspace) return hipErrorInvalidValue;
+  const unsigned units = ((unsigned)a.aux + kBlockedRows - 1) / kBlockedRows;
+  unsigned grid = resident_grid(&foldseg_blocked_kernel<Op, F, KV, KI, KT>) / 8 * 8;   // whole rounds of the eight XCDs
+  grid = std::max(8u, std::min(grid, units * kQuarters / 8 * 8));
+  const size_t elems = blocked_table_bytes<KT>(a) / 4;
+  const int range_len = (int)(((elems + kQuarters - 1) / kQuarters + 31) / 32 * 32);    // whole 128-byte lines
+  return launch_k(&foldseg_blocked_kernel<Op, F, KV, KI, KT>, grid, c.stream, a, c.ctl, c.partials, c.status,
+                  static_cast<unsigned long long *>(c.workspace), range_len);
+}
+
+// ---- fold over a gathered table of one to sixty-four L2s: indices sorted by table range first ----
+template <class E> size_t binned_table_elems(const KArgs &a) {
+  constexpr int slot = GatherChain<E>::template source_slot<0>();
+  return (size_t)a.p[slot].ext[0] * (size_t)a.p[slot].ext[1];
+}
+inline size_t binned_tiles(const KArgs &a) { return ((size_t)(a.n & ~3) + kBinTile - 1) / kBinTile; }
+inline size_t binned_counts_bytes(const KArgs &a) { return (binned_tiles(a) * kBins * sizeof(int) + 255) / 256 * 256; }
+template <class E> bool fold_binned_accept(const KArgs &a) {
+  const size_t bytes = binned_table_elems<E>(a) * 4;
+  // Below two million positions the direct kernel is over before two launches would be.  Up to
+  // 64 MiB the ranges are half an L2 or less; measured at 2^24 positions: 64 MiB 124 us (direct
+  // 307), 128 MiB 132 us (319), 256 MiB, where half of a range fits, 201 us (326).
+  return a.n >= (1 << 21) && bytes > kL2Bytes && bytes <= kBins * (kL2Bytes * 2) &&
+         binned_tiles(a) * kBins * kBinCap * sizeof(int) < (1ull << 31);
+}
+size_t fold_binned_workspace(const KArgs &a) { return binned_counts_bytes(a) + binned_tiles(a) * kBins * kBinCap * sizeof(int); }
+template <class Op, class E> hipError_t launch_fold_binned(const KArgs &a, const LaunchCtx &c) {
+  if (!c.workspace) return hipErrorInvalidValue;
+  const unsigned tiles = (unsigned)binned_tiles(a);
+  int *counts = static_cast<int *>(c.workspace);
+  int *entries = reinterpret_cast<int *>(static_cast<char *>(c.workspace) + binned_counts_bytes(a));
+  const size_t range_len = (binned_table_elems<E>(a) + kBins - 1) / kBins;
+  const unsigned inv_range = (unsigned)(((1ull << 32) + range_len - 1) / range_len);
+  const unsigned first = std::min(tiles, std::min<unsigned>(resident_grid(&bin_indices_kernel<Op, E>), kMaxPartials / 2));
+  hipError_t e = launch_k(&bin_indices_kernel<Op, E>, first, c.stream, a, c.ctl, c.partials, counts, entries, tiles, inv_range);
+  if (e != hipSuccess) return e;
+  // One workgroup per compute unit for the second kernel.  A compute unit's vector cache returns
+  // data in request order, so its gathers (L2 hits) queue behind the entry reads (from memory) of
+  // whichever wave issued some: with eight workgroups per unit the kernel took 130 us where the
+  // gathers alone take 66 and the entry reads alone 27; with one or two it takes their sum.
+  const int cus = device_compute_units();
+  const unsigned second = std::max(8u, (unsigned)(cus > 0 ? cus : 256) / 8 * 8);
+  return launch_k(&fold_binned_kernel<Op, E>, second, c.stream, a, c.ctl, c.partials, static_cast<const int *>(counts),
+                  static_cast<const int *>(entries), tiles, first);
+}
+
+template <class EX, class EV, int Mode, bool Reverse = false> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {
+  long long tiles = std::max<long long>(1, ((long long)a.n + kScanTile - 1) / kScanTile);
+  if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
+  return launch_k(&scan_kernel<EX, EV, Mode, Reverse>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
+}
+// lanes per row by row length, as for the row folds
+template <class EX, bool Reverse = false> hipError_t launch_scan_f32(const KArgs &a, const LaunchCtx &c) {
+  long long tiles = std::max<long long>(1, ((long long)a.n + kScanFTile - 1) / kScanFTile);
+  if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
+  return launch_k(&scan_f32_kernel<EX, Reverse>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
+}
+template <class E, bool Reverse> hipError_t launch_rowscan(const KArgs &a, const LaunchCtx &c) {
+  if (a.aux == 0 || a.w == 0) return hipSuccess;
+  if (a.w <= 64)
+    return launch_k(&rowscan_kernel<E, Reverse, 16>, grid_for(a.aux, kBlock / 16, resident_grid(&rowscan_kernel<E, Reverse, 16>)), c.stream, a);
+  if (a.w <= 1024)
+    return launch_k(&rowscan_kernel<E, Reverse, kWave>, grid_for(a.aux, kBlock / kWave, resident_grid(&rowscan_kernel<E, Reverse, kWave>)), c.stream, a);
+  return launch_k(&rowscan_kernel<E, Reverse, kBlock>, grid_for(a.aux, 1, resident_grid(&rowscan_kernel<E, Reverse, kBlock>)), c.stream, a);
+}
+template <class EI, class EV, class EF, bool Add> hipError_t launch_scatter(const KArgs &a, const LaunchCtx &c) {
+  if (a.n == 0) return hipSuccess;
+  return launch_k(&scatter_kernel<EI, EV, EF, Add>, grid_for(a.n, kTile, resident_grid(&scatter_kernel<EI, EV, EF, Add>)), c.stream, a);
+}
+template <class E1, class E2> hipError_t launch_store2(const KArgs &a, const LaunchCtx &c) {
+  if (a.n == 0) return hipSuccess;
+  return launch_k(&store2_kernel<E1, E2>, grid_for(a.n, kTile, resident_grid(&store2_kernel<E1, E2>)), c.stream, a);
+}
+// lanes per row by row length: a 16-lane DPP row, a wave, or the whole workgroup
+template <class Op1, class Op2, class E, class RI> hipError_t launch_rowfold(const KArgs &a, const LaunchCtx &c) {
+  if (a.aux == 0) return hipSuccess;
+  if (a.w <= 64) return launch_k(&rowfold_kernel<Op1, Op2, E, RI, 16>, grid_for(a.aux, kBlock / 16, kMaxGrid * 4), c.stream, a);
+  if (a.w <= 2048) return launch_k(&rowfold_kernel<Op1, Op2, E, RI, kWave>, grid_for(a.aux, kBlock / kWave, kMaxGrid * 4), c.stream, a);
+  if (a.aux < 1024 && a.w >= 4 * kTile) {
+    // few long rows: cut every row into chunks (a multiple of the 128-bit stride) so that ~2048 workgroups run
+    unsigned splits = std::min<unsigned>((unsigned)(a.w / kTile), std::max(1u, 2048u / (unsigned)a.aux));
+    splits = std::min<unsigned>(splits, (unsigned)(kMaxPartials / 2) / (unsigned)a.aux);
+    if (splits > 1) {
+      unsigned chunk = (((unsigned)a.w + splits - 1) / splits + kBlock * kVec - 1) / (kBlock * kVec) * (kBlock * kVec);
+      splits = ((unsigned)a.w + chunk - 1) / chunk;
+      return launch_k(&rowfold_split_kernel<Op1, Op2, E, RI>, (unsigned)a.aux * splits, c.stream, a, c.ctl, c.partials,
+                      splits, chunk);
+    }
+  }
+  return launch_k(&rowfold_kernel<Op1, Op2, E, RI, kBlock>, grid_for(a.aux, 1, kMaxGrid * 4), c.stream, a);
+}
+
+// ---- signatures -----------------------------------------------------------
+template <class E> std::string sig_of() { std::string s; E::sig(s); return s; }
+template <class E> Instance store_() { return {"store[" + sig_of<E>() + "]", &launch_store<E>}; }
+template <class Op, class E> Instance fold_() {
+  return {std::string("fold.") + Op::name() + "[" + sig_of<E>() + "]", &launch_fold<Op, E>};
+}
+template <class ES, class Op, class EF> Instance store_fold_() {
+  return {"store[" + sig_of<ES>() + "]+fold." + Op::name() + "[" + sig_of<EF>() + "]", &launch_store_fold<ES, Op, EF>};
+}
+template <class Op, class E> Instance foldseg_() {
+  return {std::string("foldseg.") + Op::name() + "[" + sig_of<E>() + "]", &launch_foldseg<Op, E>};
+}
+template <class EX, class EV, int Mode, bool Reverse = false> Instance scan_() {
+  std::string s = std::string(Reverse ? "scanr[" : "scan[") + sig_of<EX>() + "]";
+  if (Mode & kOffs) s += "+offs";
+  if (Mode & kScatter) s += "+scatter[" + sig_of<EV>() + "]";
+  if (Mode & kCount) s += "+count";
+  return {s, &launch_scan<EX, EV, Mode, Reverse>};
+}
+template <class EX, bool Reverse = false> Instance scan_f32_() {
+  return {std::string(Reverse ? "scanr[" : "scan[") + sig_of<EX>() + "]+offs", &launch_scan_f32<EX, Reverse>};
+}
+template <class E, bool Reverse = false> Instance rowscan_() {
+  return {std::string(Reverse ? "rowscanr[" : "rowscan[") + sig_of<E>() + "]+offs", &launch_rowscan<E, Reverse>};
+}
+template <class EI, class EV, class EF, bool Add = false> Instance scatter_() {
+  return {std::string(Add ? "scatter.add[" : "scatter[") + sig_of<EI>() + "," + sig_of<EV>() + "," + sig_of<EF>() + "]",
+          &launch_scatter<EI, EV, EF, Add>};
+}
+template <class E1, class E2> Instance store2_() {
+  return {"store[" + sig_of<E1>() + "]+store[" + sig_of<E2>() + "]", &launch_store2<E1, E2>};
+}
+template <class Op1, class Op2, class E, class RI = NoRowIndex> Instance rowfold_() {
+  std::string s = std::string("rowfold.") + Op1::name();
+  if (!std::is_same<Op2, NoSecondOp>::value) s += std::string("+") + Op2::name();
+  s += "[" + sig_of<E>() + "]";
+  if (!std::is_same<RI, NoRowIndex>::value) s += "@gather(" + sig_of<RI>() + ")";
+  return {s, &launch_rowfold<Op1, Op2, E, RI>};
+}
+
+}  // namespace
+
+}  // namespace fc

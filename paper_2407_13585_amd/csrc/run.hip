@@ -36,7 +36,7 @@ struct Builder {
       case kCodeEnter: --on_stack; if (++gathers > kInterpGathers) code_ok = false; break;
       case kCodeLeave: --gathers; break;
       case kCodeStore: if (!c) --on_stack; break;              // c = 1: the value stays for a fold
-      default: --on_stack; break;                              // fold
+      default: --on_stack; break;                              // fold, yield
     }
     if (on_stack > kInterpDepth + 1 || on_stack < 0) code_ok = false;
   }
@@ -63,6 +63,19 @@ struct Builder {
     s.ext[0] = (int)nd.shape[0]; s.ext[1] = (int)nd.shape[1];
     if (nd.kind == FC_MAP && nd.fn == FC_FN_MOD_EQ) mod_eq_constants(s);
     if (nd.kind == FC_GENERATE && (nd.fn == FC_FN_CLAMP_SHIFT_2D || nd.fn == FC_FN_ROW_OF_2D)) div_constants(s, s.ext[1]);
+    return true;
+  }
+
+  // Element program number n_roots of a cluster whose consumer is not elementwise: its
+  // signature goes to `sig` as always; `any` receives the signature of the instance that
+  // takes any element program of this type (it runs the code between root[k] and the yield).
+  int n_roots = 0;
+  bool root(int a, std::string &sig, std::string &any) {
+    if (n_roots >= kMaxRoots || n_code > 255) code_ok = false; else args.root[n_roots] = (unsigned char)n_code;
+    ++n_roots;
+    if (!expr(a, sig)) return false;
+    emit(kCodeYield);
+    any += m.nodes[a].dtype == FC_F32 ? "*f32" : "*i32";
     return true;
   }
 
@@ -135,6 +148,7 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
   }
   std::string sig;
   int n = -1;
+  std::string any;                    // signature of the instance that takes any element program, if the shape has one
   bool interpretable = false, reducer_ok = true;
   auto reducer_code = [&](int fn, int dtype) {
     if (dtype == FC_F32) return fn == FC_OP_ADD ? (int)kFoldAddF32 : fn == FC_OP_MAX ? (int)kFoldMaxF32 : (int)kFoldMulF32;
@@ -165,25 +179,30 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
       return unsupported("a row scan can only be stored");
     sig = by_rows ? (m.nodes[sc].kind == FC_SCANR ? "rowscanr[" : "rowscan[")
                   : (m.nodes[sc].kind == FC_SCANR ? "scanr[" : "scan[");
+    any = sig;
     if (by_rows) out.aux = (int)m.nodes[sc].shape[0];
-    if (!b.expr(x, sig)) return unsupported("scan input");
+    if (!b.root(x, sig, any)) return unsupported("scan input");
     sig += "]";
+    any += "]";
     set_n(m.size(sc));
     shape_from(sc);
-    if (!c.fused_away[sc]) { sig += "+offs"; out.out_nodes[1] = sc; }
+    if (!c.fused_away[sc]) { sig += "+offs"; any += "+offs"; out.out_nodes[1] = sc; }
     if (!scatters.empty()) {
       const fc_node &st = m.nodes[scatters[0]];
       if (st.fn != FC_OP_OVERWRITE || st.arg[1] != sc || st.nargs != 4 || st.arg[3] != x)
         return unsupported("scatter fused with a scan must take the scan as index and the scanned flags as flag");
       sig += "+scatter[";
-      if (!b.expr(st.arg[2], sig)) return unsupported("scatter value");
+      any += "+scatter[";
+      if (!b.root(st.arg[2], sig, any)) return unsupported("scatter value");
       sig += "]";
+      any += "]";
       out.out_nodes[0] = scatters[0];
     }
     if (!folds.empty()) {
       const fc_node &f = m.nodes[folds[0]];
       if (f.fn != FC_OP_ADD || f.arg[0] != x || f.shape[0] != 1) return unsupported("fold beside a scan must be (+) over the scanned array");
       sig += "+count";
+      any += "+count";
       out.out_nodes[2] = folds[0];
     }
   } else if (!scatters.empty()) {
@@ -191,16 +210,21 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
       return unsupported("scatter cluster shape");
     const fc_node &st = m.nodes[scatters[0]];
     sig = st.fn == FC_OP_ADD ? "scatter.add[" : "scatter[";
-    if (!b.expr(st.arg[1], sig)) return unsupported("scatter index");
+    any = sig;
+    if (!b.root(st.arg[1], sig, any)) return unsupported("scatter index");
     sig += ",";
-    if (!b.expr(st.arg[2], sig)) return unsupported("scatter value");
+    any += ",";
+    if (!b.root(st.arg[2], sig, any)) return unsupported("scatter value");
     sig += ",";
+    any += ",";
     if (st.nargs == 4) {
-      if (!b.expr(st.arg[3], sig)) return unsupported("scatter flag");
+      if (!b.root(st.arg[3], sig, any)) return unsupported("scatter flag");
     } else {
       sig += "1";
+      any += "1";
     }
     sig += "]";
+    any += "]";
     set_n(m.size(st.arg[1]));
     shape_from(st.arg[1]);
     out.out_nodes[0] = scatters[0];
@@ -208,8 +232,10 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     if (foldsegs.size() != 1 || !folds.empty() || !stores.empty()) return unsupported("foldSeg cluster shape");
     const fc_node &f = m.nodes[foldsegs[0]];
     sig = std::string("foldseg.") + op_name(f.fn, f.dtype) + "[";
-    if (!b.expr(f.arg[0], sig)) return unsupported("foldSeg values");
+    any = sig;
+    if (!b.root(f.arg[0], sig, any)) return unsupported("foldSeg values");
     sig += "]";
+    any += "]";
     set_n(m.size(f.arg[0]));
     shape_from(f.arg[0]);
     out.aux = (int)f.shape[0];
@@ -228,8 +254,10 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     sig = std::string("rowfold.") + op_name(f0.fn, f0.dtype);
     if (folds.size() == 2) sig += std::string("+") + op_name(m.nodes[folds[1]].fn, m.nodes[folds[1]].dtype);
     sig += "[";
-    if (!b.expr(arg, sig)) return unsupported("row-fold argument");
+    any = sig;
+    if (!b.root(arg, sig, any)) return unsupported("row-fold argument");
     sig += "]";
+    any += "]";
     out.w = (int)m.nodes[arg].shape[1];
     out.h = (int)m.nodes[arg].shape[0];
     if (!stores.empty()) {
@@ -237,8 +265,10 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
       if (g.kind != FC_GATHER || folds.size() != 1 || g.arg[1] != folds[0] || !c.fused_away[folds[0]])
         return unsupported("a row fold can only be consumed by a gather inside its cluster");
       sig += "@gather(";
-      if (!b.expr(g.arg[0], sig)) return unsupported("row index");
+      any += "@gather(";
+      if (!b.root(g.arg[0], sig, any)) return unsupported("row index");
       sig += ")";
+      any += ")";
       n = (int)m.size(stores[0]);
       out.out_nodes[0] = stores[0];
     } else {
@@ -297,6 +327,7 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
   out.args.aux = out.aux;
   out.externals = b.externals;
   const Instance *inst = find_instance(sig, out.args);
+  if (!inst && !any.empty() && b.code_ok && b.on_stack == 0) inst = find_instance(any, out.args);
   if (!inst && interpretable) inst = interpreter_instance();
   if (!inst) return unsupported("no kernel instance for cluster " + sig);
   out.instance = inst;

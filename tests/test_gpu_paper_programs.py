@@ -253,68 +253,92 @@ def test_programs_whose_optimum_has_no_kernel_run_with_an_executable_plan():
         assert prog.control_words()[1] == 0
 
 
-def random_element_program(rng, n, n_stores, with_fold):
-    """A cluster of maps, generates and gathers over a few inputs: every root a tree, so that the whole
-    program is one legal cluster."""
-    g = Graph()
-    ins = {}
-    count = [0]
+class ProgramMaker:
+    """Random element programs over a few inputs of one shape: every root a tree, so that the roots
+    together with one consumer are one legal cluster."""
 
-    def fresh(prefix):
-        count[0] += 1
-        return f"{prefix}{count[0]}"
+    def __init__(self, rng, shape):
+        self.rng, self.shape = rng, tuple(shape)
+        self.size = int(np.prod(shape))
+        self.g, self.ins = Graph(), {}
+        self.count = 0
+        self.pool = {"f32": [], "i32": []}               # a handful of inputs, read from several places
 
-    pool = {"f32": [], "i32": []}                      # a handful of inputs, read from several places
+    def fresh(self, prefix):
+        self.count += 1
+        return f"{prefix}{self.count}"
 
-    def leaf_f32():
-        if len(pool["f32"]) == 4 or (pool["f32"] and rng.integers(0, 2)):
-            return pool["f32"][rng.integers(0, len(pool["f32"]))]
-        name = fresh("x")
-        g.add(name, "input", "f32", (n,))
-        ins[name] = rng.uniform(0.0, 1.0, size=n).astype(F32)
-        pool["f32"].append(name)
+    def leaf_f32(self):
+        rng, pool = self.rng, self.pool["f32"]
+        if len(pool) == 3 or (pool and rng.integers(0, 2)):
+            return pool[rng.integers(0, len(pool))]
+        name = self.fresh("x")
+        self.g.add(name, "input", "f32", self.shape)
+        self.ins[name] = rng.uniform(0.0, 1.0, size=self.shape).astype(F32)
+        pool.append(name)
         return name
 
-    def index(depth):
-        kind = rng.integers(0, 4 if depth > 0 else 3)
-        if kind == 0 and len(pool["i32"]) == 2:
-            return pool["i32"][rng.integers(0, 2)]
-        name = fresh("i")
+    def leaf_i32(self):
+        """Flat positions inside the arrays."""
+        rng, pool = self.rng, self.pool["i32"]
+        if len(pool) == 2:
+            return pool[rng.integers(0, 2)]
+        name = self.fresh("i")
+        self.g.add(name, "input", "i32", self.shape)
+        self.ins[name] = rng.integers(0, self.size, size=self.shape, dtype=np.int32)
+        pool.append(name)
+        return name
+
+    def index(self, depth, root=False):
+        rng = self.rng
+        kind = rng.integers(1 if root else 0, 4 if depth > 0 else 3)
         if kind == 0:
-            g.add(name, "input", "i32", (n,))
-            ins[name] = rng.integers(0, n, size=n, dtype=np.int32)
-            pool["i32"].append(name)
-        elif kind == 1:
-            g.add(name, "generate", "i32", (n,), fn="iota_rev")
+            return self.leaf_i32()
+        name = self.fresh("i")
+        if kind == 1:
+            self.g.add(name, "generate", "i32", self.shape, fn="iota_rev", output=root)
         elif kind == 2:
-            g.add(name, "generate", "i32", (n,), fn="iota")
+            self.g.add(name, "generate", "i32", self.shape, fn="iota", output=root)
         else:
-            g.add(name, "gather", "i32", (n,), args=(index(0), index(depth - 1)))
+            self.g.add(name, "gather", "i32", self.shape, args=(self.index(0), self.index(depth - 1)), output=root)
         return name
 
-    def value(depth, root=False):
+    def flags(self, depth):
+        """Zeros and ones computed from positions."""
+        name = self.fresh("f")
+        k = int(self.rng.integers(2, 6))
+        self.g.add(name, "map", "i32", self.shape, fn="mod_eq", iparam=(k, int(self.rng.integers(0, k))), args=(self.index(depth),))
+        return name
+
+    def value(self, depth, root=False):
+        rng, g, shape = self.rng, self.g, self.shape
         kind = rng.integers(1 if root else 0, 8) if depth > 0 else 0
         if kind == 0:
-            return leaf_f32()
-        name = fresh("v")
+            return self.leaf_f32()
+        name = self.fresh("v")
         if kind in (1, 2):
             fn = ("affine", "sq_plus_one", "exp_neg", "sin_x_mul_x", "ident")[rng.integers(0, 5)]
             kw = {"fparam": (float(rng.uniform(0.5, 1.5)), float(rng.uniform(-0.5, 0.5)))} if fn == "affine" else {}
-            g.add(name, "map", "f32", (n,), fn=fn, args=(value(depth - 1),), output=root, **kw)
+            g.add(name, "map", "f32", shape, fn=fn, args=(self.value(depth - 1),), output=root, **kw)
         elif kind in (3, 4):
-            g.add(name, "map", "f32", (n,), fn=("mul2", "add2")[rng.integers(0, 2)], args=(value(depth - 1), value(depth - 1)),
-                  output=root)
+            g.add(name, "map", "f32", shape, fn=("mul2", "add2")[rng.integers(0, 2)],
+                  args=(self.value(depth - 1), self.value(depth - 1)), output=root)
         elif kind == 5:
-            g.add(name, "map", "f32", (n,), fn="add3", args=(value(depth - 1), value(0), value(depth - 1)), output=root)
+            g.add(name, "map", "f32", shape, fn="add3", args=(self.value(depth - 1), self.value(0), self.value(depth - 1)),
+                  output=root)
         else:
-            g.add(name, "gather", "f32", (n,), args=(index(1), value(depth - 1)), output=root)
+            g.add(name, "gather", "f32", shape, args=(self.index(1), self.value(depth - 1)), output=root)
         return name
 
+
+def random_element_program(rng, n, n_stores, with_fold):
+    """A cluster of maps, generates and gathers that ends in stored arrays and at most one fold."""
+    pm = ProgramMaker(rng, (n,))
     for _ in range(n_stores):
-        value(3, root=True)                            # a stored array is computed by the cluster
+        pm.value(3, root=True)                         # a stored array is computed by the cluster
     if with_fold:
-        g.add("total", "fold", "f32", (1,), fn=("add", "max")[rng.integers(0, 2)], args=(value(3),), output=True)
-    return g, ins
+        pm.g.add("total", "fold", "f32", (1,), fn=("add", "max")[rng.integers(0, 2)], args=(pm.value(3),), output=True)
+    return pm.g, pm.ins
 
 
 def test_interpreted_clusters_match_the_compiled_kernels():
@@ -376,6 +400,192 @@ def test_interpreted_clusters_match_the_compiled_kernels():
     P.assert_bit_exact(fused.fetch("out"), env["out"], "stored and folded: out")
     P.assert_fold(fused.fetch("tot"), env["tot"], "stored and folded: tot")
     assert fused.control_words()[1] == 0
+
+
+def one_cluster(g):
+    part = fc().fc_partition_check(g, [0 if nd.kind == "input" else 1 for nd in g.nodes])
+    return part, fc().fc_cluster_kernel(g, part, 0)
+
+
+class TooLarge(Exception):
+    pass
+
+
+def fused_and_unfused(g, ins):
+    try:
+        part, name = one_cluster(g)
+    except fc().FcError as e:                            # deeper than the interpreter's stack, too many inputs
+        assert e.name == "FC_E_UNSUPPORTED"
+        raise TooLarge()
+    inter = [nd.name for nd in g.nodes if nd.kind != "input"]
+    fused, unfused = device_program(g, ins, part), device_program(g, ins, None, bind=inter)
+    fused.run()
+    unfused.run()
+    assert fused.control_words()[1] == 0
+    return fused, unfused, name
+
+
+def test_every_consumer_takes_any_element_program():
+    # segmented folds, scatters, scans (alone and as a compaction), row folds and row scans over
+    # random element programs that no instance was compiled for: the instances over Interp<K, T> run
+    # them.  Arrays that are stored, scanned or scattered agree bit for bit with the unfused arm (the
+    # same device functions in the same order); sums within the bound of the folds.
+    rng = np.random.default_rng(4242)
+    names = []
+    for trial in range(6):                                    # segmented fold of a computed array
+        n = int(rng.choice([1000, 70001]))
+        pm = ProgramMaker(rng, (n,))
+        v = pm.value(3, root=False)
+        if pm.g[v].kind == "input":
+            continue
+        rows = max(1, n // 9)
+        cuts = np.sort(rng.integers(0, n + 1, size=rows - 1))
+        off = np.concatenate([[0], cuts, [n]]).astype(np.int32)
+        pm.g.add("off", "input", "i32", (rows + 1,))
+        pm.ins["off"] = off
+        pm.g.add("y", "foldseg", "f32", (rows,), fn=("add", "max")[trial % 2], args=(v, "off"), output=True)
+        env = evaluate(pm.g, pm.ins)
+        try:
+            fused, unfused, name = fused_and_unfused(pm.g, pm.ins)
+        except TooLarge:
+            continue
+        names.append(name)
+        if trial % 2:
+            P.assert_bit_exact(fused.fetch("y"), unfused.fetch("y"), name)
+        else:
+            P.assert_segmented(fused.fetch("y"), env["y"], env[v], off, name)
+    for trial in range(8):                                    # scatter: computed index, value and flag
+        n = int(rng.choice([999, 50003]))
+        pm = ProgramMaker(rng, (n,))
+        add, flagged, ints = bool(trial & 1), bool(trial & 2), bool(trial & 4)
+        perm = rng.permutation(n).astype(np.int32)
+        pm.g.add("perm", "input", "i32", (n,))
+        pm.ins["perm"] = perm
+        pm.g.add("where", "gather", "i32", (n,), args=(pm.index(1, root=False), "perm"))   # distinct only if the index is
+        idx = "where" if add else None
+        if not add:                                          # overwrite needs distinct indices: a permutation read backwards
+            pm.g.add("back", "generate", "i32", (n,), fn="iota_rev")
+            pm.g.add("where2", "gather", "i32", (n,), args=("back", "perm"))
+            idx = "where2"
+        val = pm.index(2, root=False) if ints else pm.value(2, root=False)
+        if pm.g[val].kind == "input":
+            continue
+        dt = "i32" if ints else "f32"
+        pm.g.add("dest", "input", dt, (n,))
+        pm.ins["dest"] = (rng.integers(0, 100, size=n, dtype=np.int32) if ints else rng.uniform(0, 1, size=n).astype(F32))
+        args = ("dest", idx, val) + ((pm.flags(1),) if flagged else ())
+        pm.g.add("h", "scatter", dt, (n,), fn="add" if add else "overwrite", args=args, output=True)
+        # nodes nothing reads would be clusters of their own
+        g = prune(pm.g)
+        ins = {k: v for k, v in pm.ins.items() if k in {nd.name for nd in g.nodes}}
+        env = evaluate(g, ins)
+        try:
+            fused, unfused, name = fused_and_unfused(g, ins)
+        except TooLarge:
+            continue
+        names.append(name)
+        if add and not ints:
+            keep = env[args[3]].reshape(-1) != 0 if flagged else np.ones(n, bool)
+            scale = np.abs(ins["dest"]).astype(np.float64)
+            np.add.at(scale, env[idx].reshape(-1)[keep], np.abs(env[val].reshape(-1)[keep]).astype(np.float64))
+            assert np.all(np.abs(fused.fetch("h").astype(np.float64) - env["h"]) <= 1e-5 * scale + 1e-30), name
+        else:
+            P.assert_bit_exact(fused.fetch("h"), unfused.fetch("h"), name)
+    for trial in range(6):                                    # scans of computed flags; compaction of computed values
+        n = int(rng.choice([777, 12288 * 3 + 5, 200001]))
+        pm = ProgramMaker(rng, (n,))
+        flags = pm.flags(2)
+        mode = trial % 3
+        pm.g.add("offs", "scanl", "i32", (n,), fn="add", args=(flags,), output=(mode != 1))
+        outs = ["offs"] if mode != 1 else []
+        if mode >= 1:
+            ints = bool(trial & 1)
+            val = pm.index(2, root=False) if ints else pm.value(2, root=False)
+            if pm.g[val].kind == "input":
+                continue
+            dt = "i32" if ints else "f32"
+            pm.g.add("dest", "input", dt, (n,))
+            pm.ins["dest"] = np.zeros(n, dtype=np.int32 if ints else F32)
+            pm.g.add("out", "scatter", dt, (n,), fn="overwrite", args=("dest", "offs", val, flags), output=True)
+            pm.g.add("count", "fold", "i32", (1,), fn="add", args=(flags,), output=True)
+            outs += ["out", "count"]
+        g = prune(pm.g)
+        ins = {k: v for k, v in pm.ins.items() if k in {nd.name for nd in g.nodes}}
+        try:
+            fused, unfused, name = fused_and_unfused(g, ins)
+        except TooLarge:
+            continue
+        names.append(name)
+        for o in outs:
+            P.assert_bit_exact(fused.fetch(o), unfused.fetch(o), f"{name}/{o}")
+    for trial in range(4):                                    # prefix sums of a computed fp32 array
+        n = int(rng.choice([5000, 8192 * 5 + 3]))
+        pm = ProgramMaker(rng, (n,))
+        v = pm.value(3, root=False)
+        if pm.g[v].kind == "input":
+            continue
+        pm.g.add("l", "scanr" if trial & 1 else "scanl", "f32", (n,), fn="add", args=(v,), output=True)
+        env = evaluate(pm.g, pm.ins)
+        try:
+            fused, unfused, name = fused_and_unfused(pm.g, pm.ins)
+        except TooLarge:
+            continue
+        names.append(name)
+        got = fused.fetch("l").astype(np.float64)
+        assert np.all(np.abs(got - env["l"].astype(np.float64)) <= 1e-5 * prefix_scale(env[v], bool(trial & 1)) + 1e-30), name
+    for trial in range(8):                                    # rows: folds and scans of computed 2-D arrays
+        rows, w = [(37, 16), (5, 1000), (300, 17), (3, 5000)][trial % 4]
+        pm = ProgramMaker(rng, (rows, w))
+        if trial < 4:
+            v = pm.value(3, root=False)
+            if pm.g[v].kind == "input":
+                continue
+            fn = ("add", "max", "mul", "add")[trial]
+            if fn == "mul":                                   # keep the product of a row in range
+                pm.g.add("near1", "map", "f32", (rows, w), fn="affine", fparam=(1e-4, 1.0), args=(v,))
+                v = "near1"
+            pm.g.add("y", "fold", "f32", (rows,), fn=fn, args=(v,), output=True)
+            env = evaluate(pm.g, pm.ins)
+            try:
+                fused, unfused, name = fused_and_unfused(pm.g, pm.ins)
+            except TooLarge:
+                continue
+            got, ref = fused.fetch("y").astype(np.float64), env["y"].astype(np.float64)
+            if fn == "max":
+                P.assert_bit_exact(fused.fetch("y"), unfused.fetch("y"), name)
+            elif fn == "add":
+                assert np.all(np.abs(got - ref) <= 1e-5 * np.abs(env[v].astype(np.float64)).sum(axis=1) + 1e-30), name
+            else:
+                assert np.all(np.abs(got - ref) <= 1e-4 * np.abs(ref)), name
+        else:
+            flags = pm.flags(2)
+            pm.g.add("l", "scanr" if trial & 1 else "scanl", "i32", (rows, w), fn="add", args=(flags,), output=True)
+            try:
+                fused, unfused, name = fused_and_unfused(pm.g, pm.ins)
+            except TooLarge:
+                continue
+            P.assert_bit_exact(fused.fetch("l"), unfused.fetch("l"), name)
+        names.append(name)
+    generic = [k for k in names if "element programs interpreted" in k]
+    assert len(generic) >= 20, names
+    for shape in ("foldseg.", "scatter[", "scatter.add[", "scan[", "+scatter[", "+count", "scanr[", "rowfold.", "rowscan"):
+        assert any(shape in k for k in generic), (shape, generic)
+
+
+def prune(g):
+    """The graph without the nodes no output depends on."""
+    need, by_name = set(), {nd.name: nd for nd in g.nodes}
+    stack = [nd.name for nd in g.nodes if nd.output]
+    while stack:
+        a = stack.pop()
+        if a not in need:
+            need.add(a)
+            stack.extend(by_name[a].args)
+    out = Graph()
+    for nd in g.nodes:
+        if nd.name in need:
+            out.add(nd.name, nd.kind, nd.dtype, nd.shape, fn=nd.fn, fparam=nd.fparam, iparam=nd.iparam, args=nd.args, output=nd.output)
+    return out
 
 
 def test_row_scans():
