@@ -55,7 +55,8 @@ typedef enum fc_kind {
                        a prefix differs from the sequentially rounded sum by rounding only; an f32 scan can be
                        stored but not fused with a scatter or a fold (FC_E_UNSUPPORTED) */
   FC_SCANR    = 7,  /* exclusive suffix combine; traversal order 1 */
-  FC_SCATTER  = 8,  /* arg0 = dest (infusible, updated in place), arg1 = index, arg2 = value, arg3 = flag (optional);
+  FC_SCATTER  = 8,  /* arg0 = dest (infusible, updated in place; none of the other arguments may be the same array:
+                       FC_E_BADGRAPH), arg1 = index, arg2 = value, arg3 = flag (optional);
                        fn = OVERWRITE (kept indices distinct) or ADD (colliding indices combine: exact for i32,
                        in an unspecified order for f32) */
   FC_FORCE    = 9   /* identity; every edge out of it is infusible */

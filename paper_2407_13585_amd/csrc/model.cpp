@@ -123,6 +123,9 @@ int build_model(const fc_graph *g, Model &m, std::string &err) {
         if (A(1).shape[0] * A(1).shape[1] != A(2).shape[0] * A(2).shape[1]) return bad(i, "index and value sizes differ");
         if (nd.nargs == 4 && (A(3).dtype != FC_I32 || A(3).shape[0] * A(3).shape[1] != A(1).shape[0] * A(1).shape[1]))
           return bad(i, "flag must be i32 of the source size");
+        // the destination is updated in place while the other arguments are being read
+        for (int k = 1; k < nd.nargs; ++k)
+          if (nd.arg[k] == nd.arg[0]) return bad(i, "scatter reads its destination as index, value or flag");
         break;
       case FC_FORCE:
         if (nd.nargs != 1) return bad(i, "force takes one array");

@@ -51,8 +51,8 @@ class DeviceProgram:
         for n in graph.nodes:
             if n.name in wanted and n.kind not in ("input", "scatter"):
                 self.buffers[n.name] = torch.zeros(max(n.size, 4), dtype=_TORCH[n.dtype], device=self.device)
-        for n in graph.nodes:          # a scatter lives in the buffer of its destination
-            if n.kind == "scatter":
+        for n in graph.nodes:          # a scatter lives in the buffer of its destination (if the caller holds that one)
+            if n.kind == "scatter" and by_name[n.args[0]].name in self.buffers:
                 self.buffers[n.name] = self.buffers[by_name[n.args[0]].name]
         nbytes = B.fc_scratch_bytes(self.cg, partition)
         self.scratch = torch.zeros((nbytes + 3) // 4, dtype=torch.int32, device=self.device)

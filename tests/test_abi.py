@@ -99,6 +99,21 @@ def test_run_checks_come_before_any_launch():
     expect("FC_E_SCRATCH", fc.fc_run_unfused, g, bufs, (0x10000000, B.FC_SCRATCH_CONTROL_BYTES))
 
 
+def test_scatter_that_reads_its_destination_is_refused():
+    # the destination is updated in place; a scatter that took its values (or indices, or flags)
+    # from the same array would read what it is overwriting
+    g = Graph()
+    g.add("d", "input", "i32", (16,))
+    g.add("i", "input", "i32", (16,))
+    g.add("h", "scatter", "i32", (16,), fn="add", args=("d", "i", "d"), output=True)
+    expect("FC_E_BADGRAPH", fc.fc_plan, g, "bytes")
+    g = Graph()
+    g.add("d", "input", "i32", (16,))
+    g.add("v", "input", "i32", (16,))
+    g.add("h", "scatter", "i32", (16,), fn="overwrite", args=("d", "d", "v"), output=True)
+    expect("FC_E_BADGRAPH", fc.fc_plan, g, "bytes")
+
+
 def test_unsupported_cluster_is_reported_not_executed():
     # a legal clustering with a cluster no kernel is built for: a stored predicate scanned in its own loop
     g = Graph()

@@ -588,6 +588,136 @@ def prune(g):
     return out
 
 
+def random_program(rng, n, n_ops):
+    """A random program over arrays of n elements that can be executed: arrays used as positions hold
+    positions (inputs below n, iota, gathers of such), everything else is typed by what produced it."""
+    g, ins = Graph(), {}
+    pos, flags, ints, flts = [], [], [], []                  # positions, zeros and ones, any i32, f32
+    for k in range(2):
+        g.add(f"p{k}", "input", "i32", (n,))
+        ins[f"p{k}"] = rng.integers(0, n, size=n, dtype=np.int32)
+        pos.append(f"p{k}")
+        g.add(f"x{k}", "input", "f32", (n,))
+        ins[f"x{k}"] = rng.uniform(0.0, 1.0, size=n).astype(F32)
+        flts.append(f"x{k}")
+    g.add("perm", "input", "i32", (n,))
+    ins["perm"] = rng.permutation(n).astype(np.int32)
+    pick = lambda pool: str(pool[rng.integers(0, len(pool))])
+    scattered = set()
+    for k in range(n_ops):
+        nm = f"t{k}"
+        kind = str(rng.choice(["map1", "map1", "map2", "gen", "gatherp", "gatherf", "gatherf", "flags", "scani", "scanf",
+                               "foldf", "foldi", "scatterf", "scatteri"]))
+        if kind == "map1":
+            fn = str(rng.choice(["affine", "sq_plus_one", "exp_neg", "sin_x_mul_x"]))
+            kw = {"fparam": (float(rng.uniform(0.5, 1.0)), float(rng.uniform(0.0, 0.5)))} if fn == "affine" else {}
+            g.add(nm, "map", "f32", (n,), fn=fn, args=(pick(flts),), **kw)
+            flts.append(nm)
+        elif kind == "map2":
+            g.add(nm, "map", "f32", (n,), fn=str(rng.choice(["mul2", "add2"])), args=(pick(flts), pick(flts)))
+            flts.append(nm)
+        elif kind == "gen":
+            g.add(nm, "generate", "i32", (n,), fn=str(rng.choice(["iota", "iota_rev"])))
+            pos.append(nm)
+        elif kind == "gatherp":
+            g.add(nm, "gather", "i32", (n,), args=(pick(pos), pick(pos)))
+            pos.append(nm)
+        elif kind == "gatherf":
+            g.add(nm, "gather", "f32", (n,), args=(pick(pos), pick(flts)))
+            flts.append(nm)
+        elif kind == "flags":
+            m = int(rng.integers(2, 5))
+            g.add(nm, "map", "i32", (n,), fn="mod_eq", iparam=(m, int(rng.integers(0, m))), args=(pick(pos + ints),))
+            flags.append(nm)
+        elif kind == "scani":
+            g.add(nm, str(rng.choice(["scanl", "scanr"])), "i32", (n,), fn="add", args=(pick(flags or pos),))
+            ints.append(nm)
+        elif kind == "scanf":
+            g.add(nm, str(rng.choice(["scanl", "scanr"])), "f32", (n,), fn="add", args=(pick(flts),))
+            # prefix sums grow with n: bring them back to the size of the other values
+            g.add(nm + "s", "map", "f32", (n,), fn="affine", fparam=(1.0 / n, 0.0), args=(nm,))
+            flts.append(nm + "s")
+        elif kind == "foldf":
+            g.add(nm, "fold", "f32", (1,), fn=str(rng.choice(["add", "max"])), args=(pick(flts),), output=True)
+        elif kind == "foldi":
+            if flags and rng.integers(0, 2):
+                g.add(nm, "fold", "i32", (1,), fn="add", args=(pick(flags),), output=True)      # a count
+            else:
+                g.add(nm, "fold", "i32", (1,), fn="max", args=(pick(flags + ints or pos),), output=True)
+        else:
+            f32 = kind == "scatterf"
+            dests = [d for d in (flts if f32 else ints + flags) if d not in scattered and g[d].kind != "input"]
+            if not dests:
+                continue
+            dest = pick(dests)
+            scattered.add(dest)
+            # overwrite at distinct positions (a permutation, or one read backwards); i32 may also combine anywhere
+            if f32 or rng.integers(0, 2):
+                g.add(nm + "b", "generate", "i32", (n,), fn="iota_rev")
+                g.add(nm + "w", "gather", "i32", (n,), args=(nm + "b", "perm"))
+                where, fn = nm + "w", "overwrite"
+            else:
+                where, fn = pick(pos), "add"
+            # the destination is updated in place, so the scatter reads everything else from other arrays
+            values = [v for v in (flts if f32 else flags + ints or pos) if v != dest] or pos
+            if f32 and values is pos:
+                continue
+            others = [f for f in flags if f != dest]
+            args = (dest, where, pick(values)) + ((pick(others),) if others and rng.integers(0, 2) else ())
+            g.add(nm, "scatter", "f32" if f32 else "i32", (n,), fn=fn, args=args)
+            # the scatter updates its destination in place: from here on the program names the result only
+            for pool in (pos, flags, ints, flts):
+                if dest in pool:
+                    pool.remove(dest)
+            (flts if f32 else ints).append(nm)
+            scattered.add(nm)
+        if sum(nd.kind != "input" for nd in g.nodes) >= 11:      # the chooser is exact: keep its search short
+            break
+    return g, ins
+
+
+def with_outputs(g):
+    """Every array nothing reads becomes a result (it is manifest anyway)."""
+    read = {a for nd in g.nodes for a in nd.args}
+    out = Graph()
+    for nd in g.nodes:
+        out.add(nd.name, nd.kind, nd.dtype, nd.shape, fn=nd.fn, fparam=nd.fparam, iparam=nd.iparam, args=nd.args,
+                output=nd.output or (nd.kind != "input" and nd.name not in read))
+    return out
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_programs_planned_and_run(seed):
+    # whole programs: a random DAG over every combinator, planned by the ILP among the clusterings the
+    # library runs, executed fused and unfused.  Integers agree exactly with the oracle; fp32 arrays agree
+    # bit for bit between the two arms (same device functions in the same order) and closely with the
+    # oracle; fp32 sums within the bound of the folds.
+    rng = np.random.default_rng(7000 + seed)
+    n = int(rng.choice([1000, 4097, 30001]))
+    g, ins = random_program(rng, n, int(rng.integers(4, 11)))
+    g = with_outputs(g)
+    used = {a for nd in g.nodes for a in nd.args}
+    ins = {k: v for k, v in ins.items()}
+    env = evaluate(g, ins)
+    part = fc().fc_plan(g, "bytes", executable=True)
+    inter = [nd.name for nd in g.nodes if nd.kind != "input"]
+    fused, unfused = device_program(g, ins, part), device_program(g, ins, None, bind=inter)
+    fused.run()
+    unfused.run()
+    assert fused.control_words()[1] == 0 and unfused.control_words()[1] == 0
+    for out in g.outputs():
+        nd = g[out]
+        got, ref = fused.fetch(out), env[out]
+        what = f"seed {seed} {out} {fused.kernels()}"
+        if nd.dtype == "i32":
+            P.assert_bit_exact(got, ref, what)
+        elif nd.kind == "fold" and nd.fn == "add":
+            assert abs(float(got[0]) - float(ref[0])) <= 1e-5 * np.abs(env[nd.args[0]].astype(np.float64)).sum() + 1e-30, what
+        else:
+            P.assert_bit_exact(got, unfused.fetch(out), what)
+            P.assert_close(got, ref, 2e-4, what, abs_=2e-5)
+
+
 def test_row_scans():
     # scans of two-dimensional arrays run row by row; row lengths on both sides of the
     # 16-lane / wave / workgroup variants, ragged against their step, with and without a fused producer
