@@ -134,6 +134,8 @@ typedef struct fc_partition {
   uint8_t *edge_unfused;  /* x_ab: 0 = fused over, 1 = not                              */
   int32_t  n_clusters;    /* (out) clusters after the connected-component split         */
   double   cost;          /* (out) value of the requested cost function                 */
+  int32_t  proven;        /* (out, fc_plan and fc_plan_weighted) 1: the clustering is optimal; 0: it is the
+                             best one found when the search budget of FC_PLAN_ANYTIME ran out */
 } fc_partition;
 
 /* cost functions of section 4.1 ("Cost function"), evaluated on the ILP solution */
@@ -148,6 +150,14 @@ typedef enum fc_cost {
 
 /* plan flags */
 #define FC_PLAN_NO_SPLIT 1u  /* keep the raw ILP solution (skip the connected-component split) */
+#define FC_PLAN_ANYTIME 4u    /* the chooser is an exact branch and bound: its time grows exponentially with the
+                                 number of combinators (fractions of a second up to 20, minutes from 30 on).
+                                 With this flag it starts from a clustering built greedily without backtracking,
+                                 searches for two seconds at most and returns the best clustering found, which
+                                 is legal at any moment; fc_partition.proven says whether the search had
+                                 finished.  Programs of more than 64 combinators get the greedy clustering.
+                                 Without the flag a search that exceeds its (much larger) budget, or a program
+                                 of more than 64 combinators, ends in FC_E_LIMIT */
 #define FC_PLAN_EXECUTABLE 2u /* choose among the clusterings fc_run_fused has kernels for: the kernels are a fixed
                                  set of cluster shapes, and the optimum of the ILP may contain a legal cluster that
                                  is not among them (fc_run_fused would answer FC_E_UNSUPPORTED).  With this flag the

@@ -31,6 +31,7 @@ OP = {"add": 64, "max": 65, "mul": 66, "overwrite": 67}
 COST = {"clusters": 0, "fused_edges": 1, "arrays": 2, "reads": 3, "reads_writes": 4, "bytes": 5}
 FC_PLAN_NO_SPLIT = 1
 FC_PLAN_EXECUTABLE = 2
+FC_PLAN_ANYTIME = 4
 FC_NODE_OUTPUT = 1
 
 ERRORS = {-1: "FC_E_BADGRAPH", -2: "FC_E_ILLEGAL_PARTITION", -3: "FC_E_UNSUPPORTED", -4: "FC_E_UNBOUND",
@@ -60,7 +61,7 @@ class fc_partition(C.Structure):
     _fields_ = [("n_nodes", C.c_int32), ("n_edges", C.c_int32),
                 ("pi", C.POINTER(C.c_int32)), ("fused_away", C.POINTER(C.c_uint8)),
                 ("order_out", C.POINTER(C.c_int32)), ("edge_unfused", C.POINTER(C.c_uint8)),
-                ("n_clusters", C.c_int32), ("cost", C.c_double)]
+                ("n_clusters", C.c_int32), ("cost", C.c_double), ("proven", C.c_int32)]
 
 
 class fc_buffer(C.Structure):
@@ -172,6 +173,7 @@ class Partition:
     edge_unfused: np.ndarray
     n_clusters: int = 0
     cost: float = 0.0
+    proven: bool = True          # False: the best clustering found when an anytime search ran out of budget
 
     def _c(self) -> fc_partition:
         self.pi = np.ascontiguousarray(self.pi, dtype=np.int32)
@@ -193,7 +195,7 @@ class Partition:
 
 
 def _finish(part: Partition, cp: fc_partition) -> Partition:
-    part.n_clusters, part.cost = int(cp.n_clusters), float(cp.cost)
+    part.n_clusters, part.cost, part.proven = int(cp.n_clusters), float(cp.cost), bool(cp.proven)
     return part
 
 
@@ -205,16 +207,17 @@ def fc_num_edges(graph) -> int:
     return n.value
 
 
-def _plan_flags(no_split: bool, executable: bool) -> int:
-    return (FC_PLAN_NO_SPLIT if no_split else 0) | (FC_PLAN_EXECUTABLE if executable else 0)
+def _plan_flags(no_split: bool, executable: bool, anytime: bool = False) -> int:
+    return (FC_PLAN_NO_SPLIT if no_split else 0) | (FC_PLAN_EXECUTABLE if executable else 0) | (FC_PLAN_ANYTIME if anytime else 0)
 
 
-def fc_plan(graph, cost: str = "bytes", no_split: bool = False, executable: bool = False) -> Partition:
-    """executable: choose among the clusterings the library has kernels for (FC_PLAN_EXECUTABLE)."""
+def fc_plan(graph, cost: str = "bytes", no_split: bool = False, executable: bool = False, anytime: bool = False) -> Partition:
+    """executable: choose among the clusterings the library has kernels for (FC_PLAN_EXECUTABLE).
+    anytime: search for a few seconds at most and return the best clustering found (Partition.proven tells)."""
     g = _cg(graph)
     part = Partition.empty(len(g.names), g.n_edges)
     cp = part._c()
-    _check(lib().fc_plan(g.ref(), COST[cost], _plan_flags(no_split, executable), C.byref(cp)))
+    _check(lib().fc_plan(g.ref(), COST[cost], _plan_flags(no_split, executable, anytime), C.byref(cp)))
     return _finish(part, cp)
 
 
@@ -232,11 +235,11 @@ def _weights(weights) -> "C.Array":
     return (C.c_double * len(COST))(*vec)
 
 
-def fc_plan_weighted(graph, weights, no_split: bool = False, executable: bool = False) -> Partition:
+def fc_plan_weighted(graph, weights, no_split: bool = False, executable: bool = False, anytime: bool = False) -> Partition:
     g = _cg(graph)
     part = Partition.empty(len(g.names), g.n_edges)
     cp = part._c()
-    _check(lib().fc_plan_weighted(g.ref(), _weights(weights), _plan_flags(no_split, executable), C.byref(cp)))
+    _check(lib().fc_plan_weighted(g.ref(), _weights(weights), _plan_flags(no_split, executable, anytime), C.byref(cp)))
     return _finish(part, cp)
 
 

@@ -34,7 +34,7 @@ template <class F> int guarded(F &&f) {
   }
 }
 
-int fill_partition(const fc::Model &m, const fc::Clustering &c, int n_clusters, double cost, fc_partition *out) {
+int fill_partition(const fc::Model &m, const fc::Clustering &c, int n_clusters, double cost, fc_partition *out, bool proven = true) {
   if (!out || out->n_nodes < m.n || out->n_edges < (int)m.edges.size())
     return fail(FC_E_ARG, "partition arrays are too small");
   if (m.n && (!out->pi || !out->fused_away || !out->order_out)) return fail(FC_E_ARG, "null partition array");
@@ -47,7 +47,15 @@ int fill_partition(const fc::Model &m, const fc::Clustering &c, int n_clusters, 
   for (size_t e = 0; e < m.edges.size(); ++e) out->edge_unfused[e] = c.x[e];
   out->n_clusters = n_clusters;
   out->cost = cost;
+  out->proven = proven ? 1 : 0;
   return FC_OK;
+}
+
+// FC_PLAN_ANYTIME: a search of a few seconds, the best clustering found if it does not finish
+fc::SearchBudget budget_of(uint32_t flags) {
+  fc::SearchBudget b;
+  if (flags & FC_PLAN_ANYTIME) { b.seconds = 2.0; b.anytime = true; }
+  return b;
 }
 
 int load_clustering(const fc::Model &m, const fc_partition *p, fc::Clustering &c, std::string &err) {
@@ -101,9 +109,11 @@ int fc_plan(const fc_graph *g, int cost_fn, uint32_t flags, fc_partition *out) {
     fc::Clustering c;
     int n_clusters = 0;
     double cost = 0;
-    rc = fc::choose_clustering(m, cost_fn, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err, executable_only(m, flags));
+    fc::SearchBudget budget = budget_of(flags);
+    rc = fc::choose_clustering(m, cost_fn, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err, executable_only(m, flags),
+                               &budget);
     if (rc != FC_OK) return fail(rc, err);
-    return fill_partition(m, c, n_clusters, cost, out);
+    return fill_partition(m, c, n_clusters, cost, out, budget.proven);
   });
 }
 
@@ -117,10 +127,11 @@ int fc_plan_weighted(const fc_graph *g, const double *weights, uint32_t flags, f
     fc::Clustering c;
     int n_clusters = 0;
     double cost = 0;
+    fc::SearchBudget budget = budget_of(flags);
     rc = fc::choose_clustering_weighted(m, weights, !(flags & FC_PLAN_NO_SPLIT), c, n_clusters, cost, err,
-                                        executable_only(m, flags));
+                                        executable_only(m, flags), &budget);
     if (rc != FC_OK) return fail(rc, err);
-    return fill_partition(m, c, n_clusters, cost, out);
+    return fill_partition(m, c, n_clusters, cost, out, budget.proven);
   });
 }
 

@@ -250,6 +250,39 @@ int derive_and_check(const Model &m, const std::vector<int> &pi, Clustering &c, 
   return FC_OK;
 }
 
+bool orders_completable(const Model &m, const std::vector<int> &block) {
+  const int n = m.n;
+  UnionFind uf(n);
+  for (int a = 0; a < n; ++a) {
+    if (block[a] < 0) continue;
+    if (m.nodes[a].kind == FC_SCANL && !uf.set_const(a, 0)) return false;
+    if (m.nodes[a].kind == FC_SCANR && !uf.set_const(a, 1)) return false;
+  }
+  for (const Edge &ed : m.edges) {
+    if (block[ed.a] < 0 || block[ed.b] < 0 || block[ed.a] != block[ed.b]) continue;
+    bool ok = true;
+    switch (m.in_order(ed.b, ed.slot)) {
+      case InOrder::SameAsOut: ok = uf.unite(ed.a, ed.b); break;
+      case InOrder::Label: ok = uf.set_const(ed.a, m.label[ed.b]); break;
+      case InOrder::Zero: ok = uf.set_const(ed.a, 0); break;
+      case InOrder::One: ok = uf.set_const(ed.a, 1); break;
+      case InOrder::None: ok = false; break;
+    }
+    if (!ok) return false;
+  }
+  for (int a = 0; a < n; ++a) {
+    if (block[a] < 0) continue;
+    if (uf.konst[uf.find(a)] <= 1) continue;
+    bool manifest = m.nodes[a].kind == FC_SCATTER || m.out_edges[a].empty() || (m.nodes[a].flags & FC_NODE_OUTPUT);
+    for (int e : m.out_edges[a]) {
+      const int b = m.edges[e].b;
+      manifest = manifest || (block[b] >= 0 && block[b] != block[a]);
+    }
+    if (manifest) return false;
+  }
+  return true;
+}
+
 double evaluate_cost(const Model &m, const Clustering &c, int cost_fn) {
   const int n = m.n;
   auto reads = [&](bool weighted) {

@@ -57,6 +57,13 @@ struct Clustering {
 // Returns FC_OK or FC_E_ILLEGAL_PARTITION (err says which rule).
 int derive_and_check(const Model &m, const std::vector<int> &pi, Clustering &c, std::string &err);
 
+// Can a partial clustering still be completed as far as traversal orders go?  block[a] >= 0:
+// the cluster node a has been put into; -1: not placed yet; -2: a program input.  The order
+// equalities over edges inside one cluster only grow as nodes are added, so a conflict among
+// the placed nodes stays one; likewise an array that is certainly manifest (a result, or read
+// from another cluster already) cannot take the order of a gather.
+bool orders_completable(const Model &m, const std::vector<int> &block);
+
 double evaluate_cost(const Model &m, const Clustering &c, int cost_fn);
 
 // Connected-component split (section 4.1, "Performance and correctness"):

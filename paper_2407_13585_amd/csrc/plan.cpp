@@ -13,6 +13,7 @@
 #include "plan.hpp"
 
 #include <algorithm>
+#include <chrono>
 #include <map>
 #include <set>
 
@@ -35,6 +36,8 @@ struct Search {
   bool aborted = false;
   std::vector<int> forced;         // per node: representative of the set it must share a cluster with
   bool stop_at_first = false;      // feasibility question only
+  double seconds = 0;                       // wall-clock limit of the search, 0 = none
+  std::chrono::steady_clock::time_point started = std::chrono::steady_clock::now();
   const Admissible *admissible = nullptr;   // extra condition on complete clusterings
   bool split = true;                        // it is judged after the connected-component split
   // block graph: adj[b] = bitmask of blocks that must run strictly after b
@@ -47,7 +50,39 @@ struct Search {
     }
     forced.resize(m.n);
     for (int a = 0; a < m.n; ++a) forced[a] = a;
+    // What an array costs whatever the clustering: a write if it cannot be fused away (a result, no
+    // consumer, an infusible edge, or consumers that ask for different fixed traversal orders: a scan
+    // from the left and one from the right, the sources of two gathers), and then at least one read
+    // unless it is manifest only for being a result; an input is read once per fixed order asked of it.
+    sure_write.assign(m.n, 0);
+    sure_reads.assign(m.n, 0);
+    for (int a = 0; a < m.n; ++a) {
+      std::vector<int> fixed;                        // distinct constant orders among the consumers
+      bool infusible = false;
+      for (int e : m.out_edges[a]) {
+        const Edge &ed = m.edges[e];
+        infusible = infusible || !ed.fusible;
+        int k = -1;
+        switch (m.in_order(ed.b, ed.slot)) {
+          case InOrder::Label: k = m.label[ed.b]; break;
+          case InOrder::Zero: k = 0; break;
+          case InOrder::One: k = 1; break;
+          default: break;
+        }
+        if (k >= 0 && std::find(fixed.begin(), fixed.end(), k) == fixed.end()) fixed.push_back(k);
+      }
+      if (m.is_input(a)) {
+        sure_reads[a] = m.out_edges[a].empty() ? 0 : std::max<int>(1, (int)fixed.size());
+      } else {
+        const bool result = m.out_edges[a].empty() || (m.nodes[a].flags & FC_NODE_OUTPUT);
+        const bool split = infusible || fixed.size() > 1;
+        sure_write[a] = result || split;
+        sure_reads[a] = split ? 1 : 0;
+      }
+    }
   }
+  std::vector<char> sure_write;
+  std::vector<int> sure_reads;
 
   int forced_root(int a) const { while (forced[a] != a) a = forced[a]; return a; }
   void force_together(int a, int b) {
@@ -73,19 +108,28 @@ struct Search {
   double lower_bound() const {
     double reads = 0, writes = 0, unfused = 0, bytes = 0;
     for (int a = 0; a < m.n; ++a) {
-      if (block[a] == -1) continue;
+      if (block[a] == -1) {
+        // not placed yet: what it costs whatever happens
+        writes += sure_write[a];
+        reads += sure_reads[a];
+        bytes += (double)m.bytes(a) * (sure_write[a] + sure_reads[a]);
+        continue;
+      }
       uint64_t readers = 0;
+      std::vector<int> many;                           // the reader blocks when there are more than 64 blocks
       bool manifest = !m.is_input(a) && (m.out_edges[a].empty() || (m.nodes[a].flags & FC_NODE_OUTPUT));
       for (int e : m.out_edges[a]) {
         int b = m.edges[e].b;
         if (block[b] < 0) continue;
         if (block[b] != block[a]) {
-          readers |= 1ull << block[b];
+          if (block[b] < 64) readers |= 1ull << block[b];
+          else if (std::find(many.begin(), many.end(), block[b]) == many.end()) many.push_back(block[b]);
           if (!m.is_input(a)) manifest = true;
           if (m.edges[e].fusible) unfused += 1;
         }
       }
-      const int r = __builtin_popcountll(readers);
+      int r = std::max(__builtin_popcountll(readers) + (int)many.size(), sure_reads[a]);
+      manifest = manifest || sure_write[a];
       reads += r;
       if (manifest) writes += 1;
       bytes += (double)m.bytes(a) * (r + (manifest ? 1 : 0));
@@ -133,9 +177,103 @@ struct Search {
     if (stop_at_first) aborted = true;
   }
 
+  // Is the clustering "placed nodes in their blocks, every other combinator alone" a legal one?
+  // If so `pi` receives its cluster numbers.  Used by the greedy construction below: a step that
+  // keeps this true can always be completed.
+  bool legal_with_the_rest_alone(std::vector<int> &pi) const {
+    std::vector<int> blk(m.n, -1);
+    int nb = n_blocks;
+    for (int a : order) blk[a] = block[a] >= 0 ? block[a] : nb++;
+    std::vector<std::vector<int>> after(nb);          // block -> blocks that must run later
+    std::vector<int> indeg(nb, 0);
+    auto before = [&](int x, int y) { after[x].push_back(y); ++indeg[y]; };
+    for (const Edge &ed : m.edges) {
+      if (m.is_input(ed.a)) continue;
+      if (blk[ed.a] != blk[ed.b]) before(blk[ed.a], blk[ed.b]);
+    }
+    for (int j : order) {
+      if (m.nodes[j].kind != FC_SCATTER) continue;
+      const int d = m.nodes[j].arg[0];
+      for (int e : m.out_edges[d]) {
+        const int i = m.edges[e].b;
+        if (i == j) continue;
+        if (blk[i] == blk[j]) return false;
+        before(blk[i], blk[j]);
+      }
+    }
+    std::vector<int> ready, level(nb, 0);
+    for (int b = nb - 1; b >= 0; --b) if (!indeg[b]) ready.push_back(b);
+    int done = 0;
+    while (!ready.empty()) {
+      const int b = ready.back();
+      ready.pop_back();
+      level[b] = ++done;
+      for (int d : after[b]) if (--indeg[d] == 0) ready.push_back(d);
+    }
+    if (done != nb) return false;
+    pi.assign(m.n, 0);
+    for (int a : order) pi[a] = level[blk[a]];
+    Clustering c;
+    std::string why;
+    return derive_and_check(m, pi, c, why) == FC_OK;
+  }
+
+  // A clustering built without backtracking: the combinators in program order, each into the block
+  // (one that holds a producer of it or reads one of its arguments, or a new one) that keeps the partial
+  // cost lowest among those that leave a legal clustering when the remaining combinators stay alone.
+  // It gives the exact search something to improve on; on large programs the search's first descents
+  // tend to end in clusterings that turn out illegal only once complete.
+  void greedy_incumbent() {
+    std::vector<int> pi;
+    for (int a : order) {
+      std::vector<int> cand;
+      auto add = [&](int b) { if (b >= 0 && std::find(cand.begin(), cand.end(), b) == cand.end()) cand.push_back(b); };
+      for (int e : m.in_edges[a]) {
+        add(block[m.edges[e].a]);
+        for (int e2 : m.out_edges[m.edges[e].a]) add(block[m.edges[e2].b]);      // readers of the same array
+      }
+      cand.push_back(n_blocks);
+      int best_b = -1;
+      double best_lb = 1e300;
+      for (int b : cand) {
+        block[a] = b;
+        const bool fresh = b == n_blocks;
+        if (fresh) ++n_blocks;
+        if (legal_with_the_rest_alone(pi)) {
+          const double lb = lower_bound();
+          if (lb < best_lb) { best_lb = lb; best_b = b; }
+        }
+        if (fresh) --n_blocks;
+        block[a] = -1;
+      }
+      if (best_b < 0) { best_b = n_blocks; }           // cannot happen for a legal program
+      block[a] = best_b;
+      if (best_b == n_blocks) ++n_blocks;
+    }
+    Clustering c;
+    std::string why;
+    if (legal_with_the_rest_alone(pi) && derive_and_check(m, pi, c, why) == FC_OK) {
+      bool ok = true;
+      if (admissible && *admissible) {
+        Clustering shaped = c, again;
+        if (split) split_components(m, shaped); else renumber_levels(m, shaped);
+        ok = derive_and_check(m, shaped.pi, again, why) == FC_OK && (*admissible)(again);
+      }
+      const double cost = objective(c);
+      if (ok && cost < best) { best = cost * (1.0 + 1e-12) + 1e-9; best_pi = pi; }
+    }
+    for (int a : order) block[a] = -1;
+    n_blocks = 0;
+  }
+
   void go(size_t k) {
     if (aborted) return;
     if (++visited > limit) { aborted = true; return; }
+    if (seconds > 0 && (visited & 1023) == 0 &&
+        std::chrono::duration<double>(std::chrono::steady_clock::now() - started).count() > seconds) {
+      aborted = true;
+      return;
+    }
     if (k == order.size()) { leaf(); return; }
     const int a = order[k];
     // candidate blocks: those holding a producer of `a` first, then the others, then a new one
@@ -193,7 +331,7 @@ struct Search {
       if (ok) {
         block[a] = b;
         if (fresh) ++n_blocks;
-        if (lower_bound() < best) go(k + 1);
+        if (lower_bound() < best && orders_completable(m, block)) go(k + 1);
         if (fresh) --n_blocks;
         block[a] = -1;
       }
@@ -211,15 +349,18 @@ void unit_weights(int cost_fn, double *w) {
 }  // namespace
 
 int choose_clustering(const Model &m, int cost_fn, bool split, Clustering &out, int &n_clusters, double &cost,
-                      std::string &err, const Admissible &admissible) {
+                      std::string &err, const Admissible &admissible, SearchBudget *budget) {
   if (cost_fn < FC_COST_CLUSTERS || cost_fn > FC_COST_BYTES) { err = "unknown cost function"; return FC_E_ARG; }
   double w[kCosts];
   unit_weights(cost_fn, w);
-  return choose_clustering_weighted(m, w, split, out, n_clusters, cost, err, admissible);
+  return choose_clustering_weighted(m, w, split, out, n_clusters, cost, err, admissible, budget);
 }
 
 int choose_clustering_weighted(const Model &m, const double *weights, bool split, Clustering &out, int &n_clusters,
-                               double &cost, std::string &err, const Admissible &admissible) {
+                               double &cost, std::string &err, const Admissible &admissible, SearchBudget *budget) {
+  SearchBudget standard;
+  if (!budget) budget = &standard;
+  budget->proven = true;
   bool any = false;
   for (int k = 0; k < kCosts; ++k) {
     if (!(weights[k] >= 0) || weights[k] > 1e300) { err = "cost weights must be finite and not negative"; return FC_E_ARG; }
@@ -228,12 +369,31 @@ int choose_clustering_weighted(const Model &m, const double *weights, bool split
   if (!any) { err = "all cost weights are zero"; return FC_E_ARG; }
   int non_input = 0;
   for (int a = 0; a < m.n; ++a) non_input += !m.is_input(a);
-  if (non_input > 64) { err = "the exact chooser handles at most 64 combinators"; return FC_E_LIMIT; }
-  Search s(m, weights, 200000000LL);
+  if (non_input > 64 && !budget->anytime) { err = "the exact chooser handles at most 64 combinators"; return FC_E_LIMIT; }
+  Search s(m, weights, budget->nodes);
+  s.seconds = budget->seconds;
   s.admissible = &admissible;
   s.split = split;
-  s.go(0);
-  if (s.aborted) { err = "search limit reached before optimality was proven"; return FC_E_LIMIT; }
+  {
+    // a first incumbent: every combinator a cluster of its own, in program order (legal whenever the
+    // program is); the search only has to improve on it, and a search that is cut short has it to return
+    std::vector<int> alone(m.n, 0);
+    int next = 0;
+    for (int a = 0; a < m.n; ++a) if (!m.is_input(a)) alone[a] = ++next;
+    Clustering c;
+    std::string why;
+    if (derive_and_check(m, alone, c, why) == FC_OK && (!admissible || admissible(c))) {
+      s.best = s.objective(c) * (1.0 + 1e-12) + 1e-9;   // kept if nothing cheaper exists
+      s.best_pi = alone;
+    }
+  }
+  s.greedy_incumbent();
+  if (non_input > 64) s.aborted = true;          // the search keeps its blocks in 64-bit sets: the greedy clustering stands
+  else s.go(0);
+  if (s.aborted) {
+    if (!budget->anytime || s.best_pi.empty()) { err = "search limit reached before optimality was proven"; return FC_E_LIMIT; }
+    budget->proven = false;          // the best clustering found so far: legal, maybe not the cheapest
+  }
   if (s.best_pi.empty() && non_input > 0) {
     if (admissible) { err = "no clustering passes the extra condition"; return FC_E_UNSUPPORTED; }
     err = "no feasible clustering";

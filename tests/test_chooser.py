@@ -564,3 +564,90 @@ def test_executable_plan_changes_nothing_where_the_optimum_already_runs():
         g = build(cfg, small=True).graph
         a, b = fc.fc_plan(g, "bytes"), fc.fc_plan(g, "bytes", executable=True)
         assert runs(g, a) and a.cost == b.cost
+
+
+# ------------------------------------------------------------------ programs too large for a proven optimum
+def pipeline_program(rng, n_ops, n=4096, window=4):
+    """A program of n_ops combinators whose arguments mostly come from the last few arrays of the right
+    type, as in hand-written pipelines (the paper's benchmarks have 51 to 99 combinators, section 5.2)."""
+    g = Graph()
+    pos, flags, ints, flts = [], [], [], []
+    for k in range(2):
+        g.add(f"p{k}", "input", "i32", (n,))
+        pos.append(f"p{k}")
+        g.add(f"x{k}", "input", "f32", (n,))
+        flts.append(f"x{k}")
+
+    def pick(pool):
+        if rng.random() < 0.85:
+            return str(pool[-1 - int(rng.integers(0, min(window, len(pool))))])
+        return str(pool[rng.integers(0, len(pool))])
+
+    k = 0
+    while sum(nd.kind != "input" for nd in g.nodes) < n_ops:
+        nm = f"t{k}"
+        k += 1
+        kind = str(rng.choice(["map1", "map1", "map2", "map2", "gen", "gatherp", "gatherf", "gatherf", "flags", "scani",
+                               "foldf", "scanf"]))
+        if kind == "map1":
+            g.add(nm, "map", "f32", (n,), fn=str(rng.choice(["sq_plus_one", "exp_neg", "sin_x_mul_x"])), args=(pick(flts),))
+            flts.append(nm)
+        elif kind == "map2":
+            g.add(nm, "map", "f32", (n,), fn=str(rng.choice(["mul2", "add2"])), args=(pick(flts), pick(flts)))
+            flts.append(nm)
+        elif kind == "gen":
+            g.add(nm, "generate", "i32", (n,), fn=str(rng.choice(["iota", "iota_rev"])))
+            pos.append(nm)
+        elif kind == "gatherp":
+            g.add(nm, "gather", "i32", (n,), args=(pick(pos), pick(pos)))
+            pos.append(nm)
+        elif kind == "gatherf":
+            g.add(nm, "gather", "f32", (n,), args=(pick(pos), pick(flts)))
+            flts.append(nm)
+        elif kind == "flags":
+            g.add(nm, "map", "i32", (n,), fn="mod_eq", iparam=(3, 0), args=(pick(pos + ints),))
+            flags.append(nm)
+        elif kind == "scani":
+            g.add(nm, "scanl", "i32", (n,), fn="add", args=(pick(flags or pos),))
+            ints.append(nm)
+        elif kind == "scanf":
+            g.add(nm, "scanl", "f32", (n,), fn="add", args=(pick(flts),))
+            flts.append(nm)
+        else:
+            g.add(nm, "fold", "f32", (1,), fn="add", args=(pick(flts),), output=True)
+    return g
+
+
+def test_anytime_plan_on_small_programs_is_the_proven_optimum():
+    for name in ("single_loop", "greedy_top_down_bad", "greedy_bottom_up_bad", "scatter_example", "simple5"):
+        g = PG.ALL[name]()
+        a, b = fc.fc_plan(g, "bytes"), fc.fc_plan(g, "bytes", anytime=True)
+        assert a.proven and b.proven and a.cost == b.cost, name
+    for seed in range(6):
+        g = pipeline_program(np.random.default_rng(seed), 12)
+        best, _ = OC.optimum(g, "bytes") if len(g.nodes) <= 14 else (None, None)
+        p = fc.fc_plan(g, "bytes", anytime=True, no_split=True)
+        assert p.proven
+        if best is not None:
+            assert p.cost == pytest.approx(best)
+
+
+@pytest.mark.parametrize("n_ops", [40, 66, 99])
+def test_anytime_plan_on_large_programs_is_legal_and_much_cheaper_than_no_fusion(n_ops):
+    import time
+    g = pipeline_program(np.random.default_rng(n_ops), n_ops)
+    if n_ops > 64:
+        with pytest.raises(fc.FcError) as e:
+            fc.fc_plan(g, "bytes")
+        assert e.value.name == "FC_E_LIMIT"
+    t = time.time()
+    p = fc.fc_plan(g, "bytes", anytime=True)
+    assert time.time() - t < 10.0                       # two seconds of search, plus the greedy start
+    assert not p.proven
+    again = fc.fc_partition_check(g, list(p.pi), "bytes")                  # legal, and the cost is what it says
+    assert again.cost == pytest.approx(p.cost)
+    alone = fc.fc_partition_check(g, list(range(len(g.nodes))), "bytes")
+    assert p.cost < 0.7 * alone.cost and p.n_clusters < n_ops // 2
+    q = fc.fc_plan(g, "bytes", anytime=True, executable=True)              # the same among the clusterings that run
+    for i in range(q.n_clusters):
+        fc.fc_cluster_kernel(g, q, i)
