@@ -218,6 +218,16 @@ struct Search {
     return derive_and_check(m, pi, c, why) == FC_OK;
   }
 
+  // the extra condition, judged on the clustering as it would be returned
+  bool passes(const std::vector<int> &pi) const {
+    if (!admissible || !*admissible) return true;
+    Clustering c, again;
+    std::string why;
+    if (derive_and_check(m, pi, c, why) != FC_OK) return false;
+    if (split) split_components(m, c); else renumber_levels(m, c);
+    return derive_and_check(m, c.pi, again, why) == FC_OK && (*admissible)(again);
+  }
+
   // A clustering built without backtracking: the combinators in program order, each into the block
   // (one that holds a producer of it or reads one of its arguments, or a new one) that keeps the partial
   // cost lowest among those that leave a legal clustering when the remaining combinators stay alone.
@@ -239,7 +249,7 @@ struct Search {
         block[a] = b;
         const bool fresh = b == n_blocks;
         if (fresh) ++n_blocks;
-        if (legal_with_the_rest_alone(pi)) {
+        if (legal_with_the_rest_alone(pi) && passes(pi)) {
           const double lb = lower_bound();
           if (lb < best_lb) { best_lb = lb; best_b = b; }
         }
@@ -252,15 +262,9 @@ struct Search {
     }
     Clustering c;
     std::string why;
-    if (legal_with_the_rest_alone(pi) && derive_and_check(m, pi, c, why) == FC_OK) {
-      bool ok = true;
-      if (admissible && *admissible) {
-        Clustering shaped = c, again;
-        if (split) split_components(m, shaped); else renumber_levels(m, shaped);
-        ok = derive_and_check(m, shaped.pi, again, why) == FC_OK && (*admissible)(again);
-      }
+    if (legal_with_the_rest_alone(pi) && derive_and_check(m, pi, c, why) == FC_OK && passes(pi)) {
       const double cost = objective(c);
-      if (ok && cost < best) { best = cost * (1.0 + 1e-12) + 1e-9; best_pi = pi; }
+      if (cost < best) { best = cost * (1.0 + 1e-12) + 1e-9; best_pi = pi; }
     }
     for (int a : order) block[a] = -1;
     n_blocks = 0;

@@ -567,9 +567,10 @@ def test_executable_plan_changes_nothing_where_the_optimum_already_runs():
 
 
 # ------------------------------------------------------------------ programs too large for a proven optimum
-def pipeline_program(rng, n_ops, n=4096, window=4):
+def pipeline_program(rng, n_ops, n=4096, window=4, tame=False):
     """A program of n_ops combinators whose arguments mostly come from the last few arrays of the right
-    type, as in hand-written pipelines (the paper's benchmarks have 51 to 99 combinators, section 5.2)."""
+    type, as in hand-written pipelines (the paper's benchmarks have 51 to 99 combinators, section 5.2).
+    tame: only functions that keep values of size one (for programs that are executed)."""
     g = Graph()
     pos, flags, ints, flts = [], [], [], []
     for k in range(2):
@@ -588,12 +589,13 @@ def pipeline_program(rng, n_ops, n=4096, window=4):
         nm = f"t{k}"
         k += 1
         kind = str(rng.choice(["map1", "map1", "map2", "map2", "gen", "gatherp", "gatherf", "gatherf", "flags", "scani",
-                               "foldf", "scanf"]))
+                               "foldf", "foldf" if tame else "scanf"]))
         if kind == "map1":
-            g.add(nm, "map", "f32", (n,), fn=str(rng.choice(["sq_plus_one", "exp_neg", "sin_x_mul_x"])), args=(pick(flts),))
+            fns = ["exp_neg", "sin_x_mul_x"] if tame else ["sq_plus_one", "exp_neg", "sin_x_mul_x"]
+            g.add(nm, "map", "f32", (n,), fn=str(rng.choice(fns)), args=(pick(flts),))
             flts.append(nm)
         elif kind == "map2":
-            g.add(nm, "map", "f32", (n,), fn=str(rng.choice(["mul2", "add2"])), args=(pick(flts), pick(flts)))
+            g.add(nm, "map", "f32", (n,), fn="mul2" if tame else str(rng.choice(["mul2", "add2"])), args=(pick(flts), pick(flts)))
             flts.append(nm)
         elif kind == "gen":
             g.add(nm, "generate", "i32", (n,), fn=str(rng.choice(["iota", "iota_rev"])))

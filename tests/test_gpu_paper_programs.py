@@ -718,6 +718,46 @@ def test_random_programs_planned_and_run(seed):
             P.assert_close(got, ref, 2e-4, what, abs_=2e-5)
 
 
+@pytest.mark.parametrize("n_ops", [30, 45, 70])
+def test_large_programs_planned_anytime_and_run(n_ops):
+    # programs of the size of the paper's benchmarks (section 5.2: 51 to 99 combinators): planned within
+    # the time limit among the clusterings that run, executed fused (a dozen clusters, intermediates in
+    # scratch) and one kernel per combinator; results as in test_random_programs_planned_and_run
+    from test_chooser import pipeline_program
+    n = 4096
+    for seed in range(20):
+        g = pipeline_program(np.random.default_rng(1000 * n_ops + seed), n_ops, n=n, tame=True)
+        rng = np.random.default_rng(seed)
+        ins = {nd.name: (rng.integers(0, n, size=n, dtype=np.int32) if nd.dtype == "i32" else rng.uniform(0.0, 1.0, size=n).astype(F32))
+               for nd in g.nodes if nd.kind == "input"}
+        g = with_outputs(g)
+        with np.errstate(all="ignore"):
+            env = evaluate(g, ins)
+        if all(np.all(np.isfinite(v.astype(np.float64))) and np.all(np.abs(v.astype(np.float64)) < 1e4) for v in env.values()):
+            break                                       # repeated squaring makes some programs overflow, or sin ill-conditioned
+    else:
+        pytest.skip("no program with finite results")
+    part = fc().fc_plan(g, "bytes", executable=True, anytime=True)
+    assert part.n_clusters <= (3 * n_ops) // 4
+    inter = [nd.name for nd in g.nodes if nd.kind != "input"]
+    fused, unfused = device_program(g, ins, part), device_program(g, ins, None, bind=inter)
+    fused.run()
+    unfused.run()
+    assert fused.control_words()[1] == 0 and unfused.control_words()[1] == 0
+    for out in g.outputs():
+        nd = g[out]
+        got, ref = fused.fetch(out), env[out]
+        what = f"{n_ops} combinators, {out}"
+        if nd.dtype == "i32":
+            P.assert_bit_exact(got, ref, what)
+        elif nd.kind == "fold":
+            arg = env[nd.args[0]].astype(np.float64)
+            assert abs(float(got[0]) - float(ref[0])) <= 1e-5 * np.abs(arg).sum() + 1e-30, what
+        else:
+            P.assert_bit_exact(got, unfused.fetch(out), what)
+            P.assert_close(got, ref, 1e-3, what, abs_=1e-4)
+
+
 def test_row_scans():
     # scans of two-dimensional arrays run row by row; row lengths on both sides of the
     # 16-lane / wave / workgroup variants, ragged against their step, with and without a fused producer
