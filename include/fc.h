@@ -150,6 +150,11 @@ typedef enum fc_cost {
 
 /* plan flags */
 #define FC_PLAN_NO_SPLIT 1u  /* keep the raw ILP solution (skip the connected-component split) */
+#define FC_PLAN_EXECUTABLE 2u /* choose among the clusterings fc_run_fused has kernels for: the kernels are a fixed
+                                 set of cluster shapes, and the optimum of the ILP may contain a legal cluster that
+                                 is not among them (fc_run_fused would answer FC_E_UNSUPPORTED).  With this flag the
+                                 result is the cheapest clustering that runs; FC_E_UNSUPPORTED if there is none,
+                                 i.e. some combinator has no kernel even on its own */
 #define FC_PLAN_ANYTIME 4u    /* the chooser is an exact branch and bound: its time grows exponentially with the
                                  number of combinators (fractions of a second up to 20, minutes from 30 on).
                                  With this flag it starts from a clustering built greedily without backtracking,
@@ -158,11 +163,6 @@ typedef enum fc_cost {
                                  finished.  Programs of more than 64 combinators get the greedy clustering.
                                  Without the flag a search that exceeds its (much larger) budget, or a program
                                  of more than 64 combinators, ends in FC_E_LIMIT */
-#define FC_PLAN_EXECUTABLE 2u /* choose among the clusterings fc_run_fused has kernels for: the kernels are a fixed
-                                 set of cluster shapes, and the optimum of the ILP may contain a legal cluster that
-                                 is not among them (fc_run_fused would answer FC_E_UNSUPPORTED).  With this flag the
-                                 result is the cheapest clustering that runs; FC_E_UNSUPPORTED if there is none,
-                                 i.e. some combinator has no kernel even on its own */
 
 typedef struct fc_buffer {
   void   *ptr;    /* DEVICE pointer, 16-byte aligned; NULL = not bound */
@@ -177,8 +177,9 @@ int fc_num_edges(const fc_graph *g, int32_t *n_edges);
 /* Choose the clustering that minimises `cost_fn` subject to the constraints of
  * Fig. "Total ILP formulation" (sections 4.1, 4.2), by exact branch and bound over
  * the edge variables x, then split clusters into connected components (section
- * 4.1, "Performance and correctness").  Fills every array of *out, n_clusters and
- * cost.  Graphs of more than 64 non-input nodes are refused (FC_E_LIMIT). */
+ * 4.1, "Performance and correctness").  Fills every array of *out, n_clusters, cost
+ * and proven.  Graphs of more than 64 non-input nodes, and searches that exceed their
+ * budget, are refused (FC_E_LIMIT) unless FC_PLAN_ANYTIME is set. */
 int fc_plan(const fc_graph *g, int cost_fn, uint32_t flags, fc_partition *out);
 
 /* fc_plan for a linear combination of the cost functions: minimises
