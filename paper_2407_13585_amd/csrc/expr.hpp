@@ -72,10 +72,12 @@ enum : unsigned char {
   kCodeMap,     // a = element function, b = slot, c = number of arguments: replace them by the result
   kCodeEnter,   // pop an index and make it the position
   kCodeLeave,   // back to the position before the matching kCodeEnter
-  kCodeStore,   // a = output array: pop a value into it at the element's own position (c = 1: leave it on the stack)
-  kCodeFold,    // a = output array, b = reducer (kFold...): pop a value into the accumulator
-  kCodeYield    // the value on the stack is the result of this element program (Interp<K, T>)
+  kCodeStore,   // a = output array: pop a value into it at the element's own position
+  kCodeFold,    // a = output array, b = reducer (kFold...), c = accumulator: pop a value into it
+  kCodeYield,   // the value on the stack is the result of this element program (Interp<K, T>)
+  kCodeDup      // push a copy of the top of the stack (an array with several consumers is computed once)
 };
+constexpr int kInterpFolds = 2;       // folds of one interpreted cluster
 enum : unsigned char { kFoldAddF32 = 0, kFoldMaxF32, kFoldMulF32, kFoldAddI32, kFoldMaxI32 };
 struct Code { unsigned char op, a, b, c; };
 

@@ -191,7 +191,9 @@ const std::vector<Instance> &registry() {
 }
 
 static hipError_t launch_interp(const KArgs &a, const LaunchCtx &c) {
-  return launch_k(&interp_kernel<>, grid_for(a.n, kBlock * kVec, resident_grid(&interp_kernel<>)), c.stream, a, c.ctl, c.partials);
+  // a fold of the cluster keeps a partial per workgroup; there may be kInterpFolds of them
+  const unsigned cap = std::min<unsigned>(resident_grid(&interp_kernel<>), kMaxPartials / kInterpFolds);
+  return launch_k(&interp_kernel<>, grid_for(a.n, kBlock * kVec, cap), c.stream, a, c.ctl, c.partials);
 }
 const Instance *interpreter_instance() {
   static const Instance inst = [] {

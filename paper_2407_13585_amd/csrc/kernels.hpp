@@ -217,7 +217,7 @@ __global__ __launch_bounds__(kBlock) void store_fold_kernel(const KArgs a, Contr
 
 // ------------------------------------------------------------------ interpreted elementwise clusters
 // Any cluster of maps, generates and gathers that ends in up to kMaxOut stored arrays
-// or in stored arrays and one fold, for which no kernel was compiled: the element
+// or in stored arrays and up to two folds, for which no kernel was compiled: the element
 // programs are run from KArgs::code, four elements per lane at a time.  The top of the
 // value stack stays in registers, what lies below in LDS (a column per lane: registers
 // cannot be indexed by a run-time number); the positions that gathers suspend are at most
@@ -282,8 +282,8 @@ __device__ __forceinline__ unsigned interp_identity(int op) {
 // lane's column of the value stack.
 // Starts at instruction `pc`; a kCodeYield ends the run with the program's values in `result`.
 template <int V, int Threads>
-__device__ __forceinline__ void interp_run(const KArgs &a, int pc, unsigned first, unsigned (*below)[kVec][Threads], unsigned &acc,
-                                           unsigned (&result)[V]) {
+__device__ __forceinline__ void interp_run(const KArgs &a, int pc, unsigned first, unsigned (*below)[kVec][Threads],
+                                           unsigned (&acc)[kInterpFolds], unsigned (&result)[V]) {
   using Raw = unsigned __attribute__((ext_vector_type(4)));
   int at[V];                                           // the positions element programs read at
   int suspended[kInterpGathers][V];
@@ -365,39 +365,72 @@ __device__ __forceinline__ void interp_run(const KArgs &a, int pc, unsigned firs
         } else {
           p[0] = top[0];
         }
-        if (!c.c) pop();                                // c = 1: the value stays for the fold that follows
-        break;
-      }
-      default:                                          // kCodeFold
-#pragma unroll
-        for (int e = 0; e < V; ++e) acc = interp_fold(c.b, acc, top[e]);
         pop();
         break;
+      }
+      case kCodeDup: push_room(); break;               // the top goes below and stays the top
+      default: {                                        // kCodeFold
+        unsigned v = c.c == 0 ? acc[0] : acc[1];
+#pragma unroll
+        for (int e = 0; e < V; ++e) v = interp_fold(c.b, v, top[e]);
+        if (c.c == 0) acc[0] = v; else acc[1] = v;
+        pop();
+        break;
+      }
     }
+  }
+}
+
+// Workgroup reduction with the reducer picked at run time (the same for the whole grid).
+__device__ __forceinline__ unsigned interp_block_reduce(int op, unsigned v, unsigned *lds) {
+  switch (op) {
+    case kFoldAddF32: return (unsigned)as_bits(block_reduce<AddF32>(from_bits<float>((int)v), reinterpret_cast<float *>(lds)));
+    case kFoldMaxF32: return (unsigned)as_bits(block_reduce<MaxF32>(from_bits<float>((int)v), reinterpret_cast<float *>(lds)));
+    case kFoldMulF32: return (unsigned)as_bits(block_reduce<MulF32>(from_bits<float>((int)v), reinterpret_cast<float *>(lds)));
+    case kFoldAddI32: return (unsigned)block_reduce<AddI32>((int)v, reinterpret_cast<int *>(lds));
+    default: return (unsigned)block_reduce<MaxI32>((int)v, reinterpret_cast<int *>(lds));
   }
 }
 
 template <class Tag = void>            // a template only so that every translation unit may see the definition
 __global__ __launch_bounds__(kBlock) void interp_kernel(const KArgs a, Control *ctl, unsigned long long *partials) {
   __shared__ unsigned below[kInterpDepth][kVec][kBlock];
+  __shared__ unsigned lds[kWavesPerBlock + 1];
   const unsigned n = (unsigned)a.n, n4 = n & ~3u;
-  // the fold of the cluster, if it has one (at most one)
-  int fold_op = -1, fold_out = 0;
+  // the folds of the cluster (at most kInterpFolds), each with an accumulator of its own
+  int n_folds = 0, fold_op[kInterpFolds] = {0, 0}, fold_out[kInterpFolds] = {0, 0};
   for (int pc = 0; pc < kMaxCode && a.code[pc].op != kCodeEnd; ++pc)
-    if (a.code[pc].op == kCodeFold) { fold_op = a.code[pc].b; fold_out = a.code[pc].a; }
-  unsigned acc = fold_op >= 0 ? interp_identity(fold_op) : 0u;
+    if (a.code[pc].op == kCodeFold) {
+      const int k = a.code[pc].c == 0 ? 0 : 1;
+      if (k == 0) { fold_op[0] = a.code[pc].b; fold_out[0] = a.code[pc].a; } else { fold_op[1] = a.code[pc].b; fold_out[1] = a.code[pc].a; }
+      n_folds = n_folds > k + 1 ? n_folds : k + 1;
+    }
+  unsigned acc[kInterpFolds] = {interp_identity(fold_op[0]), interp_identity(fold_op[1])};
   unsigned none4[kVec], none1[1];
   for (unsigned i = (blockIdx.x * kBlock + threadIdx.x) * kVec; i < n4; i += gridDim.x * kBlock * kVec)
     interp_run<kVec, kBlock>(a, 0, i, below, acc, none4);
   if (blockIdx.x == 0 && threadIdx.x < n - n4) interp_run<1, kBlock>(a, 0, n4 + threadIdx.x, below, acc, none1);
-  switch (fold_op) {                                     // the same for the whole grid
-    case kFoldAddF32: fold_finish<AddF32>(from_bits<float>((int)acc), a, fold_out, ctl, partials); break;
-    case kFoldMaxF32: fold_finish<MaxF32>(from_bits<float>((int)acc), a, fold_out, ctl, partials); break;
-    case kFoldMulF32: fold_finish<MulF32>(from_bits<float>((int)acc), a, fold_out, ctl, partials); break;
-    case kFoldAddI32: fold_finish<AddI32>((int)acc, a, fold_out, ctl, partials); break;
-    case kFoldMaxI32: fold_finish<MaxI32>((int)acc, a, fold_out, ctl, partials); break;
-    default: break;
+  if (n_folds == 0) return;                              // the same for the whole grid
+  // as fold_finish, for up to two accumulators under one tag: fold k keeps its partials at
+  // [k * gridDim.x, (k + 1) * gridDim.x); the last workgroup combines them and takes the next tag
+  const unsigned epoch = load_agent(&ctl->epoch);
+  const unsigned tag = tag_of_epoch(epoch);
+  for (int k = 0; k < n_folds; ++k) {
+    const unsigned r = interp_block_reduce(k == 0 ? fold_op[0] : fold_op[1], k == 0 ? acc[0] : acc[1], lds);
+    if (threadIdx.x == 0) store_agent64(&partials[(size_t)k * gridDim.x + blockIdx.x], pack_word(r, tag, 1u));
   }
+  if (blockIdx.x != gridDim.x - 1) return;
+  for (int k = 0; k < n_folds; ++k) {
+    const int op = k == 0 ? fold_op[0] : fold_op[1];
+    unsigned s = interp_identity(op);
+    for (unsigned j = threadIdx.x; j < gridDim.x; j += kBlock) {
+      const unsigned long long w = wait_word(&partials[(size_t)k * gridDim.x + j], tag, ctl);
+      s = interp_fold(op, s, w ? (unsigned)(w >> 32) : interp_identity(op));
+    }
+    s = interp_block_reduce(op, s, lds);
+    if (threadIdx.x == 0) static_cast<unsigned *>(a.out[k == 0 ? fold_out[0] : fold_out[1]])[0] = s;
+  }
+  if (threadIdx.x == 0) store_agent(&ctl->epoch, epoch + 1u);
 }
 
 // Element program K of a cluster as an expression node: evaluated by running its code
@@ -416,13 +449,13 @@ struct Interp {
   static constexpr int kNodes = 0;                     // the code names its parameter slots itself
   static constexpr bool kMirror = false;
   template <int Base, bool Stream = false> static __device__ __forceinline__ T eval(const KArgs &a, int i) {
-    unsigned r[1] = {0u}, none = 0u;
+    unsigned r[1] = {0u}, none[kInterpFolds] = {0u, 0u};
     interp_run<1, Threads>(a, a.root[K], (unsigned)i, interp_stack<Threads>(), none, r);
     return from_bits<T>((int)r[0]);
   }
   // i is a multiple of four (the callers read 128-bit groups)
   template <int Base> static __device__ __forceinline__ Vec4<T> eval4(const KArgs &a, int i) {
-    unsigned r[kVec] = {0u, 0u, 0u, 0u}, none = 0u;
+    unsigned r[kVec] = {0u, 0u, 0u, 0u}, none[kInterpFolds] = {0u, 0u};
     interp_run<kVec, Threads>(a, a.root[K], (unsigned)i, interp_stack<Threads>(), none, r);
     return Vec4<T>{{from_bits<T>((int)r[0]), from_bits<T>((int)r[1]), from_bits<T>((int)r[2]), from_bits<T>((int)r[3])}};
   }

@@ -35,8 +35,8 @@ struct Builder {
       case kCodeMap: on_stack -= c - 1; break;
       case kCodeEnter: --on_stack; if (++gathers > kInterpGathers) code_ok = false; break;
       case kCodeLeave: --gathers; break;
-      case kCodeStore: if (!c) --on_stack; break;              // c = 1: the value stays for a fold
-      default: --on_stack; break;                              // fold, yield
+      case kCodeDup: ++on_stack; break;
+      default: --on_stack; break;                              // store, fold, yield
     }
     if (on_stack > kInterpDepth + 1 || on_stack < 0) code_ok = false;
   }
@@ -279,41 +279,55 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     }
     out.aux = n;
   } else {
-    // stored arrays and at most one fold; compiled instances exist for some of these shapes,
-    // the interpreting kernel takes the others
-    if (folds.size() > 1 || (stores.empty() && folds.empty()) || stores.size() + folds.size() > (size_t)kMaxOut)
+    // stored arrays and folds of the flattened argument; compiled instances exist for some of these
+    // shapes (at most one fold), the interpreting kernel takes the others (at most kInterpFolds folds)
+    if (folds.size() > (size_t)kInterpFolds || (stores.empty() && folds.empty()) || stores.size() + folds.size() > (size_t)kMaxOut)
       return unsupported("cluster with " + std::to_string(stores.size()) + " stored arrays and " + std::to_string(folds.size()) + " folds");
+    // the code computes an array once, however many of the cluster's stores and folds take it:
+    // after its element program come its consumers, a copy of the value for all but the last
+    auto emit_consumers = [&](int array) {
+      std::vector<Code> ops;
+      for (size_t k = 0; k < stores.size(); ++k)
+        if (stores[k] == array) ops.push_back(Code{kCodeStore, (unsigned char)k, 0, 0});
+      for (size_t f = 0; f < folds.size(); ++f)
+        if (m.nodes[folds[f]].arg[0] == array)
+          ops.push_back(Code{kCodeFold, (unsigned char)(stores.size() + f),
+                             (unsigned char)reducer_code(m.nodes[folds[f]].fn, m.nodes[folds[f]].dtype), (unsigned char)f});
+      for (size_t k = 0; k < ops.size(); ++k) {
+        if (k + 1 < ops.size()) b.emit(kCodeDup);
+        b.emit(ops[k].op, ops[k].a, ops[k].b, ops[k].c);
+      }
+    };
+    std::set<int> computed;
     for (size_t k = 0; k < stores.size(); ++k) {
       if (k) sig += "+";
       sig += "store[";
       if (!b.expr(stores[k], sig)) return unsupported("stored array");
       sig += "]";
-      // a stored array that is folded as well is computed once: the value stays on the stack
-      const bool folded = !folds.empty() && m.nodes[folds[0]].arg[0] == stores[k];
-      b.emit(kCodeStore, (int)k, 0, folded ? 1 : 0);
-      if (folded) b.emit(kCodeFold, (int)stores.size(), reducer_code(m.nodes[folds[0]].fn, m.nodes[folds[0]].dtype));
+      emit_consumers(stores[k]);
+      computed.insert(stores[k]);
       if (!set_n(m.size(stores[k]))) return unsupported("iteration sizes differ inside a cluster");
       if (k == 0) shape_from(stores[0]);
       out.out_nodes[k] = stores[k];
     }
-    if (!folds.empty()) {
-      const fc_node &f = m.nodes[folds[0]];
-      if (!stores.empty()) sig += "+";
-      sig += std::string("fold.") + op_name(f.fn, f.dtype) + "[";
-      const bool stored = std::find(stores.begin(), stores.end(), f.arg[0]) != stores.end();
+    for (size_t f = 0; f < folds.size(); ++f) {
+      const fc_node &fd = m.nodes[folds[f]];
+      if (!stores.empty() || f) sig += "+";
+      sig += std::string("fold.") + op_name(fd.fn, fd.dtype) + "[";
       const int code_before = b.n_code, stack_before = b.on_stack;
-      if (!b.expr(f.arg[0], sig)) return unsupported("fold argument");
+      if (!b.expr(fd.arg[0], sig)) return unsupported("fold argument");
       sig += "]";
-      if (stored) {            // its code was emitted with the store (the signature and the slots keep both)
+      if (computed.count(fd.arg[0])) {   // its code stands where the array was first computed (signature and slots keep both)
         for (int k = code_before; k < b.n_code; ++k) b.args.code[k] = Code{kCodeEnd, 0, 0, 0};
         b.n_code = code_before;
         b.on_stack = stack_before;
       } else {
-        b.emit(kCodeFold, (int)stores.size(), reducer_code(f.fn, f.dtype));
+        emit_consumers(fd.arg[0]);
+        computed.insert(fd.arg[0]);
       }
-      if (!set_n(m.size(f.arg[0]))) return unsupported("iteration sizes differ inside a cluster");
-      if (stores.empty()) shape_from(f.arg[0]);
-      out.out_nodes[stores.size()] = folds[0];
+      if (!set_n(m.size(fd.arg[0]))) return unsupported("iteration sizes differ inside a cluster");
+      if (stores.empty() && f == 0) shape_from(fd.arg[0]);
+      out.out_nodes[stores.size() + f] = folds[f];
     }
     interpretable = b.code_ok && b.on_stack == 0 && reducer_ok;
   }

@@ -506,12 +506,13 @@ def unsupported_optimum_graphs():
     g.add("l", "scanl", "f32", (n,), fn="add", args=("y",), output=True)
     g.add("t", "fold", "f32", (1,), fn="add", args=("y",), output=True)
     out["fp32 scan + total"] = g
-    g = Graph()                                  # sum and maximum of one computed array
+    g = Graph()                                  # sum, maximum and product of one computed array
     g.add("x", "input", "f32", (n,))
-    g.add("a", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("x",))
+    g.add("a", "map", "f32", (n,), fn="affine", fparam=(1e-3, 1.0), args=("x",))
     g.add("s", "fold", "f32", (1,), fn="add", args=("a",), output=True)
     g.add("t", "fold", "f32", (1,), fn="max", args=("a",), output=True)
-    out["two folds"] = g
+    g.add("u", "fold", "f32", (1,), fn="mul", args=("a",), output=True)
+    out["three folds"] = g
     return out
 
 

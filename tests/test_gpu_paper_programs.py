@@ -246,6 +246,8 @@ def test_programs_whose_optimum_has_no_kernel_run_with_an_executable_plan():
             elif node.kind == "fold" and node.fn == "add":
                 scale = np.abs(env[node.args[0]].astype(np.float64)).sum()
                 assert abs(float(got[0]) - float(ref[0])) <= 1e-5 * scale, (name, out)
+            elif node.kind == "fold" and node.fn == "mul":
+                assert abs(float(got[0]) - float(ref[0])) <= 1e-4 * abs(float(ref[0])), (name, out)
             elif node.kind == "fold":
                 P.assert_bit_exact(got, ref, f"{name}/{out}")        # a maximum of exactly computed values
             else:
@@ -379,6 +381,29 @@ def test_interpreted_clusters_match_the_compiled_kernels():
                 P.assert_close(got, env[out], 1e-4, f"{trial}/{out}", abs_=1e-5)
         assert fused.control_words()[1] == 0
     assert seen_interpreted >= 15
+    # sum and maximum of one computed array, and of two different ones, in one pass
+    for shared in (True, False):
+        n = 70001
+        g = Graph()
+        g.add("x", "input", "f32", (n,))
+        g.add("a", "map", "f32", (n,), fn="sin_x_mul_x", args=("x",), output=shared)
+        g.add("b", "map", "f32", (n,), fn="exp_neg", args=("x",))
+        g.add("s", "fold", "f32", (1,), fn="add", args=("a",), output=True)
+        g.add("t", "fold", "f32", (1,), fn="max", args=("a" if shared else "b",), output=True)
+        ins = {"x": rng.uniform(0, 1, n).astype(F32)}
+        env = evaluate(g, ins)
+        part = fc().fc_plan(g, "bytes")
+        fused = device_program(g, ins, part)
+        assert part.n_clusters == 1 and "interpreted" in fused.kernels()[0], fused.kernels()
+        unfused = device_program(g, ins, None, bind=["a", "b"])
+        for _ in range(2):                                   # two accumulators, one tag per launch
+            fused.run()
+            unfused.run()
+            P.assert_fold(fused.fetch("s"), env["s"], "two folds: sum")
+            P.assert_bit_exact(fused.fetch("t"), unfused.fetch("t"), "two folds: max")
+            if shared:
+                P.assert_bit_exact(fused.fetch("a"), unfused.fetch("a"), "two folds: stored array")
+        assert fused.control_words()[1] == 0 and fused.control_words()[0] == 2
     # an array that is stored and folded is computed once (the store leaves the value for the fold)
     n = 100003
     g = Graph()
