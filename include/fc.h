@@ -30,7 +30,7 @@ extern "C" {
 #define FC_E_BADGRAPH          -1  /* cycle / arity / dtype / shape mismatch, unknown function  */
 #define FC_E_ILLEGAL_PARTITION -2  /* breaks a rule of section 3.4 or a constraint of Fig. "Total ILP formulation" */
 #define FC_E_UNSUPPORTED       -3  /* legal cluster, but no kernel is built for its combination of consumers (e.g. three
-                                      folds of flattened arrays, a scan that also stores its input), or its element
+                                      folds of flattened arrays, a scan of f32 that feeds a fold in its cluster), or its element
                                       programs exceed the limits (24 nodes, 7 external arrays, gathers nested 3 deep).
                                       Element programs of maps, generates and gathers as such always run: compiled for
                                       the shapes of the paper's programs, interpreted otherwise */

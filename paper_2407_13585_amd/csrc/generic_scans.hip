@@ -20,6 +20,14 @@ void append_generic_scan_instances(std::vector<Instance> &r) {
   r.push_back(scan_<SI0, SF1, kScatter | kCount>());
   r.push_back(scan_<SI0, SI1, kOffs | kScatter | kCount>());
   r.push_back(scan_<SI0, SF1, kOffs | kScatter | kCount>());
+  // the scanned stream stored as well
+  r.push_back(scan_<SI0, SI0, kOffs | kStoreX>());
+  r.push_back(scan_<SI0, SI0, kOffs | kStoreX, true>());
+  r.push_back(scan_<SI0, SI0, kOffs | kCount | kStoreX>());
+  r.push_back(scan_<SI0, SI1, kScatter | kCount | kStoreX>());
+  r.push_back(scan_<SI0, SF1, kScatter | kCount | kStoreX>());
+  r.push_back(scan_<SI0, SI1, kOffs | kScatter | kCount | kStoreX>());
+  r.push_back(scan_<SI0, SF1, kOffs | kScatter | kCount | kStoreX>());
   r.push_back(scan_f32_<SF0>());
   r.push_back(scan_f32_<SF0, true>());
   for (size_t k = first; k < r.size(); ++k) r[k].variant = "element programs interpreted";

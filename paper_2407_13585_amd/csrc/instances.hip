@@ -136,6 +136,9 @@ std::vector<Instance> build_registry() {
   r.push_back(scan_<ModFlag, I0, kScatter | kCount>());
   r.push_back(scan_<ModFlag, I0, kScatter>());
   r.push_back(scan_<ModFlag, I0, kOffs | kCount>());
+  // the predicate is a result as well (stored from the registers it was computed into)
+  r.push_back(scan_<ModFlag, I0, kOffs | kStoreX>());
+  r.push_back(scan_<ModFlag, I0, kScatter | kCount | kStoreX>());
   r.push_back(store_fold_<Stencil5, MaxF32, ExpNeg0>());
   r.push_back(store_fold_<ExpNeg0, MaxF32, ExpNeg0>());       // diagonal: p stored and folded
   r.push_back(store_<Stencil5Mat>());

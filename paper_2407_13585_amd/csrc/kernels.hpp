@@ -982,6 +982,7 @@ constexpr int kScanAcc = kScanItems / kVec;
 constexpr int kScanTile = kScanBlock * kScanItems;    // 12288 elements
 constexpr int kScanGroup = 256;                       // tiles per group
 constexpr int kOffs = 1, kScatter = 2, kCount = 4;
+constexpr int kStoreX = 8;                            // the scanned stream is a result too: stored to out[3] (diagonal fusion)
 // A compaction (the scanned stream is a 0/1 predicate, the kept elements are
 // scattered, the offsets are not stored) parks the kept elements of a tile in
 // LDS (see scan_kernel); the other forms hold the tile in registers across the
@@ -1190,6 +1191,23 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
   P cur;
   const unsigned tile = blockIdx.x;
   cur.load(a, tile, n);
+  if (Mode & kStoreX) {
+    // the scanned stream is stored as well as scanned: straight from the registers it was loaded into
+    int *xs = static_cast<int *>(a.out[3]);
+    const unsigned base = tile * kScanTile + wave * (kWave * kScanItems);
+    const bool whole = (unsigned long long)(tile + 1) * kScanTile <= n && (!Reverse || (n & 3u) == 0u);
+#pragma unroll
+    for (int j = 0; j < kScanAcc; ++j) {
+      const unsigned i = base + j * (kWave * kVec) + lane * kVec;
+      const Vec4<int> v = {{cur.flag(j, 0), cur.flag(j, 1), cur.flag(j, 2), cur.flag(j, 3)}};
+      if (whole) {
+        if (Reverse) store4(xs + (n - 4 - i), Vec4<int>{{v.v[3], v.v[2], v.v[1], v.v[0]}}); else store4(xs + i, v);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) if (i + c < n) xs[Reverse ? n - 1 - (i + c) : i + c] = v.v[c];
+      }
+    }
+  }
   {
 
     const unsigned wbase = tile * kScanTile + wave * (kWave * kScanItems);

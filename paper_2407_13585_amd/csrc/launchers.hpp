@@ -196,6 +196,7 @@ template <class EX, class EV, int Mode, bool Reverse = false> Instance scan_() {
   if (Mode & kOffs) s += "+offs";
   if (Mode & kScatter) s += "+scatter[" + sig_of<EV>() + "]";
   if (Mode & kCount) s += "+count";
+  if (Mode & kStoreX) s += "+input";
   return {s, &launch_scan<EX, EV, Mode, Reverse>};
 }
 template <class EX, bool Reverse = false> Instance scan_f32_() {

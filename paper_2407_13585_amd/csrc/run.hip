@@ -167,16 +167,19 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
     return FC_OK;
   }
   if (!scans.empty()) {
-    if (scans.size() != 1 || scatters.size() > 1 || folds.size() > 1 || !foldsegs.empty() || !stores.empty())
-      return unsupported("scan cluster shape");
     const int sc = scans[0];
     const int x = m.nodes[sc].arg[0];
+    // the scanned array may be a result as well (it is then stored by the same kernel); nothing else is stored
+    const bool stores_input = stores.size() == 1 && stores[0] == x;
+    if (scans.size() != 1 || scatters.size() > 1 || folds.size() > 1 || !foldsegs.empty() || (!stores.empty() && !stores_input))
+      return unsupported("scan cluster shape");
     if (m.nodes[sc].dtype != FC_I32 && (!scatters.empty() || !folds.empty() || c.fused_away[sc]))
       return unsupported("a scan of f32 can only be stored");
     // a two-dimensional array is scanned row by row (one row: the same as one dimension)
     const bool by_rows = m.nodes[sc].rank == 2 && m.nodes[sc].shape[0] != 1;
-    if (by_rows && (!scatters.empty() || !folds.empty() || c.fused_away[sc]))
+    if (by_rows && (!scatters.empty() || !folds.empty() || c.fused_away[sc] || stores_input))
       return unsupported("a row scan can only be stored");
+    if (stores_input && m.nodes[sc].dtype != FC_I32) return unsupported("a scan of f32 cannot store its input");
     sig = by_rows ? (m.nodes[sc].kind == FC_SCANR ? "rowscanr[" : "rowscan[")
                   : (m.nodes[sc].kind == FC_SCANR ? "scanr[" : "scan[");
     any = sig;
@@ -204,6 +207,11 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
       sig += "+count";
       any += "+count";
       out.out_nodes[2] = folds[0];
+    }
+    if (stores_input) {
+      sig += "+input";
+      any += "+input";
+      out.out_nodes[3] = x;
     }
   } else if (!scatters.empty()) {
     if (scatters.size() != 1 || !folds.empty() || !foldsegs.empty() || !stores.empty())

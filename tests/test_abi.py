@@ -115,15 +115,16 @@ def test_scatter_that_reads_its_destination_is_refused():
 
 
 def test_unsupported_cluster_is_reported_not_executed():
-    # a legal clustering with a cluster no kernel is built for: a stored predicate scanned in its own loop
+    # a legal clustering with a cluster no kernel is built for: prefix sums and the total of a computed fp32 array
     g = Graph()
-    g.add("v", "input", "i32", (64,))
-    g.add("flags", "map", "i32", (64,), fn="mod_eq", iparam=(3, 0), args=("v",), output=True)
-    g.add("offs", "scanl", "i32", (64,), fn="add", args=("flags",), output=True)
+    g.add("x", "input", "f32", (64,))
+    g.add("y", "map", "f32", (64,), fn="affine", fparam=(2.0, 1.0), args=("x",))
+    g.add("l", "scanl", "f32", (64,), fn="add", args=("y",), output=True)
+    g.add("t", "fold", "f32", (1,), fn="add", args=("y",), output=True)
     part = fc.fc_plan(g, "bytes")
     assert part.n_clusters == 1
     msg = expect("FC_E_UNSUPPORTED", fc.fc_cluster_kernel, g, part, 0)
-    assert "scan cluster shape" in msg
+    assert "scan of f32" in msg
     fake = (0x10000000, 1 << 30)
     bufs = {n.name: fake for n in g.nodes}
     expect("FC_E_UNSUPPORTED", fc.fc_run_fused, g, part, bufs, fake)

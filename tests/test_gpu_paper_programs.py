@@ -783,6 +783,41 @@ def test_large_programs_planned_anytime_and_run(n_ops):
             P.assert_close(got, ref, 1e-3, what, abs_=1e-4)
 
 
+def test_scan_clusters_that_also_store_what_they_scan():
+    # diagonal fusion into a scan: the predicate is a result as well as scanned (and the compaction's
+    # scatter and count may sit in the same cluster); stored straight from the registers it was loaded into
+    rng = np.random.default_rng(21)
+    for n in (5, 12288, 12288 * 2 + 8, 100003):
+        for shape in ("offsets", "compaction", "computed", "right"):
+            g = Graph()
+            g.add("v", "input", "i32", (n,))
+            if shape == "computed":                          # no compiled instance: the element programs are interpreted
+                g.add("back", "generate", "i32", (n,), fn="iota_rev")
+                g.add("vv", "gather", "i32", (n,), args=("back", "v"))
+                g.add("flags", "map", "i32", (n,), fn="mod_eq", iparam=(4, 1), args=("vv",), output=True)
+            else:
+                g.add("flags", "map", "i32", (n,), fn="mod_eq", iparam=(3, 0), args=("v",), output=True)
+            g.add("offs", "scanr" if shape == "right" else "scanl", "i32", (n,), fn="add", args=("flags",),
+                  output=shape != "compaction")
+            outs = ["flags"] + (["offs"] if shape != "compaction" else [])
+            if shape in ("compaction", "computed"):
+                g.add("dest", "input", "i32", (n,))
+                g.add("out", "scatter", "i32", (n,), fn="overwrite", args=("dest", "offs", "v", "flags"), output=True)
+                g.add("count", "fold", "i32", (1,), fn="add", args=("flags",), output=True)
+                outs += ["out", "count"]
+            ins = {"v": rng.integers(0, 2 ** 31, size=n, dtype=np.int32), "dest": np.zeros(n, np.int32)}
+            ins = {k: v for k, v in ins.items() if k in {nd.name for nd in g.nodes}}
+            env = evaluate(g, ins)
+            part = fc().fc_plan(g, "bytes")
+            prog = device_program(g, ins, part)
+            assert part.n_clusters == 1 and "+input" in prog.kernels()[0], prog.kernels()
+            assert ("interpreted" in prog.kernels()[0]) == (shape in ("computed", "right"))
+            prog.run()
+            for o in outs:
+                P.assert_bit_exact(prog.fetch(o), env[o], f"{shape} n={n} {o}")
+            assert prog.control_words()[1] == 0
+
+
 def test_row_scans():
     # scans of two-dimensional arrays run row by row; row lengths on both sides of the
     # 16-lane / wave / workgroup variants, ragged against their step, with and without a fused producer
