@@ -748,7 +748,8 @@ __global__ __launch_bounds__(kBlock) void foldseg_kernel(const KArgs a) {
     int lo = 0, hi = 0;
     if (r < rows) { lo = off[r]; hi = off[r + 1]; }
     T acc = Op::identity();
-    for (int k = lo + (int)sub; k < hi; k += 16) acc = Op::apply(acc, E::template eval<0>(a, k));
+    // unsigned: the step past a segment that ends at 2^31 - 1 must not wrap
+    for (unsigned k = (unsigned)lo + sub; k < (unsigned)hi; k += 16) acc = Op::apply(acc, E::template eval<0>(a, (int)k));
     acc = row_scan_inclusive<Op>(acc);
     if (sub == 15 && r < rows) y[r] = acc;
   }
@@ -1488,16 +1489,17 @@ __global__ __launch_bounds__(kBlock) void rowscan_kernel(const KArgs a) {
   constexpr int kRows = kBlock / L;                     // rows a workgroup handles at a time
   __shared__ T lds[kWavesPerBlock];
   T *out = static_cast<T *>(a.out[1]);
-  const int rows = a.aux, w = a.w;
-  const int sub = (int)threadIdx.x % L, which = (int)threadIdx.x / L;
-  for (int r0 = (int)blockIdx.x * kRows; r0 < rows; r0 += (int)gridDim.x * kRows) {
-    const int r = r0 + which;
+  // unsigned throughout: the steps past the last row and past a row's end must not wrap
+  const unsigned rows = (unsigned)a.aux, w = (unsigned)a.w;
+  const unsigned sub = threadIdx.x % L, which = threadIdx.x / L;
+  for (unsigned r0 = blockIdx.x * kRows; r0 < rows; r0 += gridDim.x * kRows) {
+    const unsigned r = r0 + which;
     T carry = T();
     // every lane runs the same number of steps, so DPP and the barriers stay converged
-    for (int c0 = 0; c0 < w; c0 += L) {
-      const int c = c0 + sub;
+    for (unsigned c0 = 0; c0 < w; c0 += L) {
+      const unsigned c = c0 + sub;
       const bool live = r < rows && c < w;
-      const int e = r * w + (Reverse ? w - 1 - c : c);
+      const int e = live ? (int)(r * w + (Reverse ? w - 1 - c : c)) : 0;
       const T x = live ? E::template eval<0>(a, e) : T();
       // inclusive prefix over the L lanes, the exclusive one by moving it one lane on (a
       // floating-point sum cannot give its last term back), and the step's total

@@ -363,6 +363,117 @@ def test_fusion_rule_clusters_execute():
     P.assert_bit_exact(prog.fetch("bs"), evaluate(g, ins)["bs"], "simple2")
 
 
+# ------------------------------------------------------------------ the largest arrays the library takes
+@pytest.mark.timeout(900)
+def test_arrays_of_two_to_the_31_minus_one_elements():
+    # The inputs repeat a seeded block, less the very last element (a ragged tail of three): what the oracle
+    # computes on one block then fixes every output of the whole array -- the kept elements repeat, the
+    # offsets of repetition k are the block's plus k times its count, a sum is the block's times the repetitions.
+    B, reps = 1 << 24, 128
+    n = B * reps - 1
+    rng = np.random.default_rng(77)
+
+    block = rng.integers(0, 2 ** 31, size=B, dtype=np.int32)
+    wb = C.compaction(v=block)
+    eb = evaluate(wb.graph, wb.inputs)
+    count_b = int(eb["count"][0])
+    kept_b = eb["out"][:count_b]
+    count = reps * count_b - int(eb["flags"][B - 1])
+    g = Graph()
+    g.add("v", "input", "i32", (n,))
+    g.add("dest", "input", "i32", (n,))
+    g.add("flags", "map", "i32", (n,), fn="mod_eq", iparam=(3, 0), args=("v",))
+    g.add("offs", "scanl", "i32", (n,), fn="add", args=("flags",))
+    g.add("count", "fold", "i32", (1,), fn="add", args=("flags",), output=True)
+    g.add("out", "scatter", "i32", (n,), fn="overwrite", args=("dest", "offs", "v", "flags"), output=True)
+    ins = {"v": np.tile(block, reps)[:n], "dest": np.full(n, -1, np.int32)}
+    want_out = np.full(n, -1, np.int32)
+    want_out[:count] = np.tile(kept_b, reps)[:count]
+    want_offs = (eb["offs"][None, :] + (np.arange(reps, dtype=np.int32) * np.int32(count_b))[:, None]).reshape(-1)[:n]
+    for fused in (True, False):
+        part = fc().fc_plan(g, "bytes") if fused else None
+        prog = device_program(g, ins, part, bind=() if fused else ["flags", "offs"])
+        prog.run()
+        what = "fused" if fused else "unfused"
+        assert int(prog.fetch("count")[0]) == count, what
+        P.assert_bit_exact(prog.fetch("out"), want_out, what + " out")
+        if not fused:
+            P.assert_bit_exact(prog.fetch("offs"), want_offs, "offs")
+        assert prog.control_words()[1] == 0
+        del prog
+    del ins, want_out, want_offs
+
+    # reversed dot product: position i meets position n-1-i, which lies B-2-i (mod B) into the block
+    xb = rng.uniform(-1.0, 1.0, size=B).astype(F32)
+    gb = Graph()
+    gb.add("xs", "input", "f32", (B,))
+    gb.add("idx", "input", "i32", (B,))
+    gb.add("ys", "map", "f32", (B,), fn="affine", fparam=(2.0, 1.0), args=("xs",))
+    gb.add("zs", "gather", "f32", (B,), args=("idx", "ys"))
+    gb.add("ps", "map", "f32", (B,), fn="mul2", args=("ys", "zs"))
+    gb.add("r", "fold", "f32", (1,), fn="add", args=("ps",), output=True)
+    eb = evaluate(gb, {"xs": xb, "idx": ((B - 2 - np.arange(B)) % B).astype(np.int32)})
+    last = float(eb["ys"][B - 1])
+    want = reps * float(eb["r"][0]) - last * last        # the missing position would have met itself
+    w = C.reverse_dot(xs=np.tile(xb, reps)[:n])
+    for dup in (True, False):
+        gg, part = plan(w.graph, dup)
+        prog = device_program(gg, w.inputs, part)
+        prog.run()
+        P.assert_fold(prog.fetch("r"), np.array([want]), "reversed dot product at 2^31-1")
+        assert prog.control_words()[1] == 0
+        del prog
+
+
+@pytest.mark.timeout(900)
+def test_segments_that_end_at_two_to_the_31_minus_one():
+    # 2^27 rows over 2^31 - 1 elements: a block of 2^20 rows with exactly 2^24 elements, repeated; the last
+    # row is one element short.  A row's sum takes its terms in an order that depends on the row alone, so
+    # every repetition must give the bits of the first, and the first is compared with the oracle.
+    Rb, reps, ncols = 1 << 20, 128, 1 << 20
+    rng = np.random.default_rng(78)
+    lengths = rng.poisson(16.0, size=Rb).astype(np.int64)
+    diff = (1 << 24) - int(lengths.sum())
+    rows_to_change = np.flatnonzero(lengths > 1)[:abs(diff)]
+    lengths[rows_to_change] += 1 if diff > 0 else -1
+    lengths[-1] = max(lengths[-1], 2); lengths[0] += (1 << 24) - int(lengths.sum())
+    assert lengths.sum() == 1 << 24 and lengths.min() >= 0
+    def graph_of(nnz, rows):
+        g = Graph()
+        g.add("x", "input", "f32", (ncols,))
+        g.add("col", "input", "i32", (nnz,))
+        g.add("vals", "input", "f32", (nnz,))
+        g.add("off", "input", "i32", (rows + 1,))
+        g.add("g", "gather", "f32", (nnz,), args=("col", "x"))
+        g.add("p", "map", "f32", (nnz,), fn="mul2", args=("vals", "g"))
+        g.add("y", "foldseg", "f32", (rows,), fn="add", args=("p", "off"), output=True)
+        return g
+
+    wb = C.spmv(lengths=lengths, ncols=ncols, seed=78)
+    eb = evaluate(wb.graph, wb.inputs)
+    # the block with its last row one element short
+    off_s = wb.inputs["off"].copy(); off_s[-1] -= 1
+    es = evaluate(graph_of((1 << 24) - 1, Rb), {"x": wb.inputs["x"], "col": wb.inputs["col"][:-1],
+                                               "vals": wb.inputs["vals"][:-1], "off": off_s})
+
+    nnz, rows = (1 << 31) - 1, Rb * reps
+    off = (wb.inputs["off"][None, :-1].astype(np.int64) + (np.arange(reps, dtype=np.int64) << 24)[:, None]).reshape(-1)
+    off = np.append(off, nnz).astype(np.int32)
+    ins = {"x": wb.inputs["x"], "col": np.tile(wb.inputs["col"], reps)[:nnz], "vals": np.tile(wb.inputs["vals"], reps)[:nnz],
+           "off": off}
+    g = graph_of(nnz, rows)
+    for fused in (True, False):
+        prog = device_program(g, ins, fc().fc_plan(g, "bytes") if fused else None)
+        prog.run()
+        y = prog.fetch("y").reshape(reps, Rb)
+        what = "fused" if fused else "unfused"
+        P.assert_segmented(y[0], eb["y"], eb["p"], wb.inputs["off"], what + " first repetition")
+        assert np.array_equal(y[1:-1].view(np.int32), np.broadcast_to(y[0].view(np.int32), (reps - 2, Rb))), what
+        assert np.array_equal(y[-1, :-1].view(np.int32), y[0, :-1].view(np.int32)), what
+        P.assert_segmented(y[-1, -1:], es["y"][-1:], es["p"][off_s[-2]:], np.array([0, off_s[-1] - off_s[-2]]), what + " last row")
+        del prog
+
+
 # ------------------------------------------------------------------ full sizes (the launch shapes the bench times)
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
 def test_full_size_configs_match_oracle(cfg):
