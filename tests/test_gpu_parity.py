@@ -288,6 +288,32 @@ def test_repeated_runs_share_scratch():
         assert words[0] == 4            # one tagged launch per run
 
 
+def test_two_streams_each_with_its_own_scratch():
+    # launches that overlap in time must not share a scratch buffer; with one each they may: two streams
+    # (default priority) take turns over four programs whose kernels wait for other workgroups
+    import torch
+    rng = np.random.default_rng(79)
+    big = 2200003
+    items = [(4, C.compaction(n=3000001, seed=9)),
+             (3, C.spmv(lengths=rng.poisson(8.0, size=20000), seed=6, ncols=1200000)),
+             (2, C.perm_gather_fold(xs=rng.standard_normal(size=big).astype(F32), idx=rng.permutation(big).astype(np.int32))),
+             (5, build(5, small=True))]
+    progs = []
+    for cfg, w in items:
+        g, part = plan(w.graph, True)
+        progs.append(device_program(g, w.inputs, part))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(6):
+        for k, p in enumerate(progs):
+            p.run(streams[(k + rep) % 2])
+    torch.cuda.synchronize()
+    for (cfg, w), p in zip(items, progs):
+        compare(cfg, w, evaluate(w.graph, w.inputs), p, w.graph.outputs(), "two streams")
+        words = p.control_words()
+        assert words[1] == 0 and words[0] >= 6
+
+
 def test_step_replays_from_a_hip_graph():
     # fc_run_fused only enqueues kernels (no allocation, no host synchronisation, no memset), so a
     # caller can capture a step into a HIP graph.  Captured here: the five pipelines at small sizes
