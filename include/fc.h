@@ -157,10 +157,12 @@ typedef enum fc_cost {
                                  i.e. some combinator has no kernel even on its own */
 #define FC_PLAN_ANYTIME 4u    /* the chooser is an exact branch and bound: its time grows exponentially with the
                                  number of combinators (fractions of a second up to 20, minutes from 30 on).
-                                 With this flag it starts from a clustering built greedily without backtracking,
-                                 searches for two seconds at most and returns the best clustering found, which
-                                 is legal at any moment; fc_partition.proven says whether the search had
-                                 finished.  Programs of more than 64 combinators get the greedy clustering.
+                                 With this flag it starts from a clustering built greedily and improved by
+                                 moving combinators between neighbouring clusters, searches for 1.2 seconds at
+                                 most, spends what is left of two seconds on further (random) moves if the search
+                                 had not finished, and returns the best clustering found, which is legal at any
+                                 moment; fc_partition.proven says whether the search had finished.  Programs of
+                                 more than 64 combinators get the greedy clustering improved by two seconds of moves.
                                  Without the flag a search that exceeds its (much larger) budget, or a program
                                  of more than 64 combinators, ends in FC_E_LIMIT */
 

@@ -1210,7 +1210,6 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
     }
   }
   {
-
     const unsigned wbase = tile * kScanTile + wave * (kWave * kScanItems);
     int s[kScanAcc];
 #pragma unroll

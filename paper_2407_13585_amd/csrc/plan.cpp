@@ -37,6 +37,10 @@ struct Search {
   std::vector<int> forced;         // per node: representative of the set it must share a cluster with
   bool stop_at_first = false;      // feasibility question only
   double seconds = 0;                       // wall-clock limit of the search, 0 = none
+  double share = 1.0;                       // the part of it the running phase may use up to
+  bool timed_out = false;                   // the search ended on the clock (not on the node limit)
+  std::vector<int> moved_block;             // the clustering the local improvement has reached, to go on from
+  int moved_n_blocks = 0;
   std::chrono::steady_clock::time_point started = std::chrono::steady_clock::now();
   const Admissible *admissible = nullptr;   // extra condition on complete clusterings
   bool split = true;                        // it is judged after the connected-component split
@@ -260,22 +264,147 @@ struct Search {
       block[a] = best_b;
       if (best_b == n_blocks) ++n_blocks;
     }
-    Clustering c;
-    std::string why;
-    if (legal_with_the_rest_alone(pi) && derive_and_check(m, pi, c, why) == FC_OK && passes(pi)) {
-      const double cost = objective(c);
-      if (cost < best) { best = cost * (1.0 + 1e-12) + 1e-9; best_pi = pi; }
-    }
+    improve_by_moves(false);
     for (int a : order) block[a] = -1;
     n_blocks = 0;
+  }
+
+  // goes on from where the local improvement stopped, with random moves, until the phase's time is up
+  void keep_improving() {
+    if (moved_block.empty() || !(seconds > 0)) return;
+    block = moved_block;
+    n_blocks = moved_n_blocks;
+    improve_by_moves(true);
+    for (int a : order) block[a] = -1;
+    n_blocks = 0;
+  }
+
+  // Cost of the complete clustering held in `block` (1e300 if it is not legal or fails the extra condition).
+  double cost_of_blocks(std::vector<int> &pi) const {
+    Clustering c;
+    std::string why;
+    if (!legal_with_the_rest_alone(pi) || derive_and_check(m, pi, c, why) != FC_OK || !passes(pi)) return 1e300;
+    return objective(c);
+  }
+
+  // Local improvement of the greedy clustering.  A move: a combinator goes to a neighbouring block (one
+  // that holds a producer or a consumer of it, or another reader of one of its arguments) or to a block
+  // of its own, or its whole block joins such a block.  `descend` takes the best improving move of each
+  // combinator in turn until none helps: the construction above never revisits a decision, this repairs
+  // the early ones that later combinators made wrong.  With a time limit (an anytime search) it goes on
+  // from there for `share` of the limit: a few random legal moves, a descent, kept unless it ends higher.
+  // The result is the incumbent of the exact search and what an anytime search returns for a program it
+  // cannot finish.  The random numbers come from a fixed seed.
+  std::vector<int> neighbouring_blocks(int a) const {
+    std::vector<int> cand;
+    auto add = [&](int b) { if (b >= 0 && b != block[a] && std::find(cand.begin(), cand.end(), b) == cand.end()) cand.push_back(b); };
+    for (int e : m.in_edges[a]) {
+      add(block[m.edges[e].a]);
+      for (int e2 : m.out_edges[m.edges[e].a]) add(block[m.edges[e2].b]);
+    }
+    for (int e : m.out_edges[a]) add(block[m.edges[e].b]);
+    cand.push_back(n_blocks);                                   // a block of its own
+    return cand;
+  }
+
+  bool past(double part) const {
+    return seconds > 0 && std::chrono::duration<double>(std::chrono::steady_clock::now() - started).count() > seconds * part;
+  }
+
+  double descend(double cur, std::vector<int> &pi_of_cur) {
+    std::vector<int> pi;
+    for (int round = 0, moved = 1; moved && round < 16 && !past(share); ++round) {
+      moved = 0;
+      for (int a : order) {
+        if (past(share)) break;
+        const int home = block[a];
+        int best_b = home, best_kind = 0;
+        double best_cost = cur;
+        std::vector<int> best_pi_here;
+        for (int b : neighbouring_blocks(a)) {
+          const bool fresh = b == n_blocks;
+          block[a] = b;                                     // (1) the combinator alone moves
+          if (fresh) ++n_blocks;
+          const double c1 = cost_of_blocks(pi);
+          if (c1 < best_cost * (1.0 - 1e-12)) { best_cost = c1; best_b = b; best_kind = 1; best_pi_here = pi; }
+          if (fresh) --n_blocks;
+          block[a] = home;
+          if (fresh) continue;
+          std::vector<int> members;                         // (2) its whole block joins block b
+          for (int x : order) if (block[x] == home) members.push_back(x);
+          if (members.size() > 1) {
+            for (int x : members) block[x] = b;
+            const double c2 = cost_of_blocks(pi);
+            if (c2 < best_cost * (1.0 - 1e-12)) { best_cost = c2; best_b = b; best_kind = 2; best_pi_here = pi; }
+            for (int x : members) block[x] = home;
+          }
+        }
+        if (best_kind == 1) {
+          block[a] = best_b;
+          if (best_b == n_blocks) ++n_blocks;
+        } else if (best_kind == 2) {
+          for (int x : order) if (block[x] == home) block[x] = best_b;
+        }
+        if (best_kind) { cur = best_cost; pi_of_cur = best_pi_here; moved = 1; }
+      }
+    }
+    return cur;
+  }
+
+  void renumber_blocks() {
+    std::vector<int> id(n_blocks, -1);
+    int next = 0;
+    for (int a : order) {
+      if (id[block[a]] < 0) id[block[a]] = next++;
+      block[a] = id[block[a]];
+    }
+    n_blocks = next;
+  }
+
+  void improve_by_moves(bool with_random_moves) {
+    std::vector<int> pi, pi_of_cur;
+    double cur = cost_of_blocks(pi);
+    if (cur >= 1e300 || order.empty()) return;
+    pi_of_cur = pi;
+    cur = descend(cur, pi_of_cur);
+    auto record = [&]() {
+      if (cur < best) { best = cur * (1.0 + 1e-12) + 1e-9; best_pi = pi_of_cur; }
+      moved_block = block;
+      moved_n_blocks = n_blocks;
+    };
+    record();
+    if (!with_random_moves) return;
+    unsigned long long state = 0x9E3779B97F4A7C15ull;
+    auto draw = [&](size_t below) {
+      state = state * 6364136223846793005ull + 1442695040888963407ull;
+      return (size_t)((state >> 33) % below);
+    };
+    while (!past(share)) {
+      renumber_blocks();
+      const std::vector<int> kept_block = block, kept_pi = pi_of_cur;
+      const int kept_n = n_blocks;
+      const double kept = cur;
+      for (int k = 0; k < 3; ++k) {
+        const int a = order[draw(order.size())];
+        const std::vector<int> cand = neighbouring_blocks(a);
+        const int b = cand[draw(cand.size())], home = block[a];
+        block[a] = b;
+        if (b == n_blocks) ++n_blocks;
+        const double c = cost_of_blocks(pi);
+        if (c >= 1e300) block[a] = home;          // not a legal clustering: taken back (a fresh block number stays unused)
+        else { cur = c; pi_of_cur = pi; }
+      }
+      cur = descend(cur, pi_of_cur);
+      if (cur <= kept * (1.0 + 1e-12)) record();
+      else { block = kept_block; n_blocks = kept_n; cur = kept; pi_of_cur = kept_pi; }
+    }
   }
 
   void go(size_t k) {
     if (aborted) return;
     if (++visited > limit) { aborted = true; return; }
-    if (seconds > 0 && (visited & 1023) == 0 &&
-        std::chrono::duration<double>(std::chrono::steady_clock::now() - started).count() > seconds) {
-      aborted = true;
+    if (seconds > 0 && (visited & 1023) == 0 && past(share)) {
+      aborted = timed_out = true;
       return;
     }
     if (k == order.size()) { leaf(); return; }
@@ -392,8 +521,22 @@ int choose_clustering_weighted(const Model &m, const double *weights, bool split
     }
   }
   s.greedy_incumbent();
-  if (non_input > 64) s.aborted = true;          // the search keeps its blocks in 64-bit sets: the greedy clustering stands
-  else s.go(0);
+  if (non_input > 64) {
+    // the search keeps its blocks in 64-bit sets: the greedy clustering, improved by moves for the time allowed, stands
+    s.keep_improving();
+    s.aborted = true;
+  } else if (budget->seconds > 0) {
+    // the search first, for 0.6 of the time (programs it can finish end here, proven); if that was not enough,
+    // random moves and descents from the greedy clustering for the rest
+    s.share = 0.6;
+    s.go(0);
+    if (s.timed_out) {
+      s.share = 1.0;
+      s.keep_improving();
+    }
+  } else {
+    s.go(0);
+  }
   if (s.aborted) {
     if (!budget->anytime || s.best_pi.empty()) { err = "search limit reached before optimality was proven"; return FC_E_LIMIT; }
     budget->proven = false;          // the best clustering found so far: legal, maybe not the cheapest
