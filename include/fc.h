@@ -222,9 +222,10 @@ int fc_duplicate(const fc_graph *g, fc_node *out_nodes, int32_t capacity, int32_
  * intermediates, and the workspace of the cluster kernel that asks for the most. */
 int fc_scratch_bytes(const fc_graph *g, const fc_partition *p, size_t *bytes);
 
-/* Execute the program cluster by cluster, one kernel launch per cluster, on
- * `hip_stream` (a hipStream_t; NULL = the default stream).  The call only
- * enqueues work and returns; results are valid after the stream is synchronised.
+/* Execute the program cluster by cluster, one kernel launch per cluster (two for a
+ * fold over a gather from a table larger than the L2 of an XCD), on `hip_stream`
+ * (a hipStream_t; NULL = the default stream).  The call only enqueues work and
+ * returns; results are valid after the stream is synchronised.
  *
  * bufs[i] is the DEVICE buffer of node i.  Inputs and manifest arrays (m = 0) of
  * the clustering must be bound, fused-away arrays are ignored.  Arrays made
