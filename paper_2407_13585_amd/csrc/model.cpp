@@ -250,7 +250,7 @@ int derive_and_check(const Model &m, const std::vector<int> &pi, Clustering &c, 
   return FC_OK;
 }
 
-bool orders_completable(const Model &m, const std::vector<int> &block) {
+bool orders_completable(const Model &m, const std::vector<int> &block, std::vector<int> *resolved) {
   const int n = m.n;
   UnionFind uf(n);
   for (int a = 0; a < n; ++a) {
@@ -279,6 +279,10 @@ bool orders_completable(const Model &m, const std::vector<int> &block) {
       manifest = manifest || (block[b] >= 0 && block[b] != block[a]);
     }
     if (manifest) return false;
+  }
+  if (resolved) {
+    resolved->assign(n, -1);
+    for (int a = 0; a < n; ++a) if (block[a] >= 0) (*resolved)[a] = uf.konst[uf.find(a)];
   }
   return true;
 }

@@ -62,7 +62,9 @@ int derive_and_check(const Model &m, const std::vector<int> &pi, Clustering &c, 
 // equalities over edges inside one cluster only grow as nodes are added, so a conflict among
 // the placed nodes stays one; likewise an array that is certainly manifest (a result, or read
 // from another cluster already) cannot take the order of a gather.
-bool orders_completable(const Model &m, const std::vector<int> &block);
+// `resolved`, if given, receives per placed node the constant its traversal order is tied to so far
+// (0, 1 or a gather's label), -1 where nothing ties it yet.
+bool orders_completable(const Model &m, const std::vector<int> &block, std::vector<int> *resolved = nullptr);
 
 double evaluate_cost(const Model &m, const Clustering &c, int cost_fn);
 

@@ -54,15 +54,20 @@ struct Search {
     }
     forced.resize(m.n);
     for (int a = 0; a < m.n; ++a) forced[a] = a;
-    // What an array costs whatever the clustering: a write if it cannot be fused away (a result, no
-    // consumer, an infusible edge, or consumers that ask for different fixed traversal orders: a scan
-    // from the left and one from the right, the sources of two gathers), and then at least one read
-    // unless it is manifest only for being a result; an input is read once per fixed order asked of it.
+    // What an array costs whatever the clustering: a write if it cannot be fused away, and then at least
+    // one read unless it is manifest only for being a result; an input is read once per traversal order
+    // asked of it.  An array cannot be fused away if it is a result or has no consumer, if an edge out
+    // of it is infusible, or if its consumers cannot all read it in the one order it would be produced
+    // in: two different fixed orders (a scan from the left and one from the right, the sources of two
+    // gathers), a fixed order other than the scan's own for a scan result, or the source of a gather
+    // next to a consumer that reads in its own order and is itself manifest for sure (a manifest array is
+    // in order 0 or 1, a gather's source is read in the gather's label).  Consumers come later in
+    // program order, so one pass from the back knows each consumer's status.
     sure_write.assign(m.n, 0);
     sure_reads.assign(m.n, 0);
-    for (int a = 0; a < m.n; ++a) {
+    for (int a = m.n - 1; a >= 0; --a) {
       std::vector<int> fixed;                        // distinct constant orders among the consumers
-      bool infusible = false;
+      bool infusible = false, low = false;           // low: some consumer reads it in order 0 or 1, whichever
       for (int e : m.out_edges[a]) {
         const Edge &ed = m.edges[e];
         infusible = infusible || !ed.fusible;
@@ -71,21 +76,28 @@ struct Search {
           case InOrder::Label: k = m.label[ed.b]; break;
           case InOrder::Zero: k = 0; break;
           case InOrder::One: k = 1; break;
+          case InOrder::SameAsOut: low = low || sure_write[ed.b]; break;
           default: break;
         }
         if (k >= 0 && std::find(fixed.begin(), fixed.end(), k) == fixed.end()) fixed.push_back(k);
       }
+      int labels = 0, zero_one = 0;
+      for (int k : fixed) if (k >= 2) ++labels; else ++zero_one;
       if (m.is_input(a)) {
-        sure_reads[a] = m.out_edges[a].empty() ? 0 : std::max<int>(1, (int)fixed.size());
+        sure_reads[a] = m.out_edges[a].empty() ? 0 : std::max(1, labels + std::max(zero_one, low ? 1 : 0));
       } else {
+        const int made = m.nodes[a].kind == FC_SCANL ? 0 : m.nodes[a].kind == FC_SCANR ? 1 : -1;
+        bool clash = fixed.size() > 1 || (low && labels > 0);
+        if (made >= 0) for (int k : fixed) clash = clash || k != made;
         const bool result = m.out_edges[a].empty() || (m.nodes[a].flags & FC_NODE_OUTPUT);
-        const bool split = infusible || fixed.size() > 1;
+        const bool split = infusible || clash;
         sure_write[a] = result || split;
         sure_reads[a] = split ? 1 : 0;
       }
     }
   }
   std::vector<char> sure_write;
+  std::vector<int> resolved;       // per placed node: the constant its order is tied to, -1 if none (empty: not computed)
   std::vector<int> sure_reads;
 
   int forced_root(int a) const { while (forced[a] != a) a = forced[a]; return a; }
@@ -109,6 +121,7 @@ struct Search {
 
   // cost of the decisions taken so far; never above the cost of any completion (every
   // cost function only grows as nodes are placed, and the weights are not negative)
+  static constexpr int kMaxTracked = 48;      // reader blocks and known orders tracked per array; more only loosen the bound
   double lower_bound() const {
     double reads = 0, writes = 0, unfused = 0, bytes = 0;
     for (int a = 0; a < m.n; ++a) {
@@ -119,20 +132,41 @@ struct Search {
         bytes += (double)m.bytes(a) * (sure_write[a] + sure_reads[a]);
         continue;
       }
-      uint64_t readers = 0;
-      std::vector<int> many;                           // the reader blocks when there are more than 64 blocks
+      // A block reads the array once per traversal order it asks for.  Orders known by now: the fixed ones
+      // (a gather's source, a scan's argument) and those of consumers whose own order is tied to a constant;
+      // a consumer whose order nothing ties yet may still come to share a read with any of them.
+      int n_readers = 0, reader[kMaxTracked], n_known = 0, known_block[kMaxTracked], known_order[kMaxTracked];
       bool manifest = !m.is_input(a) && (m.out_edges[a].empty() || (m.nodes[a].flags & FC_NODE_OUTPUT));
+      int untracked = 0;
       for (int e : m.out_edges[a]) {
-        int b = m.edges[e].b;
-        if (block[b] < 0) continue;
-        if (block[b] != block[a]) {
-          if (block[b] < 64) readers |= 1ull << block[b];
-          else if (std::find(many.begin(), many.end(), block[b]) == many.end()) many.push_back(block[b]);
-          if (!m.is_input(a)) manifest = true;
-          if (m.edges[e].fusible) unfused += 1;
+        const Edge &ed = m.edges[e];
+        const int rb = block[ed.b];
+        if (rb < 0 || rb == block[a]) continue;
+        if (!m.is_input(a)) manifest = true;
+        if (ed.fusible) unfused += 1;
+        bool seen = false;
+        for (int i = 0; i < n_readers; ++i) seen = seen || reader[i] == rb;
+        if (!seen) { if (n_readers < kMaxTracked) reader[n_readers++] = rb; else ++untracked; }
+        int k = -1;
+        switch (m.in_order(ed.b, ed.slot)) {
+          case InOrder::Label: k = m.label[ed.b]; break;
+          case InOrder::Zero: k = 0; break;
+          case InOrder::One: k = 1; break;
+          case InOrder::SameAsOut: k = resolved.empty() ? -1 : resolved[ed.b]; break;
+          default: break;
         }
+        if (k < 0 || n_known == kMaxTracked) continue;
+        bool have = false;
+        for (int i = 0; i < n_known; ++i) have = have || (known_block[i] == rb && known_order[i] == k);
+        if (!have) { known_block[n_known] = rb; known_order[n_known] = k; ++n_known; }
       }
-      int r = std::max(__builtin_popcountll(readers) + (int)many.size(), sure_reads[a]);
+      int r = untracked;
+      for (int i = 0; i < n_readers; ++i) {
+        int distinct = 0;
+        for (int j = 0; j < n_known; ++j) distinct += known_block[j] == reader[i];
+        r += std::max(1, distinct);
+      }
+      r = std::max(r, sure_reads[a]);
       manifest = manifest || sure_write[a];
       reads += r;
       if (manifest) writes += 1;
@@ -400,6 +434,46 @@ struct Search {
     }
   }
 
+  // the blocks that hold a combinator linked to `a` by a chain of edges and common arguments whose inner
+  // members are all still unplaced
+  uint64_t blocks_in_reach(int a) const {
+    std::vector<char> seen(m.n, 0);
+    std::vector<int> stack(1, a);
+    uint64_t blocks = 0;
+    seen[a] = 1;
+    auto touch = [&](int v) {
+      if (seen[v]) return;
+      seen[v] = 1;
+      if (m.is_input(v)) return;
+      if (block[v] >= 0) blocks |= 1ull << block[v]; else stack.push_back(v);
+    };
+    // the order an edge reads its array in, if it is fixed (-1: the consumer's own order, open)
+    auto fixed_order = [&](const Edge &ed) {
+      switch (m.in_order(ed.b, ed.slot)) {
+        case InOrder::Label: return m.label[ed.b];
+        case InOrder::Zero: return 0;
+        case InOrder::One: return 1;
+        default: return -1;
+      }
+    };
+    while (!stack.empty()) {
+      const int u = stack.back();
+      stack.pop_back();
+      for (int e : m.out_edges[u]) if (m.edges[e].fusible) touch(m.edges[e].b);     // an edge that can be fused
+      for (int e : m.in_edges[u]) {
+        const Edge &mine = m.edges[e];
+        if (mine.fusible) touch(mine.a);
+        // the other readers of this argument, unless both orders are fixed and differ (no read to share)
+        const int k = fixed_order(mine);
+        for (int e2 : m.out_edges[mine.a]) {
+          const int k2 = fixed_order(m.edges[e2]);
+          if (k < 0 || k2 < 0 || k == k2) touch(m.edges[e2].b);
+        }
+      }
+    }
+    return blocks;
+  }
+
   void go(size_t k) {
     if (aborted) return;
     if (++visited > limit) { aborted = true; return; }
@@ -415,7 +489,18 @@ struct Search {
       int b = block[m.edges[e].a];
       if (b >= 0 && std::find(cand.begin(), cand.end(), b) == cand.end()) cand.push_back(b);
     }
-    for (int b = 0; b < n_blocks; ++b) if (std::find(cand.begin(), cand.end(), b) == cand.end()) cand.push_back(b);
+    // A cluster whose members fall into groups that share nothing (no edge between them, no array
+    // read by both) costs what the groups cost as clusters of their own, and those are legal when it is
+    // (section 4.1, the split into connected components).  So `a` need only try the blocks it can still
+    // come to share something with: those reached from it over edges and common arguments through
+    // combinators that are not placed yet.  (The number of clusters is the one cost a block of strangers lowers.)
+    if (weight[FC_COST_CLUSTERS] == 0) {
+      const uint64_t useful = blocks_in_reach(a);
+      for (int b = 0; b < n_blocks; ++b)
+        if ((useful >> b & 1) && std::find(cand.begin(), cand.end(), b) == cand.end()) cand.push_back(b);
+    } else {
+      for (int b = 0; b < n_blocks; ++b) if (std::find(cand.begin(), cand.end(), b) == cand.end()) cand.push_back(b);
+    }
     if (n_blocks < 64) cand.push_back(n_blocks);
     // a node tied to already placed nodes has no choice
     int must = -1;
@@ -464,7 +549,8 @@ struct Search {
       if (ok) {
         block[a] = b;
         if (fresh) ++n_blocks;
-        if (lower_bound() < best && orders_completable(m, block)) go(k + 1);
+        if (orders_completable(m, block, &resolved) && lower_bound() < best) go(k + 1);
+        resolved.clear();
         if (fresh) --n_blocks;
         block[a] = -1;
       }
