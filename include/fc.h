@@ -156,7 +156,7 @@ typedef enum fc_cost {
                                  result is the cheapest clustering that runs; FC_E_UNSUPPORTED if there is none,
                                  i.e. some combinator has no kernel even on its own */
 #define FC_PLAN_ANYTIME 4u    /* the chooser is an exact branch and bound: its time grows exponentially with the
-                                 number of combinators (fractions of a second up to 20, minutes from 30 on).
+                                 number of combinators (seconds up to 24, half a minute at 30, much longer from 36 on).
                                  With this flag it starts from a clustering built greedily and improved by
                                  moving combinators between neighbouring clusters, searches for 1.2 seconds at
                                  most, spends what is left of two seconds on further (random) moves if the search
