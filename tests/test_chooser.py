@@ -635,11 +635,11 @@ def test_anytime_plan_on_small_programs_is_the_proven_optimum():
             assert p.cost == pytest.approx(best)
 
 
-@pytest.mark.parametrize("seed", [1, 4])
+@pytest.mark.parametrize("seed", [1, 2])
 def test_anytime_plan_comes_close_to_an_optimum_the_search_needs_longer_for(seed):
-    # programs of 20 combinators whose exact search takes longer than the two seconds of an anytime one:
+    # programs of 30 combinators whose exact search takes longer than the two seconds of an anytime one:
     # the greedy clustering improved by moves (and what the search adds) lands on the optimum or next to it
-    g = pipeline_program(np.random.default_rng(seed), 20)
+    g = pipeline_program(np.random.default_rng(seed), 30)
     exact = fc.fc_plan(g, "bytes")
     quick = fc.fc_plan(g, "bytes", anytime=True)
     assert exact.proven and exact.cost <= quick.cost <= 1.05 * exact.cost
