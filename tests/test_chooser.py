@@ -621,6 +621,29 @@ def pipeline_program(rng, n_ops, n=4096, window=4, tame=False):
     return g
 
 
+def test_a_result_joins_the_block_it_will_share_a_read_with_later():
+    # The search tries only blocks a combinator can still come to share something with.  Here `a`, a result
+    # nobody consumes, shares nothing with `p` when it is placed; `c`, placed later, reads p (fused) and the
+    # input a reads, so the cheapest clustering has all three in one loop and x0 read once.  Both program
+    # orders of a and p, every cost function, against the enumeration of all clusterings.
+    n = 4096
+    for a_first in (True, False):
+        g = Graph()
+        g.add("x0", "input", "f32", (n,))
+        g.add("x1", "input", "f32", (n,))
+        for name in (("a", "p") if a_first else ("p", "a")):
+            if name == "a":
+                g.add("a", "map", "f32", (n,), fn="sq_plus_one", args=("x0",), output=True)
+            else:
+                g.add("p", "map", "f32", (n,), fn="exp_neg", args=("x1",))
+        g.add("c", "map", "f32", (n,), fn="mul2", args=("p", "x0"), output=True)
+        for cost in COSTS:
+            best, _ = OC.optimum(g, cost)
+            plan = fc.fc_plan(g, cost, no_split=True)
+            assert plan.cost == pytest.approx(best), (a_first, cost)
+        assert fc.fc_plan(g, "bytes").n_clusters == 1
+
+
 def test_anytime_plan_on_small_programs_is_the_proven_optimum():
     for name in ("single_loop", "greedy_top_down_bad", "greedy_bottom_up_bad", "scatter_example", "simple5"):
         g = PG.ALL[name]()
