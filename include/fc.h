@@ -53,7 +53,8 @@ typedef enum fc_kind {
   FC_SCANL    = 6,  /* exclusive prefix combine (+), identity seeded; traversal order 0; a rank-2 array is scanned row
                        by row.  i32: exact.  f32: summed in a fixed tree order (the same bits on every launch), so
                        a prefix differs from the sequentially rounded sum by rounding only; an f32 scan can be
-                       stored but not fused with a scatter or a fold (FC_E_UNSUPPORTED) */
+                       stored (also together with the array it scans) but not fused with a scatter or a fold
+                       (FC_E_UNSUPPORTED) */
   FC_SCANR    = 7,  /* exclusive suffix combine; traversal order 1 */
   FC_SCATTER  = 8,  /* arg0 = dest (infusible, updated in place; none of the other arguments may be the same array:
                        FC_E_BADGRAPH), arg1 = index, arg2 = value, arg3 = flag (optional);

@@ -30,6 +30,8 @@ void append_generic_scan_instances(std::vector<Instance> &r) {
   r.push_back(scan_<SI0, SF1, kOffs | kScatter | kCount | kStoreX>());
   r.push_back(scan_f32_<SF0>());
   r.push_back(scan_f32_<SF0, true>());
+  r.push_back(scan_f32_<SF0, false, true>());
+  r.push_back(scan_f32_<SF0, true, true>());
   for (size_t k = first; k < r.size(); ++k) r[k].variant = "element programs interpreted";
 }
 

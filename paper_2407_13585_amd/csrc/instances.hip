@@ -101,6 +101,7 @@ std::vector<Instance> build_registry() {
   r.push_back(scan_f32_<F0>());
   r.push_back(scan_f32_<F0, true>());
   r.push_back(scan_f32_<Map<FnAffine, F0>>());
+  r.push_back(scan_f32_<Map<FnAffine, F0>, false, true>());       // the scanned array stored as well
   r.push_back(scan_f32_<Map<FnMul2, F0, F1>>());
   r.push_back(rowscan_<F0>());
   r.push_back(rowscan_<F0, true>());

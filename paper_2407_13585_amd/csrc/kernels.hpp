@@ -1381,7 +1381,7 @@ __device__ __forceinline__ float scan_block_sum_f32(float v, float *lds) {
   return r;
 }
 
-template <class EX, bool Reverse>
+template <class EX, bool Reverse, bool StoreX = false>
 __global__ __launch_bounds__(kScanBlock) void scan_f32_kernel(const KArgs a, Control *ctl, unsigned long long *status,
                                                               unsigned n_tiles) {
   static_assert(std::is_same<typename EX::R, float>::value, "fp32 stream");
@@ -1416,6 +1416,24 @@ __global__ __launch_bounds__(kScanBlock) void scan_f32_kernel(const KArgs a, Con
         const unsigned i = wbase + j * (kWave * kVec) + lane * kVec + c;
         x[j][c] = i < n ? EX::template eval<0>(a, (int)(Reverse ? n - 1 - i : i)) : 0.0f;
       }
+  }
+  if (StoreX) {
+    // the scanned array is a result as well: stored from the registers it was loaded into
+    float *xs = static_cast<float *>(a.out[3]);
+#pragma unroll
+    for (int j = 0; j < kScanFAcc; ++j) {
+      const unsigned i = wbase + j * (kWave * kVec) + lane * kVec;
+      if (whole) {
+        if (Reverse)
+          store4(xs + (n - 4 - i), Vec4<float>{{x[j][3], x[j][2], x[j][1], x[j][0]}});
+        else
+          store4(xs + i, Vec4<float>{{x[j][0], x[j][1], x[j][2], x[j][3]}});
+      } else {
+#pragma unroll
+        for (int c = 0; c < kVec; ++c)
+          if (i + c < n) xs[Reverse ? n - 1 - (i + c) : i + c] = x[j][c];
+      }
+    }
   }
   // exclusive prefix of each access inside the wave
   float excl[kScanFAcc];

@@ -139,10 +139,10 @@ template <class EX, class EV, int Mode, bool Reverse = false> hipError_t launch_
   return launch_k(&scan_kernel<EX, EV, Mode, Reverse>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
 }
 // lanes per row by row length, as for the row folds
-template <class EX, bool Reverse = false> hipError_t launch_scan_f32(const KArgs &a, const LaunchCtx &c) {
+template <class EX, bool Reverse = false, bool StoreX = false> hipError_t launch_scan_f32(const KArgs &a, const LaunchCtx &c) {
   long long tiles = std::max<long long>(1, ((long long)a.n + kScanFTile - 1) / kScanFTile);
   if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
-  return launch_k(&scan_f32_kernel<EX, Reverse>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
+  return launch_k(&scan_f32_kernel<EX, Reverse, StoreX>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
 }
 template <class E, bool Reverse> hipError_t launch_rowscan(const KArgs &a, const LaunchCtx &c) {
   if (a.aux == 0 || a.w == 0) return hipSuccess;
@@ -199,8 +199,9 @@ template <class EX, class EV, int Mode, bool Reverse = false> Instance scan_() {
   if (Mode & kStoreX) s += "+input";
   return {s, &launch_scan<EX, EV, Mode, Reverse>};
 }
-template <class EX, bool Reverse = false> Instance scan_f32_() {
-  return {std::string(Reverse ? "scanr[" : "scan[") + sig_of<EX>() + "]+offs", &launch_scan_f32<EX, Reverse>};
+template <class EX, bool Reverse = false, bool StoreX = false> Instance scan_f32_() {
+  return {std::string(Reverse ? "scanr[" : "scan[") + sig_of<EX>() + "]+offs" + (StoreX ? "+input" : ""),
+          &launch_scan_f32<EX, Reverse, StoreX>};
 }
 template <class E, bool Reverse = false> Instance rowscan_() {
   return {std::string(Reverse ? "rowscanr[" : "rowscan[") + sig_of<E>() + "]+offs", &launch_rowscan<E, Reverse>};

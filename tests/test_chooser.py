@@ -495,11 +495,11 @@ def unsupported_optimum_graphs():
     """Programs whose cheapest legal clustering has a cluster no kernel is built for."""
     out = {}
     n = 1000
-    g = Graph()                                  # a computed fp32 array that is stored and scanned: one diagonal cluster
-    g.add("v", "input", "f32", (n,))
-    g.add("w", "map", "f32", (n,), fn="exp_neg", args=("v",), output=True)
-    g.add("sums", "scanl", "f32", (n,), fn="add", args=("w",), output=True)
-    out["stored fp32 array + scan"] = g
+    g = Graph()                                  # a computed 2-D array that is stored and scanned row by row: one diagonal cluster
+    g.add("v", "input", "i32", (20, 50))
+    g.add("w", "map", "i32", (20, 50), fn="mod_eq", iparam=(3, 1), args=("v",), output=True)
+    g.add("sums", "scanl", "i32", (20, 50), fn="add", args=("w",), output=True)
+    out["stored array + row scan"] = g
     g = Graph()                                  # prefix sums and the total of an fp32 array in one pass
     g.add("x", "input", "f32", (n,))
     g.add("y", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("x",))

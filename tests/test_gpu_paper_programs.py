@@ -818,6 +818,39 @@ def test_scan_clusters_that_also_store_what_they_scan():
             assert prog.control_words()[1] == 0
 
 
+def test_fp32_scans_that_also_store_what_they_scan():
+    # the same for fp32: `affine` under scanl has a compiled instance, the others run with the element
+    # program interpreted; both arrays agree bit for bit with the unfused arm (same additions in the same
+    # tree), the stored array with the oracle as its map allows, the prefixes within the bound of the folds
+    rng = np.random.default_rng(22)
+    for n in (7, 8192, 8192 * 3 + 4, 50001):
+        for fn, right in (("affine", False), ("affine", True), ("exp_neg", False), ("sq_plus_one", True)):
+            g = Graph()
+            g.add("v", "input", "f32", (n,))
+            kw = {"fparam": (0.5, 0.25)} if fn == "affine" else {}
+            g.add("w", "map", "f32", (n,), fn=fn, args=("v",), output=True, **kw)
+            g.add("sums", "scanr" if right else "scanl", "f32", (n,), fn="add", args=("w",), output=True)
+            ins = {"v": rng.uniform(-1.0, 1.0, size=n).astype(F32)}
+            env = evaluate(g, ins)
+            part = fc().fc_plan(g, "bytes")
+            fused, unfused = device_program(g, ins, part), device_program(g, ins, None)
+            assert part.n_clusters == 1 and "+input" in fused.kernels()[0], fused.kernels()
+            assert ("interpreted" in fused.kernels()[0]) == (fn != "affine" or right)
+            fused.run()
+            unfused.run()
+            what = f"{fn} right={right} n={n}"
+            for o in ("w", "sums"):
+                P.assert_bit_exact(fused.fetch(o), unfused.fetch(o), what + " " + o)
+            if fn == "exp_neg":
+                P.assert_ulp(fused.fetch("w"), np.asarray(env["w"], dtype=np.float64).astype(F32), 4, what)
+            else:
+                P.assert_bit_exact(fused.fetch("w"), env["w"], what)
+            scale = prefix_scale(env["w"], right)
+            err = np.abs(fused.fetch("sums").astype(np.float64) - env["sums"].astype(np.float64))
+            assert np.all(err <= 1e-5 * scale + 1e-30), what
+            assert fused.control_words()[1] == 0
+
+
 def test_row_scans():
     # scans of two-dimensional arrays run row by row; row lengths on both sides of the
     # 16-lane / wave / workgroup variants, ragged against their step, with and without a fused producer
