@@ -148,7 +148,7 @@ def main() -> int:
                          "that hardware counter readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py: this build runs on one GPU; there is no multi-GPU path to measure (got --gpus %d)" % args.gpus)
+        log("bench.py: the library runs on one GPU; there is no multi-GPU path to measure (got --gpus %d)" % args.gpus)
         return 2
 
     import numpy as np
@@ -305,7 +305,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": ("SMALL DEBUG SIZES " if args.small else "") +
-                   "all five BASELINE pipelines, fused: " + ", ".join(work[c].name for c in cfgs)},
+                   "all five benchmark pipelines, fused: " + ", ".join(work[c].name for c in cfgs)},
         "gpu_sum_kernel_ms": round(sum(gpu_ms.values()), 5),
         "frac_hbm_peak": round(lb_total / (sum(gpu_ms.values()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "per_config": per,
