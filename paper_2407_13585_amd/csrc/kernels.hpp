@@ -827,16 +827,21 @@ __global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, 
     __syncthreads();
     const unsigned r = unit * kBlockedRows + threadIdx.x;
     if (r < rows) {
+      // the flags live in the control block, which starts out as zeros, so a flag of this
+      // launch means that the partials have been stored; the tag of each word covers the
+      // case that a word becomes visible after its flag.  The three words are read together
+      // (one round trip to memory instead of three); one that does not carry the tag yet is waited for.
+      unsigned long long w[kQuarters];
+#pragma unroll
+      for (unsigned p = 0; p < (unsigned)kQuarters; ++p) w[p] = p != q ? load_agent64(work + (size_t)p * rows + r) : 0ull;
       T v = Op::identity();
 #pragma unroll
       for (unsigned p = 0; p < (unsigned)kQuarters; ++p) {
         T part = own[threadIdx.x];
         if (p != q) {
-          // the flags live in the control block, which starts out as zeros, so a flag of this
-          // launch means that the partials have been stored; the tag of each word covers the
-          // case that a word becomes visible after its flag
-          const unsigned long long w = wait_word(work + (size_t)p * rows + r, tag, ctl);
-          part = w ? from_bits<T>((int)(unsigned)(w >> 32)) : Op::identity();
+          const unsigned lo = (unsigned)w[p];
+          if ((lo >> 2) != tag || (lo & 3u) == 0u) w[p] = wait_word(work + (size_t)p * rows + r, tag, ctl);
+          part = w[p] ? from_bits<T>((int)(unsigned)(w[p] >> 32)) : Op::identity();
         }
         v = Op::apply(v, part);
       }
@@ -844,18 +849,25 @@ __global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, 
     }
   };
 
+  // A unit is a chain of round trips to memory (row offsets, streams, gathers, the partners' partials), and a
+  // workgroup walks its units one after the other: the row offsets of the next unit are asked for while this
+  // one is worked on, which takes one link out of every chain.  (Asking for the next unit's streams that early
+  // as well costs thirty registers, a third of the resident workgroups, and gains nothing: 739 us against 730.)
+  // (agent scope, like the streams: nothing but the table should settle in L2)
+  const unsigned *offu = reinterpret_cast<const unsigned *>(off);
+  auto offset_of_row = [&](unsigned unit, unsigned local) {
+    const unsigned r = unit * kBlockedRows + local;
+    return unit < n_units ? (int)load_agent(offu + (r < rows ? r : rows)) : 0;
+  };
+  int next_start = offset_of_row(team, threadIdx.x), next_end = threadIdx.x == 0 ? offset_of_row(team, kBlockedRows) : 0;
   unsigned iter = 0, prev = ~0u;
   for (unsigned u = team; u < n_units; u += teams, ++iter) {
     T *sums = sums_of[iter & 1];
     // the unit's row offsets, read once and coalesced (rows past the end are empty)
-    {
-      const unsigned r = u * kBlockedRows + threadIdx.x;
-      // agent scope, like the streams: nothing but the table should settle in L2
-      const unsigned *offu = reinterpret_cast<const unsigned *>(off);
-      row_start[threadIdx.x] = (int)load_agent(offu + (r < rows ? r : rows));
-      if (threadIdx.x == 0)
-        row_start[kBlockedRows] = (int)load_agent(offu + (u * kBlockedRows + kBlockedRows < rows ? u * kBlockedRows + kBlockedRows : rows));
-    }
+    row_start[threadIdx.x] = next_start;
+    if (threadIdx.x == 0) row_start[kBlockedRows] = next_end;
+    next_start = offset_of_row(u + teams, threadIdx.x);
+    if (threadIdx.x == 0) next_end = offset_of_row(u + teams, kBlockedRows);
     __syncthreads();
     // the unit's stretch of both streams, from the 16-byte boundary below its first element:
     // read, gather, multiply, and leave the terms in LDS
