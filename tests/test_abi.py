@@ -248,3 +248,12 @@ def test_duplicate_keeps_program_meaning():
             assert np.array_equal(a[o], b[o])
         for i, n in enumerate(g2.nodes):
             assert n.kind == w.graph.nodes[origin[i]].kind
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU is all the library uses: asked for more, the benchmark says so and measures nothing
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert p.returncode != 0 and "one GPU" in p.stderr and p.stdout.strip() == ""
