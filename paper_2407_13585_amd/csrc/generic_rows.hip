@@ -13,6 +13,11 @@ void append_generic_row_instances(std::vector<Instance> &r) {
   r.push_back(rowscan_<XI0, true>());
   r.push_back(rowscan_<XF0>());
   r.push_back(rowscan_<XF0, true>());
+  // the scanned array stored as well
+  r.push_back(rowscan_<XI0, false, true>());
+  r.push_back(rowscan_<XI0, true, true>());
+  r.push_back(rowscan_<XF0, false, true>());
+  r.push_back(rowscan_<XF0, true, true>());
   r.push_back(rowfold_<AddF32, NoSecondOp, XF0>());
   r.push_back(rowfold_<MulF32, NoSecondOp, XF0>());
   r.push_back(rowfold_<MaxF32, NoSecondOp, XF0>());

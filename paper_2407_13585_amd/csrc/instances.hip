@@ -97,6 +97,7 @@ std::vector<Instance> build_registry() {
   r.push_back(rowscan_<I0, true>());
   r.push_back(rowscan_<ModFlag>());
   r.push_back(rowscan_<ModFlag, true>());
+  r.push_back(rowscan_<ModFlag, false, true>());                 // the flags stored as well
   // prefix sums of fp32 arrays, alone and with a producer fused in
   r.push_back(scan_f32_<F0>());
   r.push_back(scan_f32_<F0, true>());

@@ -1510,7 +1510,7 @@ __global__ __launch_bounds__(kScanBlock) void scan_f32_kernel(const KArgs a, Con
 // pass: L lanes walk it in steps of L elements, a carry links the steps, rows are
 // independent.  L is a 16-lane DPP row, a wave, or the workgroup, by row length.
 // out[1] receives the exclusive prefix sums; scanr is the same pass from the right.
-template <class E, bool Reverse, int L>
+template <class E, bool Reverse, int L, bool StoreX = false>
 __global__ __launch_bounds__(kBlock) void rowscan_kernel(const KArgs a) {
   static_assert(L == 16 || L == kWave || L == kBlock, "lanes per row");
   using T = typename E::R;
@@ -1530,6 +1530,7 @@ __global__ __launch_bounds__(kBlock) void rowscan_kernel(const KArgs a) {
       const bool live = r < rows && c < w;
       const int e = live ? (int)(r * w + (Reverse ? w - 1 - c : c)) : 0;
       const T x = live ? E::template eval<0>(a, e) : T();
+      if (StoreX && live) static_cast<T *>(a.out[3])[e] = x;      // the scanned array is a result as well
       // inclusive prefix over the L lanes, the exclusive one by moving it one lane on (a
       // floating-point sum cannot give its last term back), and the step's total
       T inc, exc, total;

@@ -144,13 +144,13 @@ template <class EX, bool Reverse = false, bool StoreX = false> hipError_t launch
   if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;
   return launch_k(&scan_f32_kernel<EX, Reverse, StoreX>, (unsigned)tiles, c.stream, kScanBlock, a, c.ctl, c.status, (unsigned)tiles);
 }
-template <class E, bool Reverse> hipError_t launch_rowscan(const KArgs &a, const LaunchCtx &c) {
+template <class E, bool Reverse, bool StoreX = false> hipError_t launch_rowscan(const KArgs &a, const LaunchCtx &c) {
   if (a.aux == 0 || a.w == 0) return hipSuccess;
   if (a.w <= 64)
-    return launch_k(&rowscan_kernel<E, Reverse, 16>, grid_for(a.aux, kBlock / 16, resident_grid(&rowscan_kernel<E, Reverse, 16>)), c.stream, a);
+    return launch_k(&rowscan_kernel<E, Reverse, 16, StoreX>, grid_for(a.aux, kBlock / 16, resident_grid(&rowscan_kernel<E, Reverse, 16, StoreX>)), c.stream, a);
   if (a.w <= 1024)
-    return launch_k(&rowscan_kernel<E, Reverse, kWave>, grid_for(a.aux, kBlock / kWave, resident_grid(&rowscan_kernel<E, Reverse, kWave>)), c.stream, a);
-  return launch_k(&rowscan_kernel<E, Reverse, kBlock>, grid_for(a.aux, 1, resident_grid(&rowscan_kernel<E, Reverse, kBlock>)), c.stream, a);
+    return launch_k(&rowscan_kernel<E, Reverse, kWave, StoreX>, grid_for(a.aux, kBlock / kWave, resident_grid(&rowscan_kernel<E, Reverse, kWave, StoreX>)), c.stream, a);
+  return launch_k(&rowscan_kernel<E, Reverse, kBlock, StoreX>, grid_for(a.aux, 1, resident_grid(&rowscan_kernel<E, Reverse, kBlock, StoreX>)), c.stream, a);
 }
 template <class EI, class EV, class EF, bool Add> hipError_t launch_scatter(const KArgs &a, const LaunchCtx &c) {
   if (a.n == 0) return hipSuccess;
@@ -203,8 +203,9 @@ template <class EX, bool Reverse = false, bool StoreX = false> Instance scan_f32
   return {std::string(Reverse ? "scanr[" : "scan[") + sig_of<EX>() + "]+offs" + (StoreX ? "+input" : ""),
           &launch_scan_f32<EX, Reverse, StoreX>};
 }
-template <class E, bool Reverse = false> Instance rowscan_() {
-  return {std::string(Reverse ? "rowscanr[" : "rowscan[") + sig_of<E>() + "]+offs", &launch_rowscan<E, Reverse>};
+template <class E, bool Reverse = false, bool StoreX = false> Instance rowscan_() {
+  return {std::string(Reverse ? "rowscanr[" : "rowscan[") + sig_of<E>() + "]+offs" + (StoreX ? "+input" : ""),
+          &launch_rowscan<E, Reverse, StoreX>};
 }
 template <class EI, class EV, class EF, bool Add = false> Instance scatter_() {
   return {std::string(Add ? "scatter.add[" : "scatter[") + sig_of<EI>() + "," + sig_of<EV>() + "," + sig_of<EF>() + "]",

@@ -177,8 +177,8 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
       return unsupported("a scan of f32 can be stored, with or without the array it scans, and nothing more");
     // a two-dimensional array is scanned row by row (one row: the same as one dimension)
     const bool by_rows = m.nodes[sc].rank == 2 && m.nodes[sc].shape[0] != 1;
-    if (by_rows && (!scatters.empty() || !folds.empty() || c.fused_away[sc] || stores_input))
-      return unsupported("a row scan can only be stored");
+    if (by_rows && (!scatters.empty() || !folds.empty() || c.fused_away[sc]))
+      return unsupported("a row scan can be stored, with or without the array it scans, and nothing more");
     sig = by_rows ? (m.nodes[sc].kind == FC_SCANR ? "rowscanr[" : "rowscan[")
                   : (m.nodes[sc].kind == FC_SCANR ? "scanr[" : "scan[");
     any = sig;

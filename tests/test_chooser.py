@@ -495,11 +495,12 @@ def unsupported_optimum_graphs():
     """Programs whose cheapest legal clustering has a cluster no kernel is built for."""
     out = {}
     n = 1000
-    g = Graph()                                  # a computed 2-D array that is stored and scanned row by row: one diagonal cluster
+    g = Graph()                                  # row-wise prefix sums and the grand total of a computed 2-D array in one pass
     g.add("v", "input", "i32", (20, 50))
-    g.add("w", "map", "i32", (20, 50), fn="mod_eq", iparam=(3, 1), args=("v",), output=True)
+    g.add("w", "map", "i32", (20, 50), fn="mod_eq", iparam=(3, 1), args=("v",))
     g.add("sums", "scanl", "i32", (20, 50), fn="add", args=("w",), output=True)
-    out["stored array + row scan"] = g
+    g.add("total", "fold", "i32", (1,), fn="add", args=("w",), output=True)
+    out["row scan + total"] = g
     g = Graph()                                  # prefix sums and the total of an fp32 array in one pass
     g.add("x", "input", "f32", (n,))
     g.add("y", "map", "f32", (n,), fn="affine", fparam=(2.0, 1.0), args=("x",))

@@ -851,6 +851,35 @@ def test_fp32_scans_that_also_store_what_they_scan():
             assert fused.control_words()[1] == 0
 
 
+def test_row_scans_that_also_store_what_they_scan():
+    # two-dimensional arrays: every row scanned on its own, the scanned array a result as well
+    rng = np.random.default_rng(23)
+    for shape in ((1, 300), (200, 777), (3000, 17), (5, 5000)):
+        for dtype, fn, right in (("i32", "mod_eq", False), ("i32", "mod_eq", True), ("f32", "sq_plus_one", False), ("f32", "affine", True)):
+            g = Graph()
+            g.add("v", "input", dtype, shape)
+            kw = {"iparam": (3, 0)} if fn == "mod_eq" else {"fparam": (0.5, 0.25)} if fn == "affine" else {}
+            g.add("w", "map", dtype, shape, fn=fn, args=("v",), output=True, **kw)
+            g.add("sums", "scanr" if right else "scanl", dtype, shape, fn="add", args=("w",), output=True)
+            ins = {"v": rng.integers(0, 2 ** 31, size=shape, dtype=np.int32) if dtype == "i32"
+                   else rng.uniform(-1.0, 1.0, size=shape).astype(F32)}
+            env = evaluate(g, ins)
+            part = fc().fc_plan(g, "bytes")
+            fused, unfused = device_program(g, ins, part), device_program(g, ins, None)
+            assert part.n_clusters == 1 and "+input" in fused.kernels()[0], fused.kernels()
+            fused.run()
+            unfused.run()
+            what = f"{shape} {dtype} right={right}"
+            for o in ("w", "sums"):
+                P.assert_bit_exact(fused.fetch(o), unfused.fetch(o), what + " " + o)
+            P.assert_bit_exact(fused.fetch("w"), env["w"], what)
+            if dtype == "i32":
+                P.assert_bit_exact(fused.fetch("sums"), env["sums"], what)
+            else:
+                err = np.abs(fused.fetch("sums").astype(np.float64) - env["sums"].astype(np.float64))
+                assert np.all(err <= 1e-5 * prefix_scale(env["w"], right) + 1e-30), what
+
+
 def test_row_scans():
     # scans of two-dimensional arrays run row by row; row lengths on both sides of the
     # 16-lane / wave / workgroup variants, ragged against their step, with and without a fused producer
