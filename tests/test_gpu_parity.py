@@ -290,18 +290,21 @@ def test_repeated_runs_share_scratch():
 
 def test_two_streams_each_with_its_own_scratch():
     # launches that overlap in time must not share a scratch buffer; with one each they may: two streams
-    # (default priority) with two programs each, whose kernels wait for other workgroups
+    # (default priority) with two and three programs, whose kernels wait for other workgroups
     import torch
     rng = np.random.default_rng(79)
     big = 2200003
     items = [(4, C.compaction(n=3000001, seed=9)),
              (3, C.spmv(lengths=rng.poisson(8.0, size=20000), seed=6, ncols=1200000)),
              (2, C.perm_gather_fold(xs=rng.standard_normal(size=big).astype(F32), idx=rng.permutation(big).astype(np.int32))),
-             (5, build(5, small=True))]
+             (5, build(5, small=True)),
+             # a second column-blocked fold, on the other stream than the first: two launches whose workgroups wait for partners
+             (3, C.spmv(lengths=rng.poisson(12.0, size=60000), seed=7, ncols=1500000))]
     progs = []
     for cfg, w in items:
         g, part = plan(w.graph, True)
         progs.append(device_program(g, w.inputs, part))
+    assert "column-blocked" in progs[1].kernels()[0] and "column-blocked" in progs[4].kernels()[0]
     torch.cuda.synchronize()
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
     for rep in range(6):
