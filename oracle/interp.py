@@ -29,6 +29,14 @@ Readings taken where the paper leaves a choice
     reduces the innermost dimension.
   * foldSeg (only named in the paper) folds the flat value array over the
     segments [off[r], off[r+1]).
+  * values that are not finite (the paper says nothing about them): every element
+    function and (+) follow IEEE-754 operation by operation, so a NaN, or infinities
+    of both signs, among the summands of a fold / segmented fold / scan prefix give
+    NaN and infinities of one sign give that infinity; max is IEEE-754 maxNum, which
+    treats a NaN operand as missing (the maximum of the other values; the identity
+    -inf when there are none).  Either rule gives one result whatever the order of
+    evaluation, which a parallel fold needs.  Partial sums that overflow fp32 although
+    the exact sum is finite are outside the comparison (the reference sums in fp64).
   * scatter(f, dest, src): src is the SoA tuple (index, value[, flag]); for every
     element in source order with a non-zero flag, dest[index] becomes
     f(dest[index], value); f = overwrite means "the new value wins" and then the
@@ -123,7 +131,9 @@ def _reduce(op, a, dtype, axis=None):
         return np.add.reduce(a, axis=axis, initial=z)
     if op == "mul":
         return np.multiply.reduce(a, axis=axis, initial=z)
-    return np.maximum.reduce(a, axis=axis, initial=z)
+    # max over fp32 is IEEE-754 maxNum: a NaN operand counts as missing, the other operand is
+    # the result (np.fmax); with integers fmax is the plain maximum
+    return np.fmax.reduce(a, axis=axis, initial=z)
 
 
 def _finish(r, dtype):
@@ -157,7 +167,7 @@ def _foldseg(op, vals, off, dtype):
     # element, so consecutive non-empty starts delimit exactly the non-empty segments.
     nonempty = np.nonzero(off[1:] > off[:-1])[0]
     if nonempty.size:
-        ufunc = {"add": np.add, "mul": np.multiply, "max": np.maximum}[op]
+        ufunc = {"add": np.add, "mul": np.multiply, "max": np.fmax}[op]
         out[nonempty] = ufunc.reduceat(a[:int(off[-1])], off[:-1][nonempty])
     return _finish(out, dtype)
 

@@ -102,6 +102,52 @@ def test_plans_have_the_expected_shape():
     assert k == {1: (2, 1), 2: (1, 1), 3: (1, 1), 4: (1, 1), 5: (2, 1)}
 
 
+# ------------------------------------------------------------------ values that are not finite
+@pytest.mark.parametrize("n", [37, 70001])
+def test_nonfinite_values_are_compared_by_class(n):
+    # an infinity and a NaN among the inputs of fold(+), fold(max), the fp32 scans and a segmented
+    # fold (+ and max), fused and one kernel per combinator.  (+) is IEEE addition, max is maxNum
+    # (a NaN counts as missing): both give one result whatever the order of evaluation.
+    rng = np.random.default_rng(n)
+    for special in ((np.inf, np.nan), (np.inf, -np.inf), (-np.inf, None), (np.nan, None)):
+        x = rng.uniform(-1.0, 1.0, n).astype(F32)
+        x[n // 3] = special[0]
+        if special[1] is not None:
+            x[(2 * n) // 3] = special[1]
+        rows = max(1, n // 9)
+        cuts = np.sort(rng.integers(0, n + 1, rows - 1))
+        off = np.concatenate([[0], cuts, [n]]).astype(np.int32)
+        g = Graph()
+        g.add("x", "input", "f32", (n,))
+        g.add("off", "input", "i32", (rows + 1,))
+        g.add("s", "fold", "f32", (1,), fn="add", args=("x",), output=True)
+        g.add("m", "fold", "f32", (1,), fn="max", args=("x",), output=True)
+        g.add("l", "scanl", "f32", (n,), fn="add", args=("x",), output=True)
+        g.add("r", "scanr", "f32", (n,), fn="add", args=("x",), output=True)
+        g.add("ys", "foldseg", "f32", (rows,), fn="add", args=("x", "off"), output=True)
+        g.add("ym", "foldseg", "f32", (rows,), fn="max", args=("x", "off"), output=True)
+        ins = {"x": x, "off": off}
+        with np.errstate(all="ignore"):
+            env = evaluate(g, ins)
+        assert not np.all(np.isfinite(env["l"])) and not np.isfinite(env["s"][0])      # the case is not vacuous
+        finite_abs = np.where(np.isfinite(x), np.abs(x), F32(0)).astype(np.float64)
+        for tag, part in (("fused", fc().fc_plan(g, "bytes")), ("unfused", None)):
+            prog = device_program(g, ins, part)
+            prog.run()
+            what = f"n={n} special={special} {tag}"
+            P.assert_fold(prog.fetch("s"), env["s"], what + " fold(+)")
+            P.assert_bit_exact(prog.fetch("m"), env["m"].astype(F32), what + " fold(max)")
+            P.assert_bit_exact(prog.fetch("ym"), env["ym"].astype(F32), what + " foldSeg(max)")
+            P.assert_segmented(prog.fetch("ys"), env["ys"], x, off, what + " foldSeg(+)")
+            for name, scale in (("l", np.concatenate([[0.0], np.cumsum(finite_abs)[:-1]])),
+                                ("r", np.concatenate([np.cumsum(finite_abs[::-1])[::-1][1:], [0.0]]))):
+                got, ref = prog.fetch(name), env[name]
+                finite = P.same_class(got, ref, what + " scan " + name)
+                err = np.abs(np.where(finite, got, 0).astype(np.float64) - np.where(finite, ref, 0).astype(np.float64))
+                assert np.all(err <= 1e-5 * scale + 1e-30), what + " scan " + name
+            assert prog.control_words()[1] == 0
+
+
 # ------------------------------------------------------------------ ragged sizes, tiles, edges
 @pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 255, 4095, 4096, 4097, 8191, 12289, 1 << 20,
                                # tile counts around the groups of 16 the mirrored tile order forms

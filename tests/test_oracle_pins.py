@@ -398,8 +398,9 @@ def test_compaction_invariants():
     count = int(env["count"][0])
     assert offs[0] == 0
     assert np.array_equal(np.diff(offs), flags[:-1])
-    assert count == int(offs[-1] + flags[-1]) == w.extra["kept"]          # count = scan total
+    assert count == int(offs[-1] + flags[-1])                             # count = scan total
     keep = [int(x) for x in v.tolist() if x % 3 == 0]                    # stable filtered subsequence
+    assert count == len(keep)
     assert out[:count].tolist() == keep
     assert np.all(out[count:] == -1)                                      # untouched part of dest
     # statistical pin on the generator + predicate: p = 715827883 / 2^31
@@ -516,3 +517,174 @@ def test_all_small_configs_evaluate():
         env = evaluate(w.graph, w.inputs)
         for o in w.graph.outputs():
             assert env[o].shape == tuple(w.graph[o].shape)
+
+
+# ---------------------------------------------------------------- the remaining vocabulary, one pin each
+def test_mul_reducer_against_python_products():
+    # fold / row fold / foldSeg with (*): exact rational products of short arrays (every value is
+    # a small integer or a power of two, so the fp64 product is the exact one), and the identity 1
+    from fractions import Fraction
+    rng = np.random.default_rng(41)
+    for n in range(0, 9):
+        a = rng.integers(-3, 4, n).astype(F32)
+        a[a == 0] = F32(2.0)
+        want = Fraction(1)
+        for v in a.tolist():
+            want *= Fraction(v)
+        assert Fraction(float(run(_fold_graph(n, "mul"), {"a": a})["r"][0])) == want
+    pw = np.array([2.0 ** k for k in (3, -5, 7, -2, 0, 1)], dtype=F32)
+    assert run(_fold_graph(6, "mul"), {"a": pw})["r"][0] == 2.0 ** 4
+    # a sign and a zero: the product is not a sum in disguise
+    assert run(_fold_graph(3, "mul"), {"a": np.array([-1.5, 2.0, 4.0], F32)})["r"][0] == -12.0
+    assert run(_fold_graph(3, "mul"), {"a": np.array([5.0, 0.0, 7.0], F32)})["r"][0] == 0.0
+    # rows of a two-dimensional array, each on its own
+    a2 = np.array([[1, 2, 3, 4], [2, 2, 2, 2], [-1, 1, -1, 5]], dtype=F32)
+    g = Graph()
+    g.add("a", "input", "f32", (3, 4))
+    g.add("r", "fold", "f32", (3,), fn="mul", args=("a",))
+    assert run(g, {"a": a2})["r"].tolist() == [24.0, 16.0, 5.0]
+    # int32 products
+    gi = Graph()
+    gi.add("a", "input", "i32", (2, 3))
+    gi.add("r", "fold", "i32", (2,), fn="mul", args=("a",))
+    assert run(gi, {"a": np.array([[2, 3, 5], [-7, 1, 11]], np.int32)})["r"].tolist() == [30, -77]
+    # segments, the empty ones yielding the identity of (*)
+    gs = Graph()
+    gs.add("v", "input", "f32", (5,))
+    gs.add("off", "input", "i32", (5,))
+    gs.add("y", "foldseg", "f32", (4,), fn="mul", args=("v", "off"))
+    y = run(gs, {"v": np.array([2, 3, 5, 7, 11], F32), "off": np.array([0, 2, 2, 5, 5], np.int32)})["y"]
+    assert y.tolist() == [6.0, 1.0, 385.0, 1.0]
+
+
+def test_add2_add3_round_after_every_addition_in_argument_order():
+    # element by element against F32(F32(a + b) + c); the triples are picked so that the other
+    # association, and a single rounding at the end, give another value
+    a = np.array([1e8, 1.0, 0.1, 16777216.0, -3.5], dtype=F32)
+    b = np.array([-1e8, 2.0 ** -24, 0.2, 1.0, 3.5], dtype=F32)
+    c = np.array([1.0, 2.0 ** -24, 0.3, 1.0, 2.0 ** -30], dtype=F32)
+    g = Graph()
+    for nm in "abc":
+        g.add(nm, "input", "f32", (5,))
+    g.add("s2", "map", "f32", (5,), fn="add2", args=("a", "b"))
+    g.add("s3", "map", "f32", (5,), fn="add3", args=("a", "b", "c"))
+    g.add("d2", "map", "f32", (5,), fn="add2", args=("b", "c"))          # arguments are not swapped or reused
+    env = run(g, {"a": a, "b": b, "c": c})
+    differs = 0
+    for i in range(5):
+        x, y, z = float(a[i]), float(b[i]), float(c[i])
+        assert env["s2"][i] == F32(x + y)                                 # the sum of two floats in fp64 rounds once: exact
+        assert env["s3"][i] == F32(float(F32(x + y)) + z)
+        assert env["d2"][i] == F32(y + z)
+        differs += env["s3"][i] != F32(x + float(F32(y + z)))
+    assert differs >= 2                                                   # the pin can tell (a+b)+c from a+(b+c)
+    assert env["s3"][0] == 1.0 and env["s3"][3] == 16777216.0
+
+
+def test_row_of_2d_and_const_i32_against_nested_loops():
+    h, w = 3, 5
+    g = Graph()
+    g.add("r", "generate", "i32", (h, w), fn="row_of_2d")
+    g.add("k", "generate", "i32", (h, w), fn="const_i32", iparam=(-7,))
+    g.add("k1", "generate", "i32", (4,), fn="const_i32", iparam=(2147483647,))
+    env = run(g, {})
+    for i in range(h):
+        for j in range(w):
+            assert env["r"][i, j] == i and env["k"][i, j] == -7
+    assert env["r"].dtype == np.int32 and env["k"].dtype == np.int32 and env["r"].shape == (h, w)
+    assert env["k1"].tolist() == [2147483647] * 4
+    # the row index picks rows: gathering a column vector by it repeats every entry along its row
+    g2 = Graph()
+    g2.add("xs", "input", "f32", (h,))
+    g2.add("r", "generate", "i32", (h, w), fn="row_of_2d")
+    g2.add("big", "gather", "f32", (h, w), args=("r", "xs"))
+    xs = np.array([1.5, -2.0, 4.0], F32)
+    assert run(g2, {"xs": xs})["big"].tolist() == [[v] * w for v in xs.tolist()]
+
+
+def test_force_and_ident_are_bit_identical_copies():
+    # bit patterns survive (a negative zero, a NaN with a payload, a denormal), for both types,
+    # and the result is a new array: later writes to one side do not show in the other
+    bits = np.array([0x80000000, 0x7fc12345, 0x00000001, 0x3f800000, 0xff800000], dtype=np.uint32)
+    xf = bits.view(F32)
+    xi = np.array([-2 ** 31, -1, 0, 7, 2 ** 31 - 1], dtype=np.int32)
+    g = Graph()
+    g.add("xf", "input", "f32", (5,))
+    g.add("xi", "input", "i32", (5,))
+    g.add("ff", "force", "f32", (5,), args=("xf",))
+    g.add("fi", "force", "i32", (5,), args=("xi",))
+    g.add("mf", "map", "f32", (5,), fn="ident", args=("xf",))
+    g.add("mi", "map", "i32", (5,), fn="ident", args=("xi",))
+    env = run(g, {"xf": xf, "xi": xi})
+    for name in ("ff", "mf"):
+        assert env[name].dtype == F32 and env[name].view(np.uint32).tolist() == bits.tolist()
+        assert not np.shares_memory(env[name], xf)
+    for name in ("fi", "mi"):
+        assert env[name].dtype == np.int32 and env[name].tolist() == xi.tolist()
+        assert not np.shares_memory(env[name], xi)
+
+
+@pytest.mark.parametrize("k,r", [(2, 1), (3, 0), (4, 3), (7, 6), (5, 5), (5, 9), (1, 0), (1000003, 17)])
+def test_mod_eq_against_python_remainders(k, r):
+    rng = np.random.default_rng(k * 31 + r)
+    v = np.concatenate([np.arange(0, 40), rng.integers(0, 2 ** 31, 200), [2 ** 31 - 1, 2 ** 31 - 2, k, k - 1 if k > 1 else 0, r]]).astype(np.int32)
+    g = Graph()
+    g.add("v", "input", "i32", (v.size,))
+    g.add("f", "map", "i32", (v.size,), fn="mod_eq", iparam=(k, r), args=("v",))
+    f = run(g, {"v": v})["f"]
+    assert f.dtype == np.int32
+    assert f.tolist() == [1 if int(x) % k == r else 0 for x in v.tolist()]
+    if r >= k:
+        assert not f.any()                                                # a residue outside [0, k) matches nothing
+
+
+# ---------------------------------------------------------------- values that are not finite
+def test_nonfinite_values_in_folds_scans_and_maps():
+    # (+) follows IEEE-754: a NaN among the summands, or infinities of both signs, give NaN;
+    # infinities of one sign give that infinity.  max is maxNum: a NaN counts as missing.
+    # Each outcome is the same for every order of evaluation, which is checked on permutations.
+    nan, inf = float("nan"), float("inf")
+    rng = np.random.default_rng(43)
+    base = rng.standard_normal(12).astype(F32)
+    cases = {"nan": [3, nan], "pinf": [5, inf], "ninf": [7, -inf], "both": [2, inf, 9, -inf], "pinf_nan": [1, inf, 4, nan]}
+    for name, spec in cases.items():
+        a = base.copy()
+        for pos, val in zip(spec[0::2], spec[1::2]):
+            a[pos] = val
+        for trial in range(4):
+            b = a[rng.permutation(12)] if trial else a
+            s = run(_fold_graph(12), {"a": b})["r"][0]
+            m = run(_fold_graph(12, "max"), {"a": b})["r"][0]
+            finite_max = max(v for v in b.tolist() if not math.isnan(v))
+            assert m == finite_max, (name, trial)
+            if name in ("nan", "both", "pinf_nan"):
+                assert math.isnan(s), (name, trial)
+            else:
+                assert s == (inf if name == "pinf" else -inf), (name, trial)
+    # nothing but NaN: the identity of max; a segment likewise, and one NaN does not leak into other segments
+    assert run(_fold_graph(3, "max"), {"a": np.full(3, nan, F32)})["r"][0] == -inf
+    gs = Graph()
+    gs.add("v", "input", "f32", (6,))
+    gs.add("off", "input", "i32", (4,))
+    gs.add("s", "foldseg", "f32", (3,), fn="add", args=("v", "off"))
+    gs.add("m", "foldseg", "f32", (3,), fn="max", args=("v", "off"))
+    env = run(gs, {"v": np.array([1, nan, 2, 3, inf, 4], F32), "off": np.array([0, 2, 4, 6], np.int32)})
+    assert math.isnan(env["s"][0]) and env["s"][1] == 5.0 and env["s"][2] == inf
+    assert env["m"].tolist() == [1.0, 3.0, inf]
+    # exclusive scan: a prefix is affected from the element after the special value on
+    gl = Graph()
+    gl.add("a", "input", "f32", (6,))
+    gl.add("l", "scanl", "f32", (6,), fn="add", args=("a",))
+    gl.add("r", "scanr", "f32", (6,), fn="add", args=("a",))
+    env = run(gl, {"a": np.array([1, 2, inf, 4, nan, 8], F32)})
+    assert env["l"][:3].tolist() == [0.0, 1.0, 3.0] and env["l"][3] == inf and env["l"][4] == inf and math.isnan(env["l"][5])
+    assert math.isnan(env["r"][0]) and math.isnan(env["r"][3]) and env["r"][4] == 8.0 and env["r"][5] == 0.0
+    # element functions: sin of an infinity is NaN, exp(-x) saturates to 0 and to +inf
+    gm = Graph()
+    gm.add("x", "input", "f32", (4,))
+    gm.add("s", "map", "f32", (4,), fn="sin_x_mul_x", args=("x",))
+    gm.add("e", "map", "f32", (4,), fn="exp_neg", args=("x",))
+    with np.errstate(all="ignore"):
+        env = run(gm, {"x": np.array([inf, -inf, nan, 1000.0], F32)})
+    assert all(math.isnan(v) for v in env["s"][:3].tolist())
+    assert env["e"][0] == 0.0 and env["e"][1] == inf and math.isnan(env["e"][2]) and env["e"][3] == 0.0

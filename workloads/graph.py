@@ -33,7 +33,7 @@ KINDS = ("input", "map", "generate", "gather", "fold", "foldseg",
 
 # element functions of map nodes (arity in brackets)
 MAP_FNS = ("ident", "affine", "sin_x_mul_x", "sq_plus_one", "mul2", "add2",
-           "add3", "add5", "exp_neg", "mod_eq", "pair_first_nonzero")
+           "add3", "add5", "exp_neg", "mod_eq")
 # index functions of generate nodes
 GEN_FNS = ("iota", "iota_rev", "clamp_shift_2d", "row_of_2d", "const_i32")
 # reducers of fold / foldseg / scan, combination functions of scatter
