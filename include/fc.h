@@ -39,6 +39,7 @@ extern "C" {
 #define FC_E_HIP               -6  /* a HIP runtime call failed (message holds hipGetErrorString) */
 #define FC_E_ARG               -7  /* NULL / out-of-range argument, capacity too small */
 #define FC_E_LIMIT             -8  /* graph too large for the exact chooser, or a size above 2^31-1 elements */
+#define FC_E_DEVICE_WAIT       -9  /* fc_check: a kernel of an earlier call gave up a bounded wait (see fc_check) */
 
 /* ---------------------------------------------------------------- vocabulary */
 /* Combinators of the language (section 2; Table 1 gives their cluster signatures).
@@ -247,6 +248,28 @@ int fc_run_fused(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs
  * (generated index arrays included) materialised in scratch unless bound. */
 int fc_run_unfused(const fc_graph *g, const fc_buffer *bufs,
                    void *scratch, size_t scratch_bytes, void *hip_stream);
+
+/* Status of the device work enqueued so far by fc_run_* calls that used `scratch`.
+ *
+ * Kernels whose workgroups hand partial results to each other (the last stage of a fold,
+ * the tiles of a single-pass scan, the teams of the column-blocked segmented fold; section
+ * 2 asks of a fold or scan inside a cluster only that it is one pass, and names the chained
+ * scan) never wait without bound: a workgroup polls for a word of another workgroup of its
+ * launch at most a fixed number of times (about a second), then takes the operator's
+ * identity in place of the missing value, sets word 1 of the control block at the start of
+ * scratch (word 0 counts the launches that used the block) and goes on, so that no launch
+ * can hang the device.  The results of such a launch are wrong.  It cannot happen while the
+ * assumptions the kernels rest on hold (workgroups of a launch start in index order; the
+ * device is not shared with work that holds compute units for seconds), and fc_run_* does
+ * not look: it only enqueues.  A caller that wants the guarantee calls fc_check after the
+ * calls whose results it is about to use.
+ *
+ * fc_check waits until the work enqueued on `hip_stream` has finished (it synchronises the
+ * stream), reads the word, and returns FC_OK if it is zero.  Otherwise it clears the word
+ * and returns FC_E_DEVICE_WAIT: every result produced with this scratch buffer since the
+ * last check is to be discarded.  scratch: DEVICE, the buffer given to fc_run_*.  Allocates
+ * nothing.  Errors: FC_E_SCRATCH (NULL or misaligned), FC_E_HIP. */
+int fc_check(void *scratch, void *hip_stream);
 
 /* Name of the kernel instance chosen for cluster `cluster` of the clustering
  * (p == NULL: the unfused clustering), for reports and profiles. */

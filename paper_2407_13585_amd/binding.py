@@ -35,7 +35,7 @@ FC_PLAN_ANYTIME = 4
 FC_NODE_OUTPUT = 1
 
 ERRORS = {-1: "FC_E_BADGRAPH", -2: "FC_E_ILLEGAL_PARTITION", -3: "FC_E_UNSUPPORTED", -4: "FC_E_UNBOUND",
-          -5: "FC_E_SCRATCH", -6: "FC_E_HIP", -7: "FC_E_ARG", -8: "FC_E_LIMIT"}
+          -5: "FC_E_SCRATCH", -6: "FC_E_HIP", -7: "FC_E_ARG", -8: "FC_E_LIMIT", -9: "FC_E_DEVICE_WAIT"}
 
 
 class FcError(RuntimeError):
@@ -110,7 +110,8 @@ def lib() -> C.CDLL:
     L.fc_run_fused.argtypes = [PG, PP, C.POINTER(fc_buffer), C.c_void_p, C.c_size_t, C.c_void_p]
     L.fc_run_unfused.argtypes = [PG, C.POINTER(fc_buffer), C.c_void_p, C.c_size_t, C.c_void_p]
     L.fc_cluster_kernel.argtypes = [PG, PP, C.c_int32, C.c_char_p, C.c_size_t]
-    for f in ("fc_num_edges", "fc_plan", "fc_plan_weighted", "fc_plan_greedy", "fc_partition_trivial", "fc_partition_check", "fc_duplicate",
+    L.fc_check.argtypes = [C.c_void_p, C.c_void_p]
+    for f in ("fc_check", "fc_num_edges", "fc_plan", "fc_plan_weighted", "fc_plan_greedy", "fc_partition_trivial", "fc_partition_check", "fc_duplicate",
               "fc_scratch_bytes", "fc_run_fused", "fc_run_unfused", "fc_cluster_kernel"):
         getattr(L, f).restype = C.c_int
     _lib = L
@@ -372,6 +373,13 @@ class BoundRun:
                                         stream or None)
         if rc != 0:
             _check(rc)
+
+
+def fc_check(scratch, stream: int = 0) -> None:
+    """Synchronises `stream` and raises FcError (FC_E_DEVICE_WAIT) if a kernel that used `scratch`
+    gave up a bounded wait since the last check."""
+    sp, _ = _scratch(scratch)
+    _check(lib().fc_check(sp, stream or None))
 
 
 def fc_cluster_kernel(graph, partition: Optional[Partition], cluster: int) -> str:

@@ -58,13 +58,45 @@ fc::SearchBudget budget_of(uint32_t flags) {
   return b;
 }
 
+// Every combinator in a cluster of its own.  The clusters are numbered in a topological
+// order of the program that also puts every other reader of a scatter's destination before
+// the scatter (the destination is updated in place, so the scatter is its last use: section
+// 4.1, the constraints on scatter); among the orders that do, the one closest to program
+// order.  A program in which a reader of the destination depends on the scatter itself has
+// no such order: it keeps program order and the check reports the reader.
+void trivial_numbering(const fc::Model &m, std::vector<int> &pi) {
+  const int n = m.n;
+  std::vector<std::vector<int>> after(n);
+  std::vector<int> waiting(n, 0);
+  auto before = [&](int a, int b) { after[a].push_back(b); ++waiting[b]; };
+  for (const fc::Edge &e : m.edges) before(e.a, e.b);
+  for (int j = 0; j < n; ++j) {
+    if (m.nodes[j].kind != FC_SCATTER) continue;
+    for (int e : m.out_edges[m.nodes[j].arg[0]])
+      if (m.edges[e].b != j) before(m.edges[e].b, j);
+  }
+  std::vector<char> placed(n, 0);
+  int next = 0;
+  for (int k = 0; k < n; ++k) {
+    int a = 0;
+    while (a < n && (placed[a] || waiting[a] != 0)) ++a;   // the first combinator in program order that is free
+    if (a == n) {                                          // a cycle through a scatter's destination
+      for (int b = 0; b < n; ++b) pi[b] = b;
+      return;
+    }
+    placed[a] = 1;
+    pi[a] = next++;
+    for (int b : after[a]) --waiting[b];
+  }
+}
+
 int load_clustering(const fc::Model &m, const fc_partition *p, fc::Clustering &c, std::string &err) {
   std::vector<int> pi(m.n);
   if (p) {
     if (p->n_nodes < m.n || (m.n && !p->pi)) { err = "partition does not cover the graph"; return FC_E_ARG; }
     for (int a = 0; a < m.n; ++a) pi[a] = p->pi[a];
   } else {
-    for (int a = 0; a < m.n; ++a) pi[a] = a;   // every combinator on its own, in program order
+    trivial_numbering(m, pi);
   }
   return fc::derive_and_check(m, pi, c, err);
 }
@@ -290,6 +322,27 @@ int fc_run_fused(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs
 
 int fc_run_unfused(const fc_graph *g, const fc_buffer *bufs, void *scratch, size_t scratch_bytes, void *hip_stream) {
   return guarded([&]() { return run_common(g, nullptr, bufs, scratch, scratch_bytes, hip_stream); });
+}
+
+int fc_check(void *scratch, void *hip_stream) {
+  return guarded([&]() {
+    if (!scratch || ((uintptr_t)scratch & 255u)) return fail(FC_E_SCRATCH, "scratch must be a 256-byte aligned device buffer");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // the control block starts with { epoch, error }: see prim.hpp, Control
+    unsigned words[2] = {0u, 0u};
+    hipError_t e = hipMemcpyAsync(words, scratch, sizeof(words), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(FC_E_HIP, hipGetErrorString(e));
+    if (words[1] == 0u) return FC_OK;
+    const unsigned zero = 0u;
+    e = hipMemcpyAsync(static_cast<char *>(scratch) + sizeof(unsigned), &zero, sizeof(zero), hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(FC_E_HIP, hipGetErrorString(e));
+    return fail(FC_E_DEVICE_WAIT,
+                "a workgroup gave up waiting for a partial result of another workgroup of its launch; the results "
+                "of the calls on this scratch buffer since the last check are invalid (launch counter " +
+                    std::to_string(words[0]) + ")");
+  });
 }
 
 int fc_cluster_kernel(const fc_graph *g, const fc_partition *p, int32_t cluster, char *name, size_t capacity) {

@@ -73,6 +73,11 @@ class DeviceProgram:
         if a.size:
             self.buffers[name][:a.size].copy_(torch.from_numpy(a))
 
+    def check(self, stream: Optional[torch.cuda.Stream] = None) -> None:
+        """fc_check on this program's scratch buffer: synchronises the stream, raises FcError if a
+        bounded wait gave up since the last check."""
+        B.fc_check(self.scratch, (stream or torch.cuda.current_stream(self.device)).cuda_stream)
+
     def control_words(self) -> np.ndarray:
         """First words of the scratch control block: launch epoch, error flag."""
         torch.cuda.synchronize(self.device)

@@ -257,3 +257,74 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert p.returncode != 0 and "one GPU" in p.stderr and p.stdout.strip() == ""
+
+
+def test_the_unfused_clustering_exists_wherever_a_clustering_does():
+    # a reader of a scatter's destination that comes after the scatter in program order: the
+    # clusters are numbered so that it still runs before the scatter (section 4.1: every other
+    # use of the destination sits in an earlier cluster)
+    n = 64
+    g = Graph()
+    g.add("dest", "input", "i32", (n,))
+    g.add("idx", "input", "i32", (n,))
+    g.add("val", "input", "i32", (n,))
+    g.add("s", "scatter", "i32", (n,), fn="add", args=("dest", "idx", "val"), output=True)
+    g.add("m", "map", "i32", (n,), fn="ident", args=("dest",), output=True)
+    assert fc.fc_plan(g, "bytes").n_clusters == 2
+    t = fc.fc_partition_trivial(g)
+    ix = g.index()
+    assert t.n_clusters == 2 and t.pi[ix["m"]] < t.pi[ix["s"]]
+    assert fc.fc_scratch_bytes(g, None) >= B.FC_SCRATCH_CONTROL_BYTES
+    # random programs with scatters: whenever fc_plan finds a clustering, the unfused one exists too,
+    # is legal, and keeps program order where no scatter forces otherwise
+    from test_chooser import random_graph
+    seen = 0
+    for seed in range(120):
+        rng = np.random.default_rng(5000 + seed)
+        g = random_graph(rng, int(rng.integers(3, 9)))
+        try:
+            fc.fc_plan(g, "reads_writes", no_split=True)
+        except fc.FcError:
+            with pytest.raises(fc.FcError):
+                fc.fc_partition_trivial(g)
+            continue
+        t = fc.fc_partition_trivial(g)
+        ops = [k for k, nd in enumerate(g.nodes) if nd.kind != "input"]
+        assert t.n_clusters == len(ops) and len({int(t.pi[k]) for k in ops}) == len(ops)
+        assert fc.fc_partition_check(g, [int(v) for v in t.pi]).n_clusters == len(ops)
+        if not any(nd.kind == "scatter" for nd in g.nodes):
+            assert [int(t.pi[k]) for k in ops] == sorted(int(t.pi[k]) for k in ops)
+        seen += any(nd.kind == "scatter" for nd in g.nodes)
+    assert seen >= 20
+
+
+def test_check_rejects_a_scratch_buffer_that_cannot_be_one():
+    # host-side argument checks only: nothing is enqueued
+    expect("FC_E_SCRATCH", fc.fc_check, (0, 0))
+    expect("FC_E_SCRATCH", fc.fc_check, (0x10000010, B.FC_SCRATCH_CONTROL_BYTES))   # not 256-byte aligned
+
+
+@pytest.mark.gpu
+def test_check_reports_and_clears_a_wait_that_gave_up():
+    # The error word is planted from the host (no kernel is made to give up a wait): fc_check
+    # must turn it into FC_E_DEVICE_WAIT once, clear it, and leave the launch counter alone,
+    # so that the scratch buffer keeps working.
+    import torch
+    from oracle.interp import evaluate
+    from paper_2407_13585_amd.device import DeviceProgram
+    w = build(4, small=True)
+    prog = DeviceProgram(w.graph, w.inputs, fc.fc_plan(w.graph, "bytes"))
+    prog.run()
+    prog.check()                                                       # a clean run: FC_OK
+    epoch = int(prog.control_words()[0])
+    assert epoch >= 1 and prog.control_words()[1] == 0
+    prog.scratch[1] = 1
+    torch.cuda.synchronize()
+    msg = expect("FC_E_DEVICE_WAIT", prog.check)
+    assert "invalid" in msg
+    assert prog.control_words().tolist()[:2] == [epoch, 0]
+    prog.check()                                                       # cleared: the next check is clean
+    prog.run()
+    prog.check()
+    env = evaluate(w.graph, w.inputs)
+    assert np.array_equal(prog.fetch("out"), env["out"]) and int(prog.fetch("count")[0]) == int(env["count"][0])

@@ -131,7 +131,7 @@ def test_nonfinite_values_are_compared_by_class(n):
             env = evaluate(g, ins)
         assert not np.all(np.isfinite(env["l"])) and not np.isfinite(env["s"][0])      # the case is not vacuous
         finite_abs = np.where(np.isfinite(x), np.abs(x), F32(0)).astype(np.float64)
-        for tag, part in (("fused", fc().fc_plan(g, "bytes")), ("unfused", None)):
+        for tag, part in (("fused", fc().fc_plan(g, "bytes", executable=True)), ("unfused", None)):
             prog = device_program(g, ins, part)
             prog.run()
             what = f"n={n} special={special} {tag}"
