@@ -244,6 +244,24 @@ int fc_scratch_bytes(const fc_graph *g, const fc_partition *p, size_t *bytes);
 int fc_run_fused(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs,
                  void *scratch, size_t scratch_bytes, void *hip_stream);
 
+/* fc_run_fused for callers that cannot allocate device memory or bring a scratch buffer:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, checks, kernels and results as fc_run_fused, but the scratch is a buffer
+ * of FC_STATIC_SCRATCH_BYTES inside the library's code object (one copy per device, zero
+ * when the library is loaded, kept until the process ends).  The call allocates nothing,
+ * on the device or through any library.  The first call on a device looks the buffer's
+ * address up (make that call outside a graph capture).
+ *
+ * Programs whose fc_scratch_bytes() exceeds FC_STATIC_SCRATCH_BYTES (manifest
+ * intermediates the caller did not bind, or a kernel workspace, too large) are refused
+ * with FC_E_LIMIT before anything is enqueued: bind the intermediates, or use fc_run_fused.
+ * All calls on one device share the one buffer: calls that overlap in time on a device
+ * (two streams, two host threads) race, as two fc_run_fused calls on one scratch buffer
+ * would.  Nothing has to be cleared between calls: words left by earlier calls carry
+ * older launch tags.  fc_check(NULL, stream) reports on this buffer. */
+#define FC_STATIC_SCRATCH_BYTES (32u << 20)
+int fc_run_fused_static(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs, void *hip_stream);
+
 /* Same program, no fusion: one kernel per combinator, every intermediate array
  * (generated index arrays included) materialised in scratch unless bound. */
 int fc_run_unfused(const fc_graph *g, const fc_buffer *bufs,
@@ -267,8 +285,9 @@ int fc_run_unfused(const fc_graph *g, const fc_buffer *bufs,
  * fc_check waits until the work enqueued on `hip_stream` has finished (it synchronises the
  * stream), reads the word, and returns FC_OK if it is zero.  Otherwise it clears the word
  * and returns FC_E_DEVICE_WAIT: every result produced with this scratch buffer since the
- * last check is to be discarded.  scratch: DEVICE, the buffer given to fc_run_*.  Allocates
- * nothing.  Errors: FC_E_SCRATCH (NULL or misaligned), FC_E_HIP. */
+ * last check is to be discarded.  scratch: DEVICE, the buffer given to fc_run_*; NULL: the
+ * buffer fc_run_fused_static uses on the current device.  Allocates nothing.
+ * Errors: FC_E_SCRATCH (misaligned), FC_E_HIP. */
 int fc_check(void *scratch, void *hip_stream);
 
 /* Name of the kernel instance chosen for cluster `cluster` of the clustering

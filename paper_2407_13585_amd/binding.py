@@ -111,7 +111,8 @@ def lib() -> C.CDLL:
     L.fc_run_unfused.argtypes = [PG, C.POINTER(fc_buffer), C.c_void_p, C.c_size_t, C.c_void_p]
     L.fc_cluster_kernel.argtypes = [PG, PP, C.c_int32, C.c_char_p, C.c_size_t]
     L.fc_check.argtypes = [C.c_void_p, C.c_void_p]
-    for f in ("fc_check", "fc_num_edges", "fc_plan", "fc_plan_weighted", "fc_plan_greedy", "fc_partition_trivial", "fc_partition_check", "fc_duplicate",
+    L.fc_run_fused_static.argtypes = [PG, PP, C.POINTER(fc_buffer), C.c_void_p]
+    for f in ("fc_check", "fc_run_fused_static", "fc_num_edges", "fc_plan", "fc_plan_weighted", "fc_plan_greedy", "fc_partition_trivial", "fc_partition_check", "fc_duplicate",
               "fc_scratch_bytes", "fc_run_fused", "fc_run_unfused", "fc_cluster_kernel"):
         getattr(L, f).restype = C.c_int
     _lib = L
@@ -346,6 +347,16 @@ def fc_run_fused(graph, partition: Partition, buffers: Dict[str, object], scratc
     _check(lib().fc_run_fused(g.ref(), C.byref(cp), _buffers(g, buffers), sp, sb, stream or None))
 
 
+FC_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def fc_run_fused_static(graph, partition: Partition, buffers: Dict[str, object], stream: int = 0) -> None:
+    """fc_run_fused in the library's own static scratch buffer (no allocation anywhere)."""
+    g = _cg(graph)
+    cp = partition._c()
+    _check(lib().fc_run_fused_static(g.ref(), C.byref(cp), _buffers(g, buffers), stream or None))
+
+
 def fc_run_unfused(graph, buffers: Dict[str, object], scratch, stream: int = 0) -> None:
     g = _cg(graph)
     sp, sb = _scratch(scratch)
@@ -378,8 +389,8 @@ class BoundRun:
 def fc_check(scratch, stream: int = 0) -> None:
     """Synchronises `stream` and raises FcError (FC_E_DEVICE_WAIT) if a kernel that used `scratch`
     gave up a bounded wait since the last check."""
-    sp, _ = _scratch(scratch)
-    _check(lib().fc_check(sp, stream or None))
+    sp = _scratch(scratch)[0] if scratch is not None else None
+    _check(lib().fc_check(sp or None, stream or None))
 
 
 def fc_cluster_kernel(graph, partition: Optional[Partition], cluster: int) -> str:

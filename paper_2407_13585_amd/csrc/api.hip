@@ -1,6 +1,6 @@
 // extern "C" entry points (include/fc.h).  Argument checking and marshalling
 // only; no exception leaves this file.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstring>
@@ -14,9 +14,38 @@
 #include "plan.hpp"
 #include "run.hpp"
 
+// Scratch of fc_run_fused_static: one copy per device, zero when the code object is
+// loaded (which is what the control block at its start needs the first time), held until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the
+// memory is reached through the address that call returns (static_scratch_of below).
+static __device__ __align__(256) unsigned char static_scratch[FC_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_error;
+
+// Address of the current device's copy of static_scratch, looked up once per device.
+constexpr int kMaxDevices = 64;
+int static_scratch_of(void **out, std::string &err) {
+  static std::mutex mu;
+  static void *known[kMaxDevices];                 // zero-initialised: not looked up yet
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { err = std::string("hipGetDevice: ") + hipGetErrorString(e); return FC_E_HIP; }
+  if (dev < 0 || dev >= kMaxDevices) { err = "device ordinal " + std::to_string(dev) + " is out of range"; return FC_E_LIMIT; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!known[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_scratch));
+    if (e != hipSuccess || !ptr) {
+      err = std::string("hipGetSymbolAddress(static_scratch): ") + hipGetErrorString(e);
+      return FC_E_HIP;
+    }
+    known[dev] = ptr;
+  }
+  *out = known[dev];
+  return FC_OK;
+}
 
 int fail(int code, const std::string &msg) {
   g_error = msg;
@@ -260,8 +289,9 @@ struct Prepared {
   std::shared_ptr<const fc::PreparedRun> run;
 };
 
+// use_static: run in the device's static scratch array instead of a buffer of the caller
 static int run_common(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs, void *scratch,
-                      size_t scratch_bytes, void *hip_stream) {
+                      size_t scratch_bytes, void *hip_stream, bool use_static = false) {
   static std::mutex mu;
   static std::vector<Prepared> cache;        // most recently used first
   if (!g || g->n < 0 || (g->n > 0 && !g->nodes)) return fail(FC_E_ARG, "null graph");
@@ -302,10 +332,19 @@ static int run_common(const fc_graph *g, const fc_partition *p, const fc_buffer 
     if (rc != FC_OK) return fail(rc, err);
     rc = fc::prepare_run(*fresh, err);
     if (rc != FC_OK) return fail(rc, err);
+    fresh->scratch_need = fc::scratch_bytes_for(fresh->model, fresh->clustering);
     run = fresh;
     std::lock_guard<std::mutex> lock(mu);
     cache.insert(cache.begin(), Prepared{key, run});
     if (cache.size() > 32) cache.pop_back();
+  }
+  if (use_static) {
+    if (run->scratch_need > (size_t)FC_STATIC_SCRATCH_BYTES)
+      return fail(FC_E_LIMIT, "the program needs " + std::to_string(run->scratch_need) + " bytes of scratch, the static buffer holds " +
+                                  std::to_string((size_t)FC_STATIC_SCRATCH_BYTES) + ": use fc_run_fused with a buffer of the caller");
+    int rc = static_scratch_of(&scratch, err);
+    if (rc != FC_OK) return fail(rc, err);
+    scratch_bytes = FC_STATIC_SCRATCH_BYTES;
   }
   int rc = fc::run_prepared(*run, bufs, scratch, scratch_bytes, static_cast<hipStream_t>(hip_stream), err);
   if (rc != FC_OK) return fail(rc, err);
@@ -320,13 +359,25 @@ int fc_run_fused(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs
   });
 }
 
+int fc_run_fused_static(const fc_graph *g, const fc_partition *p, const fc_buffer *bufs, void *hip_stream) {
+  return guarded([&]() {
+    if (!p) return fail(FC_E_ARG, "null partition");
+    return run_common(g, p, bufs, nullptr, 0, hip_stream, true);
+  });
+}
+
 int fc_run_unfused(const fc_graph *g, const fc_buffer *bufs, void *scratch, size_t scratch_bytes, void *hip_stream) {
   return guarded([&]() { return run_common(g, nullptr, bufs, scratch, scratch_bytes, hip_stream); });
 }
 
 int fc_check(void *scratch, void *hip_stream) {
   return guarded([&]() {
-    if (!scratch || ((uintptr_t)scratch & 255u)) return fail(FC_E_SCRATCH, "scratch must be a 256-byte aligned device buffer");
+    if (!scratch) {                       // the buffer fc_run_fused_static uses on the current device
+      std::string err;
+      int rc = static_scratch_of(&scratch, err);
+      if (rc != FC_OK) return fail(rc, err);
+    }
+    if ((uintptr_t)scratch & 255u) return fail(FC_E_SCRATCH, "scratch must be a 256-byte aligned device buffer");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     // the control block starts with { epoch, error }: see prim.hpp, Control
     unsigned words[2] = {0u, 0u};

@@ -40,6 +40,7 @@ struct PreparedRun {
   Model model;
   Clustering clustering;
   std::vector<ClusterLaunch> launches;
+  size_t scratch_need = 0;             // scratch_bytes_for(model, clustering)
 };
 
 int prepare_run(PreparedRun &r, std::string &err);
