@@ -99,6 +99,13 @@ typedef enum fc_fn {
 
 /* node flags */
 #define FC_NODE_OUTPUT 1u   /* a result of the program: must be manifest (m = 0) */
+#define FC_NODE_SINGLE_PASS 2u /* on a fold or foldSeg node: its cluster must run as ONE pass over the arrays it reads,
+                                  every gather issued at the position that asks for it (section 2: a fold inside a
+                                  cluster is one stage of a parallel reduction).  Without the flag the library may, for
+                                  a gathered table larger than the L2 of an XCD, run a kernel that visits the positions
+                                  in another order (indices sorted by table range in a first kernel; the streams of
+                                  a segmented fold read once per column range), which is faster and, the reducers
+                                  being commutative, gives the same result up to rounding */
 
 typedef struct fc_node {
   int32_t  kind;              /* fc_kind  */

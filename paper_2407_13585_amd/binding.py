@@ -33,6 +33,7 @@ FC_PLAN_NO_SPLIT = 1
 FC_PLAN_EXECUTABLE = 2
 FC_PLAN_ANYTIME = 4
 FC_NODE_OUTPUT = 1
+FC_NODE_SINGLE_PASS = 2
 
 ERRORS = {-1: "FC_E_BADGRAPH", -2: "FC_E_ILLEGAL_PARTITION", -3: "FC_E_UNSUPPORTED", -4: "FC_E_UNBOUND",
           -5: "FC_E_SCRATCH", -6: "FC_E_HIP", -7: "FC_E_ARG", -8: "FC_E_LIMIT", -9: "FC_E_DEVICE_WAIT"}
@@ -154,7 +155,7 @@ class CGraph:
             c.rank = len(n.shape)
             c.shape[0] = int(n.shape[0])
             c.shape[1] = int(n.shape[1]) if len(n.shape) == 2 else 1
-            c.flags = FC_NODE_OUTPUT if n.output else 0
+            c.flags = (FC_NODE_OUTPUT if n.output else 0) | (FC_NODE_SINGLE_PASS if getattr(n, "single_pass", False) else 0)
             c.infusible_args = sum(1 << k for k in getattr(n, "infusible", ()))
         self.c = fc_graph(len(graph.nodes), self.nodes)
         self.n_edges = len(graph.edges())
@@ -308,7 +309,8 @@ def fc_duplicate(graph: Graph) -> Tuple[Graph, List[int]]:
         new.add(name, base.kind, base.dtype, base.shape,
                 fn=base.fn, fparam=base.fparam, iparam=base.iparam,
                 args=tuple(new_names[out[i].arg[j]] for j in range(out[i].nargs)),
-                output=bool(out[i].flags & FC_NODE_OUTPUT), infusible=base.infusible)
+                output=bool(out[i].flags & FC_NODE_OUTPUT), infusible=base.infusible,
+                single_pass=bool(out[i].flags & FC_NODE_SINGLE_PASS))
     return new, [origin[i] for i in range(n.value)]
 
 

@@ -91,7 +91,9 @@ struct KArgs {    // arguments of one cluster launch
   Slot p[kMaxSlots];
   Code code[kMaxCode];      // kCodeEnd after the last instruction
   unsigned char root[kMaxRoots];   // where element program K of a cluster with another consumer starts in `code`
+  unsigned flags;           // kSinglePass: a fold of the cluster carries FC_NODE_SINGLE_PASS
 };
+constexpr unsigned kSinglePass = 1u;
 
 template <class T> struct Vec4 { T v[4]; };
 

@@ -81,7 +81,7 @@ template <int KT> size_t blocked_table_bytes(const KArgs &a) {
 template <int KT> bool foldseg_blocked_accept(const KArgs &a) {
   const size_t table = blocked_table_bytes<KT>(a);
   const size_t units = ((size_t)a.aux + kBlockedRows - 1) / kBlockedRows;
-  return a.n > 0 && (unsigned long long)a.n * 4 < (1ull << 31) && table > kL2Bytes && table <= kQuarters * kL2Bytes && units >= 64 &&
+  return !(a.flags & kSinglePass) && a.n > 0 && (unsigned long long)a.n * 4 < (1ull << 31) && table > kL2Bytes && table <= kQuarters * kL2Bytes && units >= 64 &&
          units * kQuarters <= kMaxTiles;
 }
 size_t foldseg_blocked_workspace(const KArgs &a) { return (size_t)kQuarters * (size_t)a.aux * sizeof(unsigned long long); }
@@ -109,7 +109,7 @@ template <class E> bool fold_binned_accept(const KArgs &a) {
   // Below two million positions the direct kernel is over before two launches would be.  Up to
   // 64 MiB the ranges are half an L2 or less; measured at 2^24 positions: 64 MiB 124 us (direct
   // 307), 128 MiB 132 us (319), 256 MiB, where half of a range fits, 201 us (326).
-  return a.n >= (1 << 21) && bytes > kL2Bytes && bytes <= kBins * (kL2Bytes * 2) &&
+  return !(a.flags & kSinglePass) && a.n >= (1 << 21) && bytes > kL2Bytes && bytes <= kBins * (kL2Bytes * 2) &&
          binned_tiles(a) * kBins * kBinCap * sizeof(int) < (1ull << 31);
 }
 size_t fold_binned_workspace(const KArgs &a) { return binned_counts_bytes(a) + binned_tiles(a) * kBins * kBinCap * sizeof(int); }

@@ -346,6 +346,8 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
   out.args.h = out.h;
   out.args.w = out.w;
   out.args.aux = out.aux;
+  for (int a : folds) if (m.nodes[a].flags & FC_NODE_SINGLE_PASS) out.args.flags |= kSinglePass;
+  for (int a : foldsegs) if (m.nodes[a].flags & FC_NODE_SINGLE_PASS) out.args.flags |= kSinglePass;
   out.externals = b.externals;
   const Instance *inst = find_instance(sig, out.args);
   if (!inst && !any.empty() && b.code_ok && b.on_stack == 0) inst = find_instance(any, out.args);

@@ -2,7 +2,7 @@
 
 Data only: no combinator is evaluated and no partition is chosen in this package.
 """
-from .graph import Graph, Node
+from .graph import Graph, Node, single_pass
 from .configs import Workload, build, BUILDERS, SMALL, SEED0
 
-__all__ = ["Graph", "Node", "Workload", "build", "BUILDERS", "SMALL", "SEED0"]
+__all__ = ["Graph", "Node", "single_pass", "Workload", "build", "BUILDERS", "SMALL", "SEED0"]

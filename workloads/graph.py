@@ -53,6 +53,7 @@ class Node:
     args: Tuple[str, ...] = ()
     output: bool = False          # a result of the program: must be manifest
     infusible: Tuple[int, ...] = ()   # argument positions reached through `!`, force or foreign code
+    single_pass: bool = False     # fold / foldseg: the cluster must be one pass over its arrays, gathers in position order
 
     def __post_init__(self):
         if self.kind not in KINDS:
@@ -111,3 +112,9 @@ class Graph:
 
 def names(nodes: Sequence[Node]) -> List[str]:
     return [n.name for n in nodes]
+
+
+def single_pass(graph: Graph) -> Graph:
+    """The same program with every fold / foldseg marked `single_pass`."""
+    from dataclasses import replace
+    return Graph([replace(n, single_pass=True) if n.kind in ("fold", "foldseg") else n for n in graph.nodes])
