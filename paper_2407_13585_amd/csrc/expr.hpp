@@ -12,6 +12,9 @@
 //   sig(std::string&) the textual signature the host matcher compares against
 //   kNodes            number of combinator nodes in the tree (parameter slots)
 //   kMirror           the tree reads an array through `reverse` as well (tile order, kernels.hpp)
+//   eval4_pair(args, i, ip, at_i, at_ip)   values at the 128-bit groups i and ip, where ip is
+//                     the mirror image of i (ip = n - 4 - i); see for_each_mirrored_pair
+//   mirrors_whole(args, n)   every `reverse` of the tree runs over exactly n elements
 // Parameter slots are numbered in pre-order, leaves included.
 #pragma once
 
@@ -91,9 +94,12 @@ struct KArgs {    // arguments of one cluster launch
   Slot p[kMaxSlots];
   Code code[kMaxCode];      // kCodeEnd after the last instruction
   unsigned char root[kMaxRoots];   // where element program K of a cluster with another consumer starts in `code`
-  unsigned flags;           // kSinglePass: a fold of the cluster carries FC_NODE_SINGLE_PASS
+  unsigned flags;           // kSinglePass: a fold of the cluster carries FC_NODE_SINGLE_PASS;
+                            // kKeepOut << k: out[k] is read back by a later cluster of the program
+  __host__ __device__ bool keeps(int k) const { return (flags >> (8 + k)) & 1u; }
 };
 constexpr unsigned kSinglePass = 1u;
+constexpr unsigned kKeepOut = 1u << 8;
 
 template <class T> struct Vec4 { T v[4]; };
 
@@ -184,6 +190,12 @@ struct In {
     V v = __builtin_nontemporal_load(reinterpret_cast<const V *>(static_cast<const T *>(a.in[K]) + i));
     return Vec4<T>{{v.x, v.y, v.z, v.w}};
   }
+  template <int Base>
+  static __device__ __forceinline__ void eval4_pair(const KArgs &a, int i, int ip, Vec4<T> &at_i, Vec4<T> &at_ip) {
+    at_i = eval4<Base>(a, i);
+    at_ip = eval4<Base>(a, ip);
+  }
+  template <int Base> static __device__ __forceinline__ bool mirrors_whole(const KArgs &, int) { return true; }
   static void sig(std::string &s) { s += "in" + std::to_string(K) + ":" + DtypeName<T>::s(); }
 };
 
@@ -216,6 +228,28 @@ struct Map {
   template <int Base> static __device__ __forceinline__ Vec4<R> eval4(const KArgs &a, int i) {
     return eval4_<Base>(a, i, std::make_integer_sequence<int, sizeof...(E)>());
   }
+  template <int Base, int... K>
+  static __device__ __forceinline__ void eval4_pair_(const KArgs &a, int i, int ip, Vec4<R> &at_i, Vec4<R> &at_ip,
+                                                     std::integer_sequence<int, K...>) {
+    std::tuple<Vec4<typename E::R>...> x, xp;
+    (E::template eval4_pair<ChildBase<Base + 1, K, E...>::value>(a, i, ip, std::get<K>(x), std::get<K>(xp)), ...);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      at_i.v[c] = F::apply(a.p[Base], std::get<K>(x).v[c]...);
+      at_ip.v[c] = F::apply(a.p[Base], std::get<K>(xp).v[c]...);
+    }
+  }
+  template <int Base>
+  static __device__ __forceinline__ void eval4_pair(const KArgs &a, int i, int ip, Vec4<R> &at_i, Vec4<R> &at_ip) {
+    eval4_pair_<Base>(a, i, ip, at_i, at_ip, std::make_integer_sequence<int, sizeof...(E)>());
+  }
+  template <int Base, int... K>
+  static __device__ __forceinline__ bool mirrors_whole_(const KArgs &a, int n, std::integer_sequence<int, K...>) {
+    return (E::template mirrors_whole<ChildBase<Base + 1, K, E...>::value>(a, n) && ... && true);
+  }
+  template <int Base> static __device__ __forceinline__ bool mirrors_whole(const KArgs &a, int n) {
+    return mirrors_whole_<Base>(a, n, std::make_integer_sequence<int, sizeof...(E)>());
+  }
   static void sig(std::string &s) {
     s += "map" + std::to_string(F::kFn) + "(";
     bool first = true;
@@ -240,6 +274,12 @@ struct Gen {
     for (int c = 0; c < 4; ++c) r.v[c] = G::apply(a.p[Base], a, i + c);
     return r;
   }
+  template <int Base>
+  static __device__ __forceinline__ void eval4_pair(const KArgs &a, int i, int ip, Vec4<int> &at_i, Vec4<int> &at_ip) {
+    at_i = eval4<Base>(a, i);
+    at_ip = eval4<Base>(a, ip);
+  }
+  template <int Base> static __device__ __forceinline__ bool mirrors_whole(const KArgs &, int) { return true; }
   static void sig(std::string &s) { s += "gen" + std::to_string(G::kFn); }
 };
 
@@ -250,6 +290,11 @@ struct AlwaysOne {
   static constexpr bool kMirror = false;
   template <int Base, bool Stream = false> static __device__ __forceinline__ int eval(const KArgs &, int) { return 1; }
   template <int Base> static __device__ __forceinline__ Vec4<int> eval4(const KArgs &, int) { return Vec4<int>{{1, 1, 1, 1}}; }
+  template <int Base>
+  static __device__ __forceinline__ void eval4_pair(const KArgs &, int, int, Vec4<int> &at_i, Vec4<int> &at_ip) {
+    at_i = at_ip = Vec4<int>{{1, 1, 1, 1}};
+  }
+  template <int Base> static __device__ __forceinline__ bool mirrors_whole(const KArgs &, int) { return true; }
   static void sig(std::string &s) { s += "1"; }
 };
 
@@ -269,6 +314,15 @@ struct Gather {
 #pragma unroll
     for (int c = 0; c < 4; ++c) r.v[c] = ES::template eval<Base + 1 + EI::kNodes>(a, j.v[c]);
     return r;
+  }
+  template <int Base>
+  static __device__ __forceinline__ void eval4_pair(const KArgs &a, int i, int ip, Vec4<R> &at_i, Vec4<R> &at_ip) {
+    at_i = eval4<Base>(a, i);
+    at_ip = eval4<Base>(a, ip);
+  }
+  // a `reverse` below an arbitrary gather is evaluated at gathered positions: it pairs with nothing
+  template <int Base> static __device__ __forceinline__ bool mirrors_whole(const KArgs &a, int n) {
+    return EI::template mirrors_whole<Base + 1>(a, n) && !ES::kMirror;
   }
   static void sig(std::string &s) {
     s += "gather(";
@@ -304,6 +358,21 @@ struct Gather<Gen<GenIotaRev>, ES> {
       for (int c = 0; c < 4; ++c) r.v[c] = ES::template eval<Base + 1 + EI::kNodes>(a, total - 1 - (i + c));
     }
     return r;
+  }
+  // Over exactly n elements (mirrors_whole, n a multiple of four) the group that `reverse` reads
+  // for position i is the one at ip taken backwards, and the other way round: the source is
+  // evaluated at the same two groups as a direct read of it, with the roles swapped, so that the
+  // reads of an array which the program takes forwards and backwards coincide (same addresses in
+  // the same registers: each is issued once).
+  template <int Base>
+  static __device__ __forceinline__ void eval4_pair(const KArgs &a, int i, int ip, Vec4<R> &at_i, Vec4<R> &at_ip) {
+    Vec4<R> v, vp;
+    ES::template eval4_pair<Base + 1 + EI::kNodes>(a, ip, i, v, vp);     // v: source at ip, vp: source at i
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { at_i.v[c] = v.v[3 - c]; at_ip.v[c] = vp.v[3 - c]; }
+  }
+  template <int Base> static __device__ __forceinline__ bool mirrors_whole(const KArgs &a, int n) {
+    return a.p[Base + 1].ext[0] * a.p[Base + 1].ext[1] == n && ES::template mirrors_whole<Base + 1 + EI::kNodes>(a, n);
   }
   static void sig(std::string &s) {
     s += "gather(";

@@ -348,6 +348,8 @@ int plan_cluster(const Model &m, const Clustering &c, const std::vector<int> &me
   out.args.aux = out.aux;
   for (int a : folds) if (m.nodes[a].flags & FC_NODE_SINGLE_PASS) out.args.flags |= kSinglePass;
   for (int a : foldsegs) if (m.nodes[a].flags & FC_NODE_SINGLE_PASS) out.args.flags |= kSinglePass;
+  for (int k = 0; k < kMaxOut; ++k)
+    if (out.out_nodes[k] >= 0 && !m.out_edges[out.out_nodes[k]].empty()) out.args.flags |= kKeepOut << k;
   out.externals = b.externals;
   const Instance *inst = find_instance(sig, out.args);
   if (!inst && !any.empty() && b.code_ok && b.on_stack == 0) inst = find_instance(any, out.args);
