@@ -134,7 +134,7 @@ struct FnModEq { using R = int; static constexpr int kFn = FC_FN_MOD_EQ;
     const unsigned t = (unsigned)x - (unsigned)s.i[1];
     const unsigned p = t * s.m[0];
     const unsigned q = __builtin_amdgcn_alignbit(p, p, s.m[1]);     // rotate right
-    return ((unsigned)x >= (unsigned)s.i[1] && q <= s.m[2]) ? 1 : 0; } };
+    return (int)((unsigned)((unsigned)x >= (unsigned)s.i[1]) & (unsigned)(q <= s.m[2])); } };   // no branch: both tests always
 
 // i / d for 0 <= i < 2^31 and a divisor that is fixed for the launch, without a
 // division: with L = ceil(log2 d) and M = ceil(2^(31+L) / d) < 2^32 the quotient is

@@ -1117,20 +1117,33 @@ template <class F, class EV> struct FlagOfValue<Map<F, EV>, EV> {
   static __device__ __forceinline__ int apply(const KArgs &a, typename EV::R v) { return F::apply(a.p[0], v); }
 };
 
+// Two tagged words (16-byte aligned) in one 128-bit read at agent scope: a read marked sc1
+// does not take a line from this XCD's L2, which may hold the words of an earlier launch, but
+// goes where the agent-scope stores of the other workgroups went.  Each 64-bit word was written
+// by one store and is validated by its own tag, so the two need not be read atomically together.
+using TaggedPair = unsigned long long __attribute__((ext_vector_type(2)));
+// `base` is the same for the whole wave (it becomes a buffer descriptor), `k` is the lane's word.
+__device__ __forceinline__ TaggedPair load_tagged_pair(const unsigned long long *base, unsigned k) {
+  using Raw = int __attribute__((ext_vector_type(4)));
+  constexpr int kAgentScope = 0x10;                 // cache policy of the buffer load: sc1
+  const __amdgpu_buffer_rsrc_t words =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned long long *>(base), 0, 0x7fffffff, 0x00020000);
+  const Raw r = __builtin_amdgcn_raw_buffer_load_b128(words, (int)(k * 8u), 0, kAgentScope);
+  return __builtin_bit_cast(TaggedPair, r);
+}
+
 // Sum of the values of `count` tagged words starting at p (16-byte aligned), this
 // thread's share.  Words are written once per launch, so a word that carries the
-// launch's tag is final whichever cache it came from: the fast path reads pairs of
-// words with ordinary cached, coalesced loads; a word that does not validate (not
-// yet published, or a stale line in this XCD's caches) is re-read at agent scope
-// until it does.  Agent-scope loads go to memory one lane at a time, so they are
-// kept for the few words that need them.
+// launch's tag is final: the fast path reads pairs of words with wide agent-scope
+// loads, coalesced over the lanes; a word that does not validate (not yet
+// published) is polled until it does.
 template <int Threads = kScanBlock, class T = int>
 __device__ __forceinline__ T sum_tagged_words(const unsigned long long *p, unsigned count, unsigned tag,
                                               Control *ctl) {
-  using Pair = unsigned long long __attribute__((ext_vector_type(2)));
+  using Pair = TaggedPair;
   T sum = T();
   for (unsigned k = 2 * (threadIdx.x % Threads); k < count; k += 2 * Threads) {
-    Pair w = *reinterpret_cast<const Pair *>(p + k);
+    Pair w = load_tagged_pair(p, k);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       if (k + j >= count) break;
@@ -1144,12 +1157,12 @@ __device__ __forceinline__ T sum_tagged_words(const unsigned long long *p, unsig
 }
 
 // The same sum with the reads split from their use: the constructor issues this
-// thread's first Pairs reads (cached, coalesced) of the range, sum() validates
+// thread's first Pairs reads of the range, sum() validates
 // them and goes on with sum_tagged_words for whatever lies beyond.  Two ranges
 // constructed back to back have their reads in flight together.
 template <int Threads, int Pairs>
 struct TaggedPairs {
-  using Pair = unsigned long long __attribute__((ext_vector_type(2)));
+  using Pair = TaggedPair;
   const unsigned long long *p;
   unsigned count;
   Pair w[Pairs];
@@ -1158,7 +1171,7 @@ struct TaggedPairs {
     for (int u = 0; u < Pairs; ++u) {
       const unsigned k = 2 * (threadIdx.x % Threads) + u * 2 * Threads;
       w[u] = Pair{0ull, 0ull};
-      if (k < count) w[u] = *reinterpret_cast<const Pair *>(p + k);
+      if (k < count) w[u] = load_tagged_pair(p, k);
     }
   }
   __device__ __forceinline__ int sum(unsigned tag, Control *ctl) const {
@@ -1280,7 +1293,7 @@ __global__ __launch_bounds__(kScanBlock, 8) void scan_kernel(const KArgs a, Cont
   __shared__ V parked[kParkCap];
   const unsigned n = (unsigned)a.n;
   const int lane = lane_id(), wave = wave_id();
-  const unsigned epoch = load_agent(&ctl->epoch);
+  const unsigned epoch = epoch_at_start(ctl);
   const unsigned tag = tag_of_epoch(epoch);
   unsigned long long *group_word = status + ((n_tiles + 15) / 16) * 16;
 
@@ -1484,7 +1497,7 @@ __global__ __launch_bounds__(kScanBlock) void scan_f32_kernel(const KArgs a, Con
   __shared__ float lds_sum[kScanWaves];
   const unsigned n = (unsigned)a.n;
   const int lane = lane_id(), wave = wave_id();
-  const unsigned epoch = load_agent(&ctl->epoch);
+  const unsigned epoch = epoch_at_start(ctl);
   const unsigned tag = tag_of_epoch(epoch);
   unsigned long long *group_word = status + ((n_tiles + 15) / 16) * 16;
   float *offs = static_cast<float *>(a.out[1]);

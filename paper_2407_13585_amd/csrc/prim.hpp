@@ -160,6 +160,16 @@ constexpr size_t kStatusOffset = kPartialsOffset + kMaxPartials * sizeof(unsigne
 constexpr size_t kMaxTiles = (FC_SCRATCH_CONTROL_BYTES - kStatusOffset) / sizeof(unsigned long long);
 constexpr unsigned kSpinLimit = 1u << 22;          // polls before a wait gives up: never hang the device
 
+// `epoch` read at the very start of a kernel, with an ordinary load.  The word changes only once
+// every workgroup of the launch has taken its tag from it (the workgroup that advances it has
+// seen a tagged word of all others), and the kernel boundary before the launch makes the store
+// of the launch before visible, so the value is the same as an agent-scope load's.  The
+// difference is where it travels: a uniform ordinary load goes through the scalar unit and
+// returns on its own counter, whereas an agent-scope load is a vector memory operation, and
+// the wait for it (a round trip to memory) would stand in front of the kernel's first reads
+// (single-pass compaction of 2^26 elements: every tile issued its reads a round trip late).
+__device__ __forceinline__ unsigned epoch_at_start(const Control *ctl) { return ctl->epoch; }
+
 __device__ __forceinline__ unsigned tag_of_epoch(unsigned epoch) { return epoch % 0x3ffffffeu + 1u; }  // 30 bits, never 0
 
 // word = value (high 32 bits) | tag << 2 | state (low 2 bits, 0 = not ready)
