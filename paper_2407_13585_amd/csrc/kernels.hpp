@@ -928,7 +928,7 @@ __global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, 
         }
         v = Op::apply(v, part);
       }
-      y[r] = v;
+      __builtin_nontemporal_store(v, y + r);     // a result: written once, and nothing but the table should settle in L2
     }
   };
 
