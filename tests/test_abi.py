@@ -327,3 +327,17 @@ def test_check_reports_and_clears_a_wait_that_gave_up():
     prog.check()
     env = evaluate(w.graph, w.inputs)
     assert np.array_equal(prog.fetch("out"), env["out"]) and int(prog.fetch("count")[0]) == int(env["count"][0])
+
+
+def test_single_pass_flag_selects_the_kernel_that_keeps_position_order():
+    # host only: the matcher's choice for the two gather pipelines at their benchmark sizes
+    from workloads import single_pass
+    for cfg, variant in ((2, "binned"), (3, "column-blocked")):
+        w = build(cfg)
+        default = fc.fc_plan(w.graph, "bytes")
+        assert variant in fc.fc_cluster_kernel(w.graph, default, 0)
+        g = single_pass(w.graph)
+        marked = fc.fc_plan(g, "bytes")
+        assert marked.n_clusters == 1 and "{" not in fc.fc_cluster_kernel(g, marked, 0)
+        # the single pass needs no workspace beyond the control block
+        assert fc.fc_scratch_bytes(g, marked) < fc.fc_scratch_bytes(w.graph, default)

@@ -289,6 +289,34 @@ def test_perm_gather_binned(table, m, spread):
     run_all_modes(2, w, env)
 
 
+def test_single_pass_flag_keeps_the_gathers_in_position_order():
+    # FC_NODE_SINGLE_PASS on the fold: the cluster runs as one pass with every gather issued at the
+    # position that asks for it, also where the library would by default sort the indices by table
+    # range (fold) or read the streams once per column range (segmented fold).  Same oracle, same bounds.
+    from workloads import single_pass
+    rng = np.random.default_rng(91)
+    table, m = 3000017, (1 << 21) + 77
+    w = C.perm_gather_fold(xs=rng.standard_normal(size=table).astype(F32), idx=rng.integers(0, table, size=m, dtype=np.int32))
+    env = evaluate(w.graph, w.inputs)
+    for marked, variant in ((False, "binned"), (True, None)):
+        g = single_pass(w.graph) if marked else w.graph
+        g, part = plan(g, False)
+        prog = device_program(g, w.inputs, part)
+        assert (variant in prog.kernels()[0]) if variant else ("{" not in prog.kernels()[0]), prog.kernels()
+        prog.run()
+        compare(2, w, env, prog, w.graph.outputs(), "single-pass" if marked else "default")
+    lengths = rng.poisson(6.0, size=40000)
+    w = C.spmv(lengths=lengths, seed=92, ncols=2500000)
+    env = evaluate(w.graph, w.inputs)
+    for marked, variant in ((False, "column-blocked"), (True, None)):
+        g = single_pass(w.graph) if marked else w.graph
+        g, part = plan(g, True)                               # the flag survives the duplication rewrite
+        prog = device_program(g, w.inputs, part)
+        assert (variant in prog.kernels()[0]) if variant else ("{" not in prog.kernels()[0]), prog.kernels()
+        prog.run()
+        compare(3, w, env, prog, w.graph.outputs(), "single-pass" if marked else "default")
+
+
 @pytest.mark.parametrize("table,m", [(1048600, 1 << 21), ((1 << 24), (1 << 21) + 8192), (5000000, (1 << 21) + 4096),
                                      (1234567, (1 << 21) + 4100), ((1 << 25) + 5, (1 << 21) + 1)])
 def test_perm_gather_binned_sizes(table, m):
