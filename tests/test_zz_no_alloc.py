@@ -67,3 +67,55 @@ def test_static_scratch_refuses_programs_that_need_more():
     with pytest.raises(fc.FcError) as e:
         fc.fc_run_fused_static(g, part, {"x": fake, "z": fake, "r": fake})
     assert e.value.name == "FC_E_LIMIT" and "static" in str(e.value)
+
+
+def test_static_scratch_runs_replay_from_a_hip_graph():
+    # what the entry point is for: a step captured into a HIP graph (no allocation may happen under
+    # capture).  The first calls are made outside the capture (the buffer's address is looked up
+    # then); every replay runs on other input values and is checked against the oracle.
+    import torch
+    import paper_2407_13585_amd as fc
+    from oracle.interp import evaluate
+    from paper_2407_13585_amd.device import DeviceProgram
+    from workloads import build
+    rng = np.random.default_rng(5)
+    items = []
+    for cfg in (1, 2, 3, 4, 5):
+        w = build(cfg, small=True)
+        g, _ = fc.fc_duplicate(w.graph)
+        part = fc.fc_plan(g, "bytes")
+        items.append((cfg, w, g, part, DeviceProgram(g, w.inputs, part)))     # the tensors only
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for cfg, w, g, part, prog in items:
+            fc.fc_run_fused_static(g, part, prog.buffers, side.cuda_stream)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for cfg, w, g, part, prog in items:
+            fc.fc_run_fused_static(g, part, prog.buffers, torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        for cfg, w, g, part, prog in items:
+            for name, a in list(w.inputs.items()):
+                if a.dtype == F32:
+                    w.inputs[name] = (a * F32(0.5) + rng.uniform(-0.1, 0.1, size=a.shape).astype(F32)).astype(F32)
+                prog.upload(name, w.inputs[name])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        fc.fc_check(None, 0)
+        for cfg, w, g, part, prog in items:
+            env = evaluate(w.graph, w.inputs)
+            for o in w.graph.outputs():
+                got, ref = prog.fetch(o), env[o]
+                what = f"{w.name} replay {rep} {o}"
+                if g[o].dtype == "i32":
+                    P.assert_bit_exact(got, ref, what)
+                elif g[o].kind == "fold" and g[o].fn == "add":
+                    P.assert_fold(got, ref, what)
+                elif g[o].kind == "foldseg":
+                    P.assert_segmented(got, ref, env["p"], w.inputs["off"], what)
+                elif g[o].kind == "fold":                                  # max of exp(-x): within 4 ulp
+                    P.assert_ulp(got, np.asarray(ref, dtype=np.float64).astype(F32), 4, what)
+                else:
+                    P.assert_close(got, ref, 1e-6, what)
