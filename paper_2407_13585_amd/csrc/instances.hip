@@ -116,6 +116,15 @@ std::vector<Instance> build_registry() {
   // ---- fused clusters ----
   r.push_back(fold_<AddF32, ReverseDot>());
   {
+    // the gathered table does not fit one L2 but its ranges fit LDS: indices binned by range, gathers from LDS (first match wins)
+    Instance fine = fold_<AddF32, PermGather>();
+    fine.launch = &launch_fold_fine<AddF32, PermGather>;
+    fine.accept = &fold_fine_accept<PermGather>;
+    fine.workspace = &fold_fine_workspace<PermGather>;
+    fine.variant = "binned, table ranges in LDS";
+    r.push_back(fine);
+  }
+  {
     // the gathered table does not fit one L2: indices binned by table range first (first match wins)
     Instance binned = fold_<AddF32, PermGather>();
     binned.launch = &launch_fold_binned<AddF32, PermGather>;

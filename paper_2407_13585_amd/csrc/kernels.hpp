@@ -218,24 +218,24 @@ __global__ __launch_bounds__(kBlock) void store2_kernel(const KArgs a) {
 // scheduling.  fold is one stage of a multi-stage parallel reduction (section 2, fold).
 // `earlier` partials, at the front of `partials`, were left there under the same tag
 // by a kernel that ran before this one on the stream; they are combined first.
-template <class Op>
+template <class Op, int Waves = kWavesPerBlock>
 __device__ __forceinline__ void fold_finish(typename Op::T acc, const KArgs &a, int out_slot, Control *ctl,
                                             unsigned long long *partials, unsigned earlier = 0) {
   using T = typename Op::T;
-  __shared__ T lds[kWavesPerBlock + 1];
+  __shared__ T lds[Waves + 1];
   const unsigned epoch = load_agent(&ctl->epoch);
   const unsigned tag = tag_of_epoch(epoch);
-  T r = block_reduce<Op>(acc, lds);
+  T r = block_reduce<Op, Waves>(acc, lds);
   if (threadIdx.x == 0) store_agent64(&partials[earlier + blockIdx.x], pack_word((unsigned)as_bits(r), tag, 1u));
   // the workgroup with the highest index is dispatched last; it waits for the
   // partials of all others and combines them in index order
   if (blockIdx.x == gridDim.x - 1) {
     T s = Op::identity();
-    for (unsigned k = threadIdx.x; k < earlier + gridDim.x; k += kBlock) {
+    for (unsigned k = threadIdx.x; k < earlier + gridDim.x; k += Waves * kWave) {
       unsigned long long w = wait_word(&partials[k], tag, ctl);
       s = Op::apply(s, w ? from_bits<T>((int)(unsigned)(w >> 32)) : Op::identity());
     }
-    s = block_reduce<Op>(s, lds);
+    s = block_reduce<Op, Waves>(s, lds);
     if (threadIdx.x == 0) {
       *static_cast<T *>(a.out[out_slot]) = s;
       store_agent(&ctl->epoch, epoch + 1u);
@@ -809,6 +809,248 @@ __global__ __launch_bounds__(kBlock) void fold_binned_kernel(const KArgs a, Cont
     step(odd, even, q + 1);
   }
   fold_finish<Op>(acc, a, 0, ctl, partials, earlier);
+}
+
+// The same fold for tables of up to 2^24 elements (64 MiB), with the ranges made so small that
+// a range of the table fits the LDS of a compute unit: gathers from LDS cost a few cycles per
+// wave, gathers that hit L2 are bound by the rate at which an L2 takes requests (12 per clock and
+// XCD: 71 us for 2^24 gathers whatever else the kernel does).  Two kernels again, both with
+// workgroups of kFineBlock = 1024 threads (one per compute unit: they fill its LDS):
+//
+//  1. bin_fine_kernel cuts the table into kFineBins ranges of equal length (FineCut: the range of
+//     an index is a multiplication and a shift that the host has checked against the division,
+//     because the offsets inside a range are kept as 16-bit numbers and have to be exact) and
+//     sorts every tile of kFineTile indices by range.  A thread keeps its 32 indices in
+//     registers; every element takes a rank from an LDS counter per (wave, range) -- one LDS
+//     operation per element -- a scan over the ranges lays the tile out, every offset goes to its
+//     place in LDS, and the waves copy the ranges to their slots, consecutive lanes to
+//     consecutive words.  A slot is kFineCap 16-bit entries at a fixed place per (range, tile);
+//     uniformly spread indices fill it with 64 +- 8, the places left over hold kFineNone, and
+//     what does not fit is evaluated on the spot.
+//  2. fold_fine_kernel: a workgroup takes a range at a time, applies the maps of the chain to the
+//     range's table elements once and keeps the values in LDS (128 KiB), with the identity of the
+//     fold behind them at kFineNone.  Then it streams the range's slots, which lie one behind the
+//     other, and gathers from LDS without looking at counts.  The table of the next range and
+//     the first entries are under way while a range is evaluated.
+//
+// Every order in here is fixed (lanes within a wave, waves, ranges, tiles), so a launch gives
+// the same bits every time.
+constexpr int kFineBlock = 1024;                       // threads per workgroup of both kernels
+constexpr int kFineWaves = kFineBlock / kWave;
+constexpr int kFineBins = 512;
+constexpr int kFineTile = 32768;                       // indices per tile
+constexpr int kFineVecs = kFineTile / (kFineBlock * kVec);   // 128-bit reads per thread and tile
+constexpr int kFineCap = 96;                           // entries per slot: mean 64 + 4 standard deviations of a uniform spread
+constexpr int kFineSlotWords = kFineCap / 2;           // two entries per 32-bit word
+constexpr int kFineSlice = 32768;                      // elements of a range at most (offsets are below 2^15)
+constexpr unsigned kFineNone = kFineSlice;             // the entry of a place that holds no index
+constexpr unsigned kFineIndexLimit = 1u << 24;         // table elements at most: FineCut is exact below it
+static_assert(kFineCap % 8 == 0 && kFineSlotWords <= kWave, "a slot is whole 128-bit groups and at most a word per lane");
+static_assert(kFineBins <= kFineBlock && kFineVecs * kFineBlock * kVec == kFineTile, "a thread per range in the scan; whole reads");
+static_assert(kFineBins % 32 == 0 && kFineNone < 65536u, "a bit per range in whole words; entries are 16-bit numbers");
+
+// How the table is cut: `range` elements per range (a multiple of four), `bins` ranges, and
+// j / range == __umulhi(j, magic) >> shift for every j below kFineIndexLimit.
+struct FineCut { unsigned range, bins, magic, shift; };
+
+template <class Op, class E>
+__global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Control *ctl, unsigned long long *partials,
+                                                              unsigned *slots, unsigned tiles, const FineCut cut) {
+  using T = typename Op::T;
+  using C = GatherChain<E>;
+  using Raw = int __attribute__((ext_vector_type(4)));
+  __shared__ unsigned cursor[kFineWaves][kFineBins];        // per (wave, range): the count, then the wave's first place
+  __shared__ unsigned bin_first[kFineBins + 1];             // start of a range in `staged`; the last entry is the tile's total
+  __shared__ unsigned short staged[kFineTile];              // the tile's offsets, sorted by range
+  __shared__ unsigned wave_total[kFineWaves];
+  __shared__ unsigned crowded[kFineBins / 32];              // a bit per range that got more than a slot takes
+  __shared__ T lds[kFineWaves + 1];
+  const int *index = static_cast<const int *>(a.in[C::kIndex]);
+  const unsigned n = (unsigned)a.n, n4 = n & ~3u;
+  const unsigned wave = (unsigned)wave_id(), lane = (unsigned)lane_id();
+  // raw buffer view of the index array (at most 2^31 bytes): an offset past the end reads zero without a memory access
+  const __amdgpu_buffer_rsrc_t index_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(index), 0, (int)(n4 * 4u), 0x00020000);
+  constexpr unsigned kPastEnd = 0xfffffff0u;
+  // the thread's indices of a tile, all reads at once; a tile past the last one reads as zeros
+  auto fetch = [&](unsigned tile, Raw (&v)[kFineVecs]) {
+#pragma unroll
+    for (int u = 0; u < kFineVecs; ++u) {
+      const unsigned i = tile * kFineTile + threadIdx.x * kVec + u * (kFineBlock * kVec);
+      v[u] = __builtin_amdgcn_raw_buffer_load_b128(index_buf, tile < tiles && i < n4 ? (int)(i * 4u) : (int)kPastEnd, 0, 0x2);
+    }
+  };
+  T acc = Op::identity();
+  Raw v[kFineVecs];
+  fetch(blockIdx.x, v);
+  for (unsigned tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const unsigned base = tile * kFineTile + threadIdx.x * kVec;
+    for (unsigned k = threadIdx.x; k < kFineWaves * kFineBins; k += kFineBlock) (&cursor[0][0])[k] = 0u;
+    if (threadIdx.x < kFineBins / 32) crowded[threadIdx.x] = 0u;
+    __syncthreads();
+    // rank of every element among the wave's elements of its range (range << 16 | rank is kept).  An index
+    // outside the table (undefined anyway) gets the last range, so that everything stays inside LDS.
+    unsigned where[kFineVecs][kVec];
+#pragma unroll
+    for (int u = 0; u < kFineVecs; ++u) {
+      const bool in = base + u * (kFineBlock * kVec) < n4;
+#pragma unroll
+      for (int c = 0; c < kVec; ++c) {
+        const unsigned b = min(__umulhi((unsigned)v[u][c], cut.magic) >> cut.shift, cut.bins - 1u);
+        where[u][c] = b << 16;
+        if (in) where[u][c] |= __hip_atomic_fetch_add(&cursor[wave][b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      }
+    }
+    __syncthreads();
+    // lay the tile out: ranges one after the other, inside a range the waves in order; thread t < kFineBins takes range t
+    {
+      const unsigned b = threadIdx.x;
+      unsigned total = 0;
+      if (b < (unsigned)kFineBins) {
+#pragma unroll
+        for (int w = 0; w < kFineWaves; ++w) total += cursor[w][b];
+      }
+      const unsigned inc = (unsigned)wave_scan_inclusive<AddI32>((int)total);
+      if (lane == kWave - 1) wave_total[wave] = inc;
+      __syncthreads();
+      unsigned before = 0;
+#pragma unroll
+      for (int w = 0; w < kFineWaves; ++w) if ((unsigned)w < wave) before += wave_total[w];
+      const unsigned start = before + inc - total;
+      if (b < (unsigned)kFineBins) {
+        bin_first[b] = start;
+        if (b == (unsigned)kFineBins - 1) bin_first[kFineBins] = start + total;
+        unsigned run = start;
+#pragma unroll
+        for (int w = 0; w < kFineWaves; ++w) {
+          const unsigned c = cursor[w][b];
+          cursor[w][b] = run;
+          run += c;
+        }
+        if (total > (unsigned)kFineCap) atomicOr(&crowded[b / 32u], 1u << (b % 32u));
+      }
+    }
+    __syncthreads();
+    // every offset to its place
+#pragma unroll
+    for (int u = 0; u < kFineVecs; ++u) {
+      if (base + u * (kFineBlock * kVec) < n4) {
+#pragma unroll
+        for (int c = 0; c < kVec; ++c) {
+          const unsigned b = where[u][c] >> 16;
+          const unsigned offset = min((unsigned)v[u][c] - b * cut.range, cut.range - 1u);
+          staged[cursor[wave][b] + (where[u][c] & 0xffffu)] = (unsigned short)offset;
+        }
+      }
+    }
+    // the indices of the workgroup's next tile are under way while this one is written out
+    fetch(tile + gridDim.x, v);
+    __syncthreads();
+    // every wave copies its share of the ranges to their slots: lane l the entries 2l and 2l+1 as one word
+    for (unsigned b = wave; b < cut.bins; b += kFineWaves) {
+      const unsigned start = bin_first[b];
+      const unsigned count = min(bin_first[b + 1] - start, (unsigned)kFineCap);
+      if (lane < (unsigned)kFineSlotWords) {
+        const unsigned e0 = 2u * lane < count ? (unsigned)staged[start + 2u * lane] : kFineNone;
+        const unsigned e1 = 2u * lane + 1u < count ? (unsigned)staged[start + 2u * lane + 1u] : kFineNone;
+        slots[((size_t)b * tiles + tile) * kFineSlotWords + lane] = e0 | (e1 << 16);
+      }
+    }
+    // what the slots cannot take (indices that crowd into few ranges) is evaluated here by the whole
+    // workgroup, range by range in the order of their numbers
+    for (unsigned word = 0; word < (unsigned)kFineBins / 32u; ++word) {
+      for (unsigned left = crowded[word]; left != 0u; left &= left - 1u) {    // the same for the whole workgroup
+        const unsigned b = word * 32u + (unsigned)__builtin_ctz(left);
+        const unsigned start = bin_first[b], total = bin_first[b + 1] - start;
+        for (unsigned j0 = (unsigned)kFineCap; j0 < total; j0 += kFineBlock) {
+          const unsigned j = j0 + threadIdx.x;
+          typename C::Leaf x = typename C::Leaf();
+          if (j < total) x = C::leaf(a, (int)(b * cut.range + (unsigned)staged[start + j]));
+          const T val = C::template from_leaf<0>(a, x);
+          if (j < total) acc = Op::apply(acc, val);
+        }
+      }
+    }
+    __syncthreads();                                          // `staged` and the counters are reused by the next tile
+  }
+  if (blockIdx.x == 0 && threadIdx.x < n - n4) acc = Op::apply(acc, E::template eval<0>(a, (int)(n4 + threadIdx.x)));
+  // one partial per workgroup; the second kernel combines them with its own
+  const unsigned tag = tag_of_epoch(load_agent(&ctl->epoch));
+  T r = block_reduce<Op, kFineWaves>(acc, lds);
+  if (threadIdx.x == 0) store_agent64(&partials[blockIdx.x], pack_word((unsigned)as_bits(r), tag, 1u));
+}
+
+template <class Op, class E>
+__global__ __launch_bounds__(kFineBlock) void fold_fine_kernel(const KArgs a, Control *ctl, unsigned long long *partials,
+                                                               const unsigned *slots, unsigned tiles, const FineCut cut,
+                                                               unsigned elems, unsigned earlier) {
+  using T = typename Op::T;
+  using C = GatherChain<E>;
+  using Leaf = typename C::Leaf;
+  using Raw = unsigned __attribute__((ext_vector_type(4)));
+  using RawI = int __attribute__((ext_vector_type(4)));
+  constexpr int kStream = 0x2;                                // cache policy of the buffer loads: nt
+  static_assert(sizeof(Leaf) == 4 && sizeof(T) == 4, "table elements and values are 32-bit words");
+  __shared__ T slice[kFineSlice + kVec];                      // the values of the range's table elements, then the identity
+  const Leaf *table = static_cast<const Leaf *>(a.in[C::kTable]);
+  constexpr int kAhead = kFineSlice / (kFineBlock * kVec);    // 128-bit reads of table elements per thread and range
+  constexpr int kInFlight = 6;                                // 128-bit reads of entries a lane has in flight
+  constexpr unsigned kVecsPerSlot = kFineCap / 8;             // a 128-bit group holds eight entries
+  // the whole 128-bit groups of range b, one read per thread and group: a group past the end of the
+  // range, and every group of a range past the last, reads as zero without a memory access
+  auto fetch_group = [&](unsigned b, int u) {
+    const unsigned lo = b < cut.bins ? b * cut.range : 0u;
+    const unsigned len = b < cut.bins ? min(cut.range, elems - lo) : 0u;
+    const __amdgpu_buffer_rsrc_t range_buf =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<Leaf *>(table + lo), 0, (int)((len & ~3u) * 4u), 0x00020000);
+    return __builtin_amdgcn_raw_buffer_load_b128(range_buf, (int)((threadIdx.x + u * kFineBlock) * (kVec * 4u)), 0, kStream);
+  };
+  if (threadIdx.x == 0) slice[kFineNone] = Op::identity();    // nothing else writes there
+  T acc = Op::identity();
+  RawI v[kAhead];
+#pragma unroll
+  for (int u = 0; u < kAhead; ++u) v[u] = fetch_group(blockIdx.x, u);
+  for (unsigned b = blockIdx.x; b < cut.bins; b += gridDim.x) {
+    const unsigned lo = b * cut.range;
+    const unsigned len = min(cut.range, elems - lo), len4 = len & ~3u;
+    // the range's slots lie one behind the other: one stream of 128-bit groups
+    const unsigned groups = tiles * kVecsPerSlot;
+    const __amdgpu_buffer_rsrc_t slot_buf = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned *>(slots + (size_t)b * tiles * kFineSlotWords), 0, (int)(groups * 16u), 0x00020000);
+    Raw w[kInFlight];
+    auto fetch_entries = [&](unsigned g0) {
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u)
+        w[u] = __builtin_bit_cast(Raw, __builtin_amdgcn_raw_buffer_load_b128(slot_buf, (int)((g0 + u * kFineBlock) * 16u), 0, kStream));
+    };
+    fetch_entries(threadIdx.x);
+    __syncthreads();                                          // the range before is done with LDS
+    // values of the range's table elements; as a group is used up, the same group of the workgroup's next range is asked for
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const unsigned i = (threadIdx.x + u * kFineBlock) * kVec;
+      RawI val;
+#pragma unroll
+      for (int c = 0; c < kVec; ++c) val[c] = as_bits(C::template from_leaf<0>(a, from_bits<Leaf>(v[u][c])));
+      if (i < len4) *reinterpret_cast<RawI *>(&slice[i]) = val;
+      v[u] = fetch_group(b + gridDim.x, u);
+    }
+    if (threadIdx.x < len - len4) slice[len4 + threadIdx.x] = C::template from_leaf<0>(a, table[lo + len4 + threadIdx.x]);
+    __syncthreads();
+    for (unsigned g0 = threadIdx.x; g0 < groups; g0 += kFineBlock * kInFlight) {
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) {
+        if (g0 + u * kFineBlock < groups) {
+          T x[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) x[k] = slice[(w[u][k / 2] >> (16 * (k & 1))) & 0xffffu];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) acc = Op::apply(acc, x[k]);
+        }
+      }
+      fetch_entries(g0 + kFineBlock * kInFlight);             // past the end: zeros, not used
+    }
+  }
+  fold_finish<Op, kFineWaves>(acc, a, 0, ctl, partials, earlier);
 }
 
 // ------------------------------------------------------------------ segmented fold

@@ -133,6 +133,59 @@ template <class Op, class E> hipError_t launch_fold_binned(const KArgs &a, const
                   static_cast<const int *>(entries), tiles, first);
 }
 
+// ---- the same fold with the table ranges in LDS: tables of more than one L2 and at most 2^24 elements ----
+// The table in kFineBins ranges of equal length (a multiple of four elements, so that every range
+// starts on a 128-bit boundary) and the multiplication that stands for the division by that length.
+// With 2^k >= limit * range and magic = floor(2^k / range) + 1, umulhi(j, magic) >> (k - 32) is
+// j / range for every j < limit; the check below walks the range boundaries, where a wrong quotient
+// would show first, and an empty FineCut (bins == 0) says that this table is not to be cut this way.
+inline FineCut fine_cut(size_t elems) {
+  const FineCut none = {0, 0, 0, 0};
+  if (elems == 0 || elems > (size_t)kFineIndexLimit) return none;
+  const unsigned range = (unsigned)(((elems + kFineBins - 1) / kFineBins + 3) / 4 * 4);
+  if (range > (unsigned)kFineSlice) return none;
+  unsigned log2_up = 0;
+  while ((1u << log2_up) < range) ++log2_up;
+  const unsigned k = 24 + log2_up;
+  if (k < 32) return none;
+  const unsigned long long magic = (1ull << k) / range + 1;
+  if (magic >> 32) return none;
+  const FineCut cut = {range, (unsigned)((elems + range - 1) / range), (unsigned)magic, k - 32};
+  auto quotient = [&](unsigned j) { return (unsigned)(((unsigned long long)j * cut.magic) >> 32) >> cut.shift; };
+  for (unsigned q = 1; (unsigned long long)q * range <= kFineIndexLimit; ++q) {
+    const unsigned at = q * range;
+    if (quotient(at - 1) != q - 1 || (at < kFineIndexLimit && quotient(at) != q)) return none;
+  }
+  return cut;
+}
+inline unsigned fine_tiles(const KArgs &a) { return (unsigned)(((size_t)(a.n & ~3) + kFineTile - 1) / kFineTile); }
+template <class E> bool fold_fine_accept(const KArgs &a) {
+  const size_t elems = binned_table_elems<E>(a);
+  // Worth it from two million positions on, for tables that no L2 holds, and while there are at
+  // least half as many positions as table elements: the second kernel evaluates the whole table.
+  // The index array and a range's slots are addressed with 32-bit byte offsets.
+  if ((a.flags & kSinglePass) || a.n < (1 << 21) || a.n > (1 << 29) || elems * 4 <= kL2Bytes || (size_t)a.n * 2 < elems) return false;
+  return fine_cut(elems).bins != 0;
+}
+template <class E> size_t fold_fine_workspace(const KArgs &a) {
+  return (size_t)fine_cut(binned_table_elems<E>(a)).bins * fine_tiles(a) * kFineSlotWords * sizeof(unsigned);
+}
+template <class Op, class E> hipError_t launch_fold_fine(const KArgs &a, const LaunchCtx &c) {
+  const unsigned elems = (unsigned)binned_table_elems<E>(a);
+  const FineCut cut = fine_cut(elems);
+  if (!c.workspace || cut.bins == 0) return hipErrorInvalidValue;
+  const unsigned tiles = fine_tiles(a);
+  unsigned *slots = static_cast<unsigned *>(c.workspace);
+  // both kernels fill the LDS of a compute unit: one workgroup of kFineBlock threads per unit
+  const int cus = device_compute_units();
+  const unsigned units = (unsigned)(cus > 0 ? cus : 256);
+  const unsigned first = std::min(tiles, units);
+  hipError_t e = launch_k(&bin_fine_kernel<Op, E>, first, c.stream, (int)kFineBlock, a, c.ctl, c.partials, slots, tiles, cut);
+  if (e != hipSuccess) return e;
+  return launch_k(&fold_fine_kernel<Op, E>, std::min(cut.bins, units), c.stream, (int)kFineBlock, a, c.ctl, c.partials,
+                  static_cast<const unsigned *>(slots), tiles, cut, elems, first);
+}
+
 template <class EX, class EV, int Mode, bool Reverse = false> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {
   long long tiles = std::max<long long>(1, ((long long)a.n + kScanTile - 1) / kScanTile);
   if (scan_status_words((size_t)tiles) > c.max_tiles) return hipErrorInvalidValue;

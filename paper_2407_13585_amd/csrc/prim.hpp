@@ -110,8 +110,8 @@ __device__ __forceinline__ int wave_id() { return (int)(threadIdx.x / kWave); }
 
 // Reduction over the workgroup in a fixed order (lane order inside waves, wave
 // order across them).  Every thread receives the result.  `lds` holds
-// kWavesPerBlock + 1 words and may be reused after the call returns.
-template <class Op>
+// Waves + 1 words (Waves: waves of the workgroup) and may be reused after the call returns.
+template <class Op, int Waves = kWavesPerBlock>
 __device__ __forceinline__ typename Op::T block_reduce(typename Op::T v, typename Op::T *lds) {
   using T = typename Op::T;
   T w = wave_reduce<Op>(v);
@@ -120,7 +120,7 @@ __device__ __forceinline__ typename Op::T block_reduce(typename Op::T v, typenam
   __syncthreads();
   T r = lds[0];
 #pragma unroll
-  for (int k = 1; k < kWavesPerBlock; ++k) r = Op::apply(r, lds[k]);
+  for (int k = 1; k < Waves; ++k) r = Op::apply(r, lds[k]);
   return r;
 }
 

@@ -210,7 +210,7 @@ def test_workspace_of_the_column_blocked_segmented_fold_is_part_of_scratch():
 
 def test_workspace_of_the_fold_over_sorted_gather_indices_is_part_of_scratch():
     # graph only, no data: a fold over a gather from a 16 MiB table takes the kernel pair that sorts
-    # the indices by table range first; the sorted indices (320 words per 256) live in scratch
+    # the indices by table range first; the sorted indices live in scratch
     def program(table, m):
         g = Graph()
         g.add("xs", "input", "f32", (table,))
@@ -221,14 +221,18 @@ def test_workspace_of_the_fold_over_sorted_gather_indices_is_part_of_scratch():
         g.add("r", "fold", "f32", (1,), fn="add", args=("ws",), output=True)
         return g
     m = 1 << 22
-    g = program(1 << 22, m)
-    part = fc.fc_plan(g, "bytes")
-    assert part.n_clusters == 1 and "binned" in fc.fc_cluster_kernel(g, part, 0)
-    need = fc.fc_scratch_bytes(g, part)
-    assert need >= B.FC_SCRATCH_CONTROL_BYTES + 5 * m
     fake = (0x10000000, 1 << 30)
-    bufs = {n.name: fake for n in g.nodes if n.kind == "input" or n.output}
-    expect("FC_E_SCRATCH", fc.fc_run_fused, g, part, bufs, (0x10000000, B.FC_SCRATCH_CONTROL_BYTES + 4 * m))
+    # up to 2^24 table elements the entries are 16-bit offsets into a table range (96 per 64 positions: 3 bytes
+    # a position), beyond that whole indices (320 words per 256: 5 bytes a position)
+    for table, variant, per_position in ((1 << 22, "LDS", 3), (1 << 25, "binned", 5)):
+        g = program(table, m)
+        part = fc.fc_plan(g, "bytes")
+        assert part.n_clusters == 1 and variant in fc.fc_cluster_kernel(g, part, 0), fc.fc_cluster_kernel(g, part, 0)
+        assert ("LDS" in fc.fc_cluster_kernel(g, part, 0)) == (variant == "LDS")
+        need = fc.fc_scratch_bytes(g, part)
+        assert B.FC_SCRATCH_CONTROL_BYTES + per_position * m <= need < B.FC_SCRATCH_CONTROL_BYTES + (per_position + 1) * m
+        bufs = {n.name: fake for n in g.nodes if n.kind == "input" or n.output}
+        expect("FC_E_SCRATCH", fc.fc_run_fused, g, part, bufs, (0x10000000, B.FC_SCRATCH_CONTROL_BYTES + (per_position - 1) * m))
     # a table that fits one L2, or few positions: gathered directly, no workspace
     for table, count in ((1 << 20, m), (1 << 22, 1 << 20)):
         small = program(table, count)

@@ -318,16 +318,21 @@ def test_single_pass_flag_keeps_the_gathers_in_position_order():
 
 
 @pytest.mark.parametrize("table,m", [(1048600, 1 << 21), ((1 << 24), (1 << 21) + 8192), (5000000, (1 << 21) + 4096),
-                                     (1234567, (1 << 21) + 4100), ((1 << 25) + 5, (1 << 21) + 1)])
+                                     (1234567, (1 << 21) + 4100), ((1 << 25) + 5, (1 << 21) + 1),
+                                     ((1 << 24) - 12345, (1 << 23) + 4100), ((1 << 24), (1 << 23) + 32768 + 3),
+                                     (9000001, 4500001)])
 def test_perm_gather_binned_sizes(table, m):
     # table sizes just above one L2, at 64 MiB and beyond (ranges larger than half an L2); position counts that
-    # are whole tiles, whole passes, and a pass with four elements in it
+    # are whole tiles, whole passes, and a pass with four elements in it.  Tables of up to 2^24 elements with
+    # at least half as many positions take the kernels that keep a table range in LDS (ranges of a power of
+    # two and of any other length, a last range that is shorter, a last tile that is all but empty).
     rng = np.random.default_rng(table ^ m)
     w = C.perm_gather_fold(xs=rng.standard_normal(size=table).astype(F32), idx=rng.integers(0, table, size=m, dtype=np.int32))
     env = evaluate(w.graph, w.inputs)
     g, part = plan(w.graph, False)
     prog = device_program(g, w.inputs, part)
     assert "binned" in prog.kernels()[0], prog.kernels()
+    assert ("LDS" in prog.kernels()[0]) == (table <= 1 << 24 and 2 * m >= table), prog.kernels()
     prog.run()
     compare(2, w, env, prog, w.graph.outputs(), "binned")
     assert prog.control_words()[1] == 0
