@@ -859,18 +859,21 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
   using T = typename Op::T;
   using C = GatherChain<E>;
   using Raw = int __attribute__((ext_vector_type(4)));
-  __shared__ unsigned cursor[kFineWaves][kFineBins];        // per (wave, range): the count, then the wave's first place
-  __shared__ unsigned bin_first[kFineBins + 1];             // start of a range in `staged`; the last entry is the tile's total
-  __shared__ unsigned short staged[kFineTile];              // the tile's offsets, sorted by range
-  __shared__ unsigned wave_total[kFineWaves];
-  __shared__ unsigned crowded[kFineBins / 32];              // a bit per range that got more than a slot takes
+  using Chunk = unsigned __attribute__((ext_vector_type(4)));
+  constexpr unsigned kChunks = kFineBins * kFineCap / 8;    // 128-bit groups of eight entries in the tile's slots
+  __shared__ unsigned cursor[kFineWaves][kFineBins];        // per (wave, range): the count, then the wave's first place in the slot
+  __shared__ Chunk image[kChunks];                          // the tile's slots as they go to memory: kFineCap entries per range
   __shared__ T lds[kFineWaves + 1];
+  unsigned short *entries = reinterpret_cast<unsigned short *>(image);
   const int *index = static_cast<const int *>(a.in[C::kIndex]);
   const unsigned n = (unsigned)a.n, n4 = n & ~3u;
-  const unsigned wave = (unsigned)wave_id(), lane = (unsigned)lane_id();
+  const unsigned wave = (unsigned)wave_id();
   // raw buffer view of the index array (at most 2^31 bytes): an offset past the end reads zero without a memory access
   const __amdgpu_buffer_rsrc_t index_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(index), 0, (int)(n4 * 4u), 0x00020000);
   constexpr unsigned kPastEnd = 0xfffffff0u;
+  // and of all slots (the tile limit keeps them below 2^31 bytes), addressed as range part + tile part
+  const __amdgpu_buffer_rsrc_t slot_buf =
+      __builtin_amdgcn_make_buffer_rsrc(slots, 0, (int)((unsigned)kFineBins * tiles * (kFineSlotWords * 4u)), 0x00020000);
   // the thread's indices of a tile, all reads at once; a tile past the last one reads as zeros
   auto fetch = [&](unsigned tile, Raw (&v)[kFineVecs]) {
 #pragma unroll
@@ -879,14 +882,17 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
       v[u] = __builtin_amdgcn_raw_buffer_load_b128(index_buf, tile < tiles && i < n4 ? (int)(i * 4u) : (int)kPastEnd, 0, 0x2);
     }
   };
+  const Chunk nothing = {kFineNone | (kFineNone << 16), kFineNone | (kFineNone << 16), kFineNone | (kFineNone << 16),
+                         kFineNone | (kFineNone << 16)};
   T acc = Op::identity();
   Raw v[kFineVecs];
   fetch(blockIdx.x, v);
+  // between tiles the counters are zero and every place of the image holds kFineNone
+  for (unsigned k = threadIdx.x; k < kFineWaves * kFineBins; k += kFineBlock) (&cursor[0][0])[k] = 0u;
+  for (unsigned q = threadIdx.x; q < kChunks; q += kFineBlock) image[q] = nothing;
+  __syncthreads();
   for (unsigned tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const unsigned base = tile * kFineTile + threadIdx.x * kVec;
-    for (unsigned k = threadIdx.x; k < kFineWaves * kFineBins; k += kFineBlock) (&cursor[0][0])[k] = 0u;
-    if (threadIdx.x < kFineBins / 32) crowded[threadIdx.x] = 0u;
-    __syncthreads();
     // rank of every element among the wave's elements of its range (range << 16 | rank is kept).  An index
     // outside the table (undefined anyway) gets the last range, so that everything stays inside LDS.
     unsigned where[kFineVecs][kVec];
@@ -901,36 +907,19 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
       }
     }
     __syncthreads();
-    // lay the tile out: ranges one after the other, inside a range the waves in order; thread t < kFineBins takes range t
-    {
-      const unsigned b = threadIdx.x;
-      unsigned total = 0;
-      if (b < (unsigned)kFineBins) {
+    // inside a range's slot the waves in order: thread t < kFineBins turns the counts of range t into first places
+    if (threadIdx.x < (unsigned)kFineBins) {
+      unsigned run = 0;
 #pragma unroll
-        for (int w = 0; w < kFineWaves; ++w) total += cursor[w][b];
-      }
-      const unsigned inc = (unsigned)wave_scan_inclusive<AddI32>((int)total);
-      if (lane == kWave - 1) wave_total[wave] = inc;
-      __syncthreads();
-      unsigned before = 0;
-#pragma unroll
-      for (int w = 0; w < kFineWaves; ++w) if ((unsigned)w < wave) before += wave_total[w];
-      const unsigned start = before + inc - total;
-      if (b < (unsigned)kFineBins) {
-        bin_first[b] = start;
-        if (b == (unsigned)kFineBins - 1) bin_first[kFineBins] = start + total;
-        unsigned run = start;
-#pragma unroll
-        for (int w = 0; w < kFineWaves; ++w) {
-          const unsigned c = cursor[w][b];
-          cursor[w][b] = run;
-          run += c;
-        }
-        if (total > (unsigned)kFineCap) atomicOr(&crowded[b / 32u], 1u << (b % 32u));
+      for (int w = 0; w < kFineWaves; ++w) {
+        const unsigned c = cursor[w][threadIdx.x];
+        cursor[w][threadIdx.x] = run;
+        run += c;
       }
     }
     __syncthreads();
-    // every offset to its place
+    // every offset to its place in the image; bit (4u + c) of `over` marks an element that found its slot full
+    unsigned over = 0u;
 #pragma unroll
     for (int u = 0; u < kFineVecs; ++u) {
       if (base + u * (kFineBlock * kVec) < n4) {
@@ -938,39 +927,55 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
         for (int c = 0; c < kVec; ++c) {
           const unsigned b = where[u][c] >> 16;
           const unsigned offset = min((unsigned)v[u][c] - b * cut.range, cut.range - 1u);
-          staged[cursor[wave][b] + (where[u][c] & 0xffffu)] = (unsigned short)offset;
+          const unsigned place = cursor[wave][b] + (where[u][c] & 0xffffu);
+          if (place < (unsigned)kFineCap) entries[b * kFineCap + place] = (unsigned short)offset;
+          else over |= 1u << (u * kVec + c);
+        }
+      }
+    }
+    // what the slots cannot take (indices that crowd into few ranges) is evaluated here: a wave skips
+    // every 128-bit group in which none of its lanes has such an element
+#pragma unroll
+    for (int u = 0; u < kFineVecs; ++u) {
+      const unsigned left = over >> (u * kVec) & ((1u << kVec) - 1u);
+      if (left != 0u) {
+        typename C::Leaf x[kVec];
+#pragma unroll
+        for (int c = 0; c < kVec; ++c) {
+          x[c] = typename C::Leaf();
+          if (left >> c & 1u) x[c] = C::leaf(a, v[u][c]);
+        }
+#pragma unroll
+        for (int c = 0; c < kVec; ++c) {
+          const T val = C::template from_leaf<0>(a, x[c]);
+          if (left >> c & 1u) acc = Op::apply(acc, val);
         }
       }
     }
     // the indices of the workgroup's next tile are under way while this one is written out
     fetch(tile + gridDim.x, v);
     __syncthreads();
-    // every wave copies its share of the ranges to their slots: lane l the entries 2l and 2l+1 as one word
-    for (unsigned b = wave; b < cut.bins; b += kFineWaves) {
-      const unsigned start = bin_first[b];
-      const unsigned count = min(bin_first[b + 1] - start, (unsigned)kFineCap);
-      if (lane < (unsigned)kFineSlotWords) {
-        const unsigned e0 = 2u * lane < count ? (unsigned)staged[start + 2u * lane] : kFineNone;
-        const unsigned e1 = 2u * lane + 1u < count ? (unsigned)staged[start + 2u * lane + 1u] : kFineNone;
-        slots[((size_t)b * tiles + tile) * kFineSlotWords + lane] = e0 | (e1 << 16);
+    // the image goes to the tile's slots as it is, 128 bits a thread and step, and is emptied on the way;
+    // ranges past the table's last one are empty and have slots of their own
+    {
+      constexpr unsigned kPerSlot = kFineCap / 8;
+      constexpr int kSteps = kChunks / kFineBlock;
+      static_assert(kSteps * kFineBlock == kChunks, "whole steps");
+      Chunk out[kSteps];
+#pragma unroll
+      for (int k = 0; k < kSteps; ++k) out[k] = image[threadIdx.x + k * kFineBlock];
+#pragma unroll
+      for (int k = 0; k < kSteps; ++k) {
+        unsigned q = threadIdx.x + k * kFineBlock;
+        asm volatile("" : "+v"(q));                           // the offsets are worked out here, not kept in registers from tile to tile
+        const unsigned b = q / kPerSlot, part = q - b * kPerSlot;
+        image[q] = nothing;
+        __builtin_amdgcn_raw_buffer_store_b128(out[k], slot_buf, (int)((b * tiles * kFineSlotWords + part * 4u) * 4u),
+                                               (int)(tile * (kFineSlotWords * 4u)), 0);
       }
     }
-    // what the slots cannot take (indices that crowd into few ranges) is evaluated here by the whole
-    // workgroup, range by range in the order of their numbers
-    for (unsigned word = 0; word < (unsigned)kFineBins / 32u; ++word) {
-      for (unsigned left = crowded[word]; left != 0u; left &= left - 1u) {    // the same for the whole workgroup
-        const unsigned b = word * 32u + (unsigned)__builtin_ctz(left);
-        const unsigned start = bin_first[b], total = bin_first[b + 1] - start;
-        for (unsigned j0 = (unsigned)kFineCap; j0 < total; j0 += kFineBlock) {
-          const unsigned j = j0 + threadIdx.x;
-          typename C::Leaf x = typename C::Leaf();
-          if (j < total) x = C::leaf(a, (int)(b * cut.range + (unsigned)staged[start + j]));
-          const T val = C::template from_leaf<0>(a, x);
-          if (j < total) acc = Op::apply(acc, val);
-        }
-      }
-    }
-    __syncthreads();                                          // `staged` and the counters are reused by the next tile
+    for (unsigned k = threadIdx.x; k < kFineWaves * kFineBins; k += kFineBlock) (&cursor[0][0])[k] = 0u;
+    __syncthreads();
   }
   if (blockIdx.x == 0 && threadIdx.x < n - n4) acc = Op::apply(acc, E::template eval<0>(a, (int)(n4 + threadIdx.x)));
   // one partial per workgroup; the second kernel combines them with its own

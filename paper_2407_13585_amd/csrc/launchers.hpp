@@ -168,7 +168,8 @@ template <class E> bool fold_fine_accept(const KArgs &a) {
   return fine_cut(elems).bins != 0;
 }
 template <class E> size_t fold_fine_workspace(const KArgs &a) {
-  return (size_t)fine_cut(binned_table_elems<E>(a)).bins * fine_tiles(a) * kFineSlotWords * sizeof(unsigned);
+  // a slot per (range, tile) for all kFineBins ranges: the first kernel writes the empty ones past the table's end too
+  return fine_cut(binned_table_elems<E>(a)).bins != 0 ? (size_t)kFineBins * fine_tiles(a) * kFineSlotWords * sizeof(unsigned) : 0;
 }
 template <class Op, class E> hipError_t launch_fold_fine(const KArgs &a, const LaunchCtx &c) {
   const unsigned elems = (unsigned)binned_table_elems<E>(a);
