@@ -874,19 +874,17 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
   // and of all slots (the tile limit keeps them below 2^31 bytes), addressed as range part + tile part
   const __amdgpu_buffer_rsrc_t slot_buf =
       __builtin_amdgcn_make_buffer_rsrc(slots, 0, (int)((unsigned)kFineBins * tiles * (kFineSlotWords * 4u)), 0x00020000);
-  // the thread's indices of a tile, all reads at once; a tile past the last one reads as zeros
-  auto fetch = [&](unsigned tile, Raw (&v)[kFineVecs]) {
-#pragma unroll
-    for (int u = 0; u < kFineVecs; ++u) {
-      const unsigned i = tile * kFineTile + threadIdx.x * kVec + u * (kFineBlock * kVec);
-      v[u] = __builtin_amdgcn_raw_buffer_load_b128(index_buf, tile < tiles && i < n4 ? (int)(i * 4u) : (int)kPastEnd, 0, 0x2);
-    }
+  // group u of the thread's indices of a tile; a tile past the last one reads as zeros
+  auto fetch_group = [&](unsigned tile, int u) {
+    const unsigned i = tile * kFineTile + threadIdx.x * kVec + u * (kFineBlock * kVec);
+    return __builtin_amdgcn_raw_buffer_load_b128(index_buf, tile < tiles && i < n4 ? (int)(i * 4u) : (int)kPastEnd, 0, 0x2);
   };
   const Chunk nothing = {kFineNone | (kFineNone << 16), kFineNone | (kFineNone << 16), kFineNone | (kFineNone << 16),
                          kFineNone | (kFineNone << 16)};
   T acc = Op::identity();
   Raw v[kFineVecs];
-  fetch(blockIdx.x, v);
+#pragma unroll
+  for (int u = 0; u < kFineVecs; ++u) v[u] = fetch_group(blockIdx.x, u);
   // between tiles the counters are zero and every place of the image holds kFineNone
   for (unsigned k = threadIdx.x; k < kFineWaves * kFineBins; k += kFineBlock) (&cursor[0][0])[k] = 0u;
   for (unsigned q = threadIdx.x; q < kChunks; q += kFineBlock) image[q] = nothing;
@@ -918,10 +916,13 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
       }
     }
     __syncthreads();
-    // every offset to its place in the image; bit (4u + c) of `over` marks an element that found its slot full
-    unsigned over = 0u;
+    // every offset to its place in the image.  What a slot cannot take (indices that crowd into few
+    // ranges) is evaluated on the spot; a wave skips that for a 128-bit group in which none of its lanes
+    // has such an element.  As a group is done with, the same group of the workgroup's next tile is asked
+    // for: asked for all at once, the reads would hold the waves up until most of them had come back.
 #pragma unroll
     for (int u = 0; u < kFineVecs; ++u) {
+      unsigned left = 0u;                                     // bit c: element c of the group found its slot full
       if (base + u * (kFineBlock * kVec) < n4) {
 #pragma unroll
         for (int c = 0; c < kVec; ++c) {
@@ -929,15 +930,9 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
           const unsigned offset = min((unsigned)v[u][c] - b * cut.range, cut.range - 1u);
           const unsigned place = cursor[wave][b] + (where[u][c] & 0xffffu);
           if (place < (unsigned)kFineCap) entries[b * kFineCap + place] = (unsigned short)offset;
-          else over |= 1u << (u * kVec + c);
+          else left |= 1u << c;
         }
       }
-    }
-    // what the slots cannot take (indices that crowd into few ranges) is evaluated here: a wave skips
-    // every 128-bit group in which none of its lanes has such an element
-#pragma unroll
-    for (int u = 0; u < kFineVecs; ++u) {
-      const unsigned left = over >> (u * kVec) & ((1u << kVec) - 1u);
       if (left != 0u) {
         typename C::Leaf x[kVec];
 #pragma unroll
@@ -951,9 +946,8 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
           if (left >> c & 1u) acc = Op::apply(acc, val);
         }
       }
+      v[u] = fetch_group(tile + gridDim.x, u);
     }
-    // the indices of the workgroup's next tile are under way while this one is written out
-    fetch(tile + gridDim.x, v);
     __syncthreads();
     // the image goes to the tile's slots as it is, 128 bits a thread and step, and is emptied on the way;
     // ranges past the table's last one are empty and have slots of their own
