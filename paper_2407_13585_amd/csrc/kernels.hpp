@@ -1021,9 +1021,12 @@ __global__ __launch_bounds__(kFineBlock) void fold_fine_kernel(const KArgs a, Co
       for (int u = 0; u < kInFlight; ++u)
         w[u] = __builtin_bit_cast(Raw, __builtin_amdgcn_raw_buffer_load_b128(slot_buf, (int)((g0 + u * kFineBlock) * 16u), 0, kStream));
     };
-    fetch_entries(threadIdx.x);
     __syncthreads();                                          // the range before is done with LDS
-    // values of the range's table elements; as a group is used up, the same group of the workgroup's next range is asked for
+    // Values of the range's table elements.  As a group is used up, a group of the range's first entries
+    // and the same group of the workgroup's next range are asked for: a compute unit has about a hundred
+    // requests under way at a time, a wave that asks for more is held up until there is room, and it should
+    // be held up here, where the other waves have values to work out, rather than with nothing to do.
+    static_assert(kInFlight <= kAhead, "a group of entries per group of table elements");
 #pragma unroll
     for (int u = 0; u < kAhead; ++u) {
       const unsigned i = (threadIdx.x + u * kFineBlock) * kVec;
@@ -1031,6 +1034,8 @@ __global__ __launch_bounds__(kFineBlock) void fold_fine_kernel(const KArgs a, Co
 #pragma unroll
       for (int c = 0; c < kVec; ++c) val[c] = as_bits(C::template from_leaf<0>(a, from_bits<Leaf>(v[u][c])));
       if (i < len4) *reinterpret_cast<RawI *>(&slice[i]) = val;
+      if (u < kInFlight)
+        w[u] = __builtin_bit_cast(Raw, __builtin_amdgcn_raw_buffer_load_b128(slot_buf, (int)((threadIdx.x + u * kFineBlock) * 16u), 0, kStream));
       v[u] = fetch_group(b + gridDim.x, u);
     }
     if (threadIdx.x < len - len4) slice[len4 + threadIdx.x] = C::template from_leaf<0>(a, table[lo + len4 + threadIdx.x]);
@@ -1046,7 +1051,7 @@ __global__ __launch_bounds__(kFineBlock) void fold_fine_kernel(const KArgs a, Co
           for (int k = 0; k < 8; ++k) acc = Op::apply(acc, x[k]);
         }
       }
-      fetch_entries(g0 + kFineBlock * kInFlight);             // past the end: zeros, not used
+      if (g0 - threadIdx.x + kFineBlock * kInFlight < groups) fetch_entries(g0 + kFineBlock * kInFlight);   // the same for the whole workgroup
     }
   }
   fold_finish<Op, kFineWaves>(acc, a, 0, ctl, partials, earlier);
