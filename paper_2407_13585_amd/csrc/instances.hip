@@ -135,6 +135,15 @@ std::vector<Instance> build_registry() {
   }
   r.push_back(fold_<AddF32, PermGather>());
   {
+    // SpMV-shaped cluster over a table that no L2 holds, up to 2^24 elements: sorted through LDS (first match wins)
+    Instance sorted = foldseg_<AddF32, SpmvTerm>();
+    sorted.launch = &launch_foldseg_sorted<AddF32, FnMul2, 0, 1, 2>;
+    sorted.accept = &foldseg_sorted_accept<2>;
+    sorted.workspace = &foldseg_sorted_workspace<2>;
+    sorted.variant = "sorted through LDS";
+    r.push_back(sorted);
+  }
+  {
     // SpMV-shaped cluster over a table of one to four L2s: column blocked (first match wins)
     Instance blocked = foldseg_<AddF32, SpmvTerm>();
     blocked.launch = &launch_foldseg_blocked<AddF32, FnMul2, 0, 1, 2>;

@@ -1298,6 +1298,370 @@ __global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, 
   }
 }
 
+// ------------------------------------------------------------------ segmented fold over a gathered table, sorted through LDS
+// The same computation, y[r] = fold(+, F(values[k], table[index[k]]) for k in segment r), for tables
+// of up to 2^24 elements, without a gather that leaves the compute unit.  Gathers from L2 are bound
+// by the rate at which an L2 takes requests and cost the streams a reading per column range (the
+// kernel above); gathers from LDS cost a few cycles a wave, but a compute unit holds 1/128 of such
+// a table, and a row has an element or none in a range that small: the gathered values have to go
+// back to their positions before rows can be added up.  Four kernels, all streaming:
+//
+//  1. seg_bin_kernel sorts every tile of kSegTile positions by table range, as bin_fine_kernel
+//     does (an LDS counter per wave and range, the tile's slots built in LDS as they go to memory),
+//     and keeps two 16-bit numbers per element, in two arrays: the offset inside the range and the
+//     position inside the tile.  An element that finds its slot full (indices that crowd into few
+//     ranges) is gathered on the spot and put on the tile's list of (position, value) pairs.
+//  2. seg_gather_kernel: a workgroup reads a table range into LDS and turns a stretch of the
+//     range's offsets into values, slot for slot (the slots of a range lie one behind the other).
+//  3. seg_rows_kernel: a workgroup per tile puts the tile's values (one slot per range, then the
+//     list) back at their positions in LDS, multiplies by the tile's stretch of `values`, and adds
+//     up the rows, four lanes a row.  A row belongs to the tile it starts in; the part of a row
+//     that lies in another tile than its own, and the part of a tile's last row when the row goes
+//     on, are kept per tile,
+//  4. and seg_join_kernel adds those up, tile after tile, for the rows that cross a tile boundary.
+//
+// Every element has one place at every stage and every sum a fixed order: the same bits on every
+// launch.  Bytes per element: 4 + 4 (first kernel), 2 + 4 (second), 4 + 2 + 4 (third), times the
+// slots' slack (a slot holds the mean of a uniform spread plus four standard deviations).
+constexpr int kSegBlock = 1024;                        // threads per workgroup of the first two kernels
+constexpr int kSegWaves = kSegBlock / kWave;
+constexpr int kSegTile = 16384;                        // positions per tile: 14-bit positions, a tile of values is 64 KiB of LDS
+constexpr int kSegVecs = kSegTile / (kSegBlock * kVec);      // 128-bit reads per thread and tile
+constexpr int kSegImageWords = 24576;                  // words of a tile's slots in LDS at most (96 KiB)
+constexpr int kSegMaxBins = 512;
+constexpr int kSegRowsBlock = 512;                     // threads per workgroup of the third kernel: two workgroups per compute unit
+constexpr unsigned kSegNoPlace = 0xffffu;              // the position of a slot's place that holds no element
+constexpr unsigned kSegNothing = kFineNone | (kSegNoPlace << 16);
+static_assert(kSegVecs * kSegBlock * kVec == kSegTile && kSegTile <= (int)kSegNoPlace, "whole reads; positions are 16-bit numbers");
+
+// Where the pieces lie in the workspace (element counts; every array starts on a 256-byte boundary).
+struct SegPlan {
+  FineCut cut;
+  unsigned cap;        // entries per slot, a multiple of eight
+  unsigned tiles;
+};
+
+template <class T, int KI, int KT>
+__global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsigned short *offsets, unsigned short *places,
+                                                            unsigned short *list_place, T *list_value, unsigned *list_count,
+                                                            const SegPlan plan, unsigned elems) {
+  using Raw = int __attribute__((ext_vector_type(4)));
+  using Chunk = unsigned __attribute__((ext_vector_type(4)));
+  __shared__ unsigned cursor[kSegWaves][kSegMaxBins];       // per (wave, range): the count, then the wave's first place in the slot
+  __shared__ Chunk image[kSegImageWords / 4];               // the tile's slots: offset | position << 16 per element
+  __shared__ unsigned listed;                               // elements on the tile's list so far
+  unsigned *entry = reinterpret_cast<unsigned *>(image);
+  const int *index = static_cast<const int *>(a.in[KI]);
+  const T *table = static_cast<const T *>(a.in[KT]);
+  const FineCut cut = plan.cut;
+  const unsigned cap = plan.cap, tiles = plan.tiles, bins = cut.bins;
+  const unsigned n = (unsigned)a.n;
+  const unsigned wave = (unsigned)wave_id();
+  const unsigned words = bins * cap;                        // of the image that are in use
+  // raw buffer view of the index array: a 32-bit word past the end reads as zero without a memory access
+  const __amdgpu_buffer_rsrc_t index_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(index), 0, (int)(n * 4u), 0x00020000);
+  constexpr unsigned kPastEnd = 0xfffffff0u;
+  auto fetch_group = [&](unsigned tile, int u) {
+    const unsigned i = tile * kSegTile + threadIdx.x * kVec + u * (kSegBlock * kVec);
+    return __builtin_amdgcn_raw_buffer_load_b128(index_buf, tile < tiles && i < n ? (int)(i * 4u) : (int)kPastEnd, 0, 0x2);
+  };
+  const Chunk nothing = {kSegNothing, kSegNothing, kSegNothing, kSegNothing};
+  Raw v[kSegVecs];
+#pragma unroll
+  for (int u = 0; u < kSegVecs; ++u) v[u] = fetch_group(blockIdx.x, u);
+  // between tiles the counters are zero, every place of the image holds nothing and the list is empty
+  for (unsigned k = threadIdx.x; k < kSegWaves * kSegMaxBins; k += kSegBlock) (&cursor[0][0])[k] = 0u;
+  for (unsigned q = threadIdx.x; q < words / 4u; q += kSegBlock) image[q] = nothing;
+  if (threadIdx.x == 0) listed = 0u;
+  __syncthreads();
+  for (unsigned tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const unsigned first = threadIdx.x * kVec;              // this thread's first position in the tile, group 0
+    const unsigned base = tile * kSegTile;
+    // rank of every element among the wave's elements of its range (range << 16 | rank is kept).  An index
+    // outside the table (undefined anyway) gets the last range, so that everything stays inside LDS.
+    unsigned where[kSegVecs][kVec];
+#pragma unroll
+    for (int u = 0; u < kSegVecs; ++u) {
+#pragma unroll
+      for (int c = 0; c < kVec; ++c) {
+        const unsigned b = min(__umulhi((unsigned)v[u][c], cut.magic) >> cut.shift, bins - 1u);
+        where[u][c] = b << 16;
+        if (base + first + u * (kSegBlock * kVec) + c < n)
+          where[u][c] |= __hip_atomic_fetch_add(&cursor[wave][b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+      }
+    }
+    __syncthreads();
+    // inside a range's slot the waves in order: thread t < bins turns the counts of range t into first places
+    if (threadIdx.x < bins) {
+      unsigned run = 0;
+#pragma unroll
+      for (int w = 0; w < kSegWaves; ++w) {
+        const unsigned c = cursor[w][threadIdx.x];
+        cursor[w][threadIdx.x] = run;
+        run += c;
+      }
+    }
+    __syncthreads();
+    // every element to its place in the image, or gathered here and onto the list; as a group is done
+    // with, the same group of the workgroup's next tile is asked for
+#pragma unroll
+    for (int u = 0; u < kSegVecs; ++u) {
+#pragma unroll
+      for (int c = 0; c < kVec; ++c) {
+        const unsigned at = first + u * (kSegBlock * kVec) + c;
+        if (base + at < n) {
+          const unsigned b = where[u][c] >> 16;
+          const unsigned offset = min((unsigned)v[u][c] - b * cut.range, cut.range - 1u);
+          const unsigned place = cursor[wave][b] + (where[u][c] & 0xffffu);
+          if (place < cap) {
+            entry[b * cap + place] = offset | (at << 16);
+          } else {
+            const T x = table[min((unsigned)v[u][c], elems - 1u)];
+            const unsigned k = atomicAdd(&listed, 1u);
+            list_place[(size_t)base + k] = (unsigned short)at;
+            list_value[(size_t)base + k] = x;
+          }
+        }
+      }
+      v[u] = fetch_group(tile + gridDim.x, u);
+    }
+    __syncthreads();
+    // the image goes to the tile's slots, eight entries a thread and step (128 bits of offsets, 128 bits
+    // of positions), and is emptied on the way
+    for (unsigned q = threadIdx.x; q < words / 8u; q += kSegBlock) {
+      const Chunk lo = image[2u * q], hi = image[2u * q + 1u];
+      image[2u * q] = nothing;
+      image[2u * q + 1u] = nothing;
+      const unsigned b = q * 8u / cap, part = q * 8u - b * cap;
+      const size_t at = ((size_t)b * tiles + tile) * cap + part;
+      Chunk o, p;
+      o[0] = (lo[0] & 0xffffu) | (lo[1] << 16);
+      o[1] = (lo[2] & 0xffffu) | (lo[3] << 16);
+      o[2] = (hi[0] & 0xffffu) | (hi[1] << 16);
+      o[3] = (hi[2] & 0xffffu) | (hi[3] << 16);
+      p[0] = (lo[0] >> 16) | (lo[1] & 0xffff0000u);
+      p[1] = (lo[2] >> 16) | (lo[3] & 0xffff0000u);
+      p[2] = (hi[0] >> 16) | (hi[1] & 0xffff0000u);
+      p[3] = (hi[2] >> 16) | (hi[3] & 0xffff0000u);
+      *reinterpret_cast<Chunk *>(offsets + at) = o;
+      *reinterpret_cast<Chunk *>(places + at) = p;
+    }
+    for (unsigned k = threadIdx.x; k < kSegWaves * kSegMaxBins; k += kSegBlock) (&cursor[0][0])[k] = 0u;
+    if (threadIdx.x == 0) {
+      list_count[tile] = listed;
+      listed = 0u;
+    }
+    __syncthreads();
+  }
+}
+
+template <class T, int KT>
+__global__ __launch_bounds__(kSegBlock) void seg_gather_kernel(const KArgs a, const unsigned short *offsets, T *gathered,
+                                                               const SegPlan plan, unsigned elems, unsigned parts) {
+  using Raw = unsigned __attribute__((ext_vector_type(4)));
+  using RawI = int __attribute__((ext_vector_type(4)));
+  using TV = T __attribute__((ext_vector_type(4)));
+  constexpr int kStream = 0x2;                                // cache policy of the buffer loads: nt
+  static_assert(sizeof(T) == 4, "table elements are 32-bit words");
+  __shared__ T slice[kFineSlice + kVec];                      // the range of the table, then an element for the places that hold nothing
+  const T *table = static_cast<const T *>(a.in[KT]);
+  const FineCut cut = plan.cut;
+  const unsigned b = blockIdx.x / parts, part = blockIdx.x - b * parts;      // the grid is bins * parts workgroups
+  const unsigned lo = b * cut.range, len = min(cut.range, elems - lo), len4 = len & ~3u;
+  {
+    const __amdgpu_buffer_rsrc_t range_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(table + lo), 0, (int)(len4 * 4u), 0x00020000);
+    constexpr int kAhead = kFineSlice / (kSegBlock * kVec);
+    RawI v[kAhead];
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u)
+      v[u] = __builtin_amdgcn_raw_buffer_load_b128(range_buf, (int)((threadIdx.x + u * kSegBlock) * (kVec * 4u)), 0, 0);
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      const unsigned i = (threadIdx.x + u * kSegBlock) * kVec;
+      if (i < len4) *reinterpret_cast<RawI *>(&slice[i]) = v[u];
+    }
+    if (threadIdx.x < len - len4) slice[len4 + threadIdx.x] = table[lo + len4 + threadIdx.x];
+    if (threadIdx.x == 0) slice[kFineNone] = T();
+  }
+  __syncthreads();
+  // the range's slots lie one behind the other: a stream of 128-bit groups of eight offsets, of which this
+  // workgroup takes the stretch `part`
+  const unsigned groups = plan.tiles * (plan.cap / 8u);
+  const unsigned per = (groups + parts - 1u) / parts;
+  const unsigned g_lo = part * per, g_hi = min(g_lo + per, groups);
+  const size_t start = (size_t)b * plan.tiles * plan.cap;
+  const __amdgpu_buffer_rsrc_t offset_buf =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned short *>(offsets + start), 0, (int)(groups * 16u), 0x00020000);
+  T *out = gathered + start;
+  constexpr int kInFlight = 4;
+  for (unsigned g0 = g_lo + threadIdx.x; g0 < g_hi; g0 += kSegBlock * kInFlight) {
+    Raw w[kInFlight];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      const unsigned g = g0 + u * kSegBlock;
+      w[u] = __builtin_bit_cast(Raw, __builtin_amdgcn_raw_buffer_load_b128(offset_buf, g < g_hi ? (int)(g * 16u) : (int)0xfffffff0u, 0, kStream));
+    }
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) {
+      const unsigned g = g0 + u * kSegBlock;
+      if (g < g_hi) {
+        TV x0, x1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          x0[k] = slice[(w[u][k / 2] >> (16 * (k & 1))) & 0xffffu];
+          x1[k] = slice[(w[u][2 + k / 2] >> (16 * (k & 1))) & 0xffffu];
+        }
+        *reinterpret_cast<TV *>(out + (size_t)g * 8u) = x0;
+        *reinterpret_cast<TV *>(out + (size_t)g * 8u + 4u) = x1;
+      }
+    }
+  }
+}
+
+// The number of rows r in [0, rows) with start[r] < target, start ascending: all lanes of a wave take
+// part, sixty-four probes a step.
+__device__ __forceinline__ unsigned wave_rows_below(const unsigned *start, unsigned rows, unsigned target) {
+  unsigned lo = 0, len = rows;
+  const unsigned lane = (unsigned)lane_id();
+  while (len != 0u) {                                         // the same for the whole wave
+    const unsigned stride = (len + kWave - 1u) / kWave;
+    const unsigned probe = lo + (lane + 1u) * stride - 1u;    // the last row of this lane's stretch
+    const bool inside = probe < lo + len;
+    const bool below = inside && start[probe] < target;
+    const unsigned k = (unsigned)__builtin_popcountll(__builtin_amdgcn_ballot_w64(below));
+    // stretches 0 .. k-1 lie below the target; the first row at or above it is in stretch k, whose last
+    // row is known not to be below if that row exists
+    const unsigned next = lo + k * stride;
+    const unsigned left = lo + len > next ? lo + len - next : 0u;
+    const bool last_known = k < (unsigned)kWave && next + stride - 1u < lo + len;
+    len = last_known ? stride - 1u : min(left, stride);
+    lo = next;
+  }
+  return lo;
+}
+
+template <class Op, class F, int KV>
+__global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, const unsigned short *places, const typename Op::T *gathered,
+                                                                 const unsigned short *list_place, const typename Op::T *list_value,
+                                                                 const unsigned *list_count, unsigned *first_row,
+                                                                 typename Op::T *head, typename Op::T *tail, const SegPlan plan) {
+  using T = typename Op::T;
+  using TV = T __attribute__((ext_vector_type(4)));
+  using Pair = unsigned __attribute__((ext_vector_type(2)));
+  __shared__ T term[kSegTile];                                // the tile's gathered values, then its terms, by position
+  __shared__ unsigned bounds[2];                              // the first row that starts in the tile, and in the next
+  const unsigned *start = reinterpret_cast<const unsigned *>(a.in[kMaxIn - 1]);
+  const T *values = static_cast<const T *>(a.in[KV]);
+  T *y = static_cast<T *>(a.out[0]);
+  const unsigned rows = (unsigned)a.aux, n = (unsigned)a.n;
+  const unsigned tile = blockIdx.x, tiles = plan.tiles, cap = plan.cap, bins = plan.cut.bins;
+  const unsigned t_lo = tile * kSegTile, t_hi = min(t_lo + (unsigned)kSegTile, n);
+  // two waves look up the rows of the tile while the others begin with the values
+  if (wave_id() == 0) {
+    const unsigned r = wave_rows_below(start, rows, t_lo);
+    if (lane_id() == 0) { bounds[0] = r; first_row[tile] = r; }
+  } else if (wave_id() == 1) {
+    const unsigned r = tile + 1u < tiles ? wave_rows_below(start, rows, t_hi) : rows;     // the last tile takes the empty rows at the end
+    if (lane_id() == 0) bounds[1] = r;
+  }
+  // the values back to their positions: four entries a thread and step, several steps under way
+  {
+    const unsigned quads_per_slot = cap / 4u, quads = bins * quads_per_slot;
+    constexpr int kAtOnce = 4;
+    for (unsigned q0 = threadIdx.x; q0 < quads; q0 += kSegRowsBlock * kAtOnce) {
+      TV x[kAtOnce];
+      Pair p[kAtOnce];
+#pragma unroll
+      for (int u = 0; u < kAtOnce; ++u) {
+        const unsigned q = min(q0 + u * kSegRowsBlock, quads - 1u);
+        const unsigned b = q / quads_per_slot, part = q - b * quads_per_slot;
+        const size_t at = ((size_t)b * tiles + tile) * cap + part * 4u;
+        x[u] = __builtin_nontemporal_load(reinterpret_cast<const TV *>(gathered + at));
+        p[u] = __builtin_nontemporal_load(reinterpret_cast<const Pair *>(places + at));
+      }
+#pragma unroll
+      for (int u = 0; u < kAtOnce; ++u) {
+        if (q0 + u * kSegRowsBlock < quads) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const unsigned place = (p[u][c / 2] >> (16 * (c & 1))) & 0xffffu;
+            if (place != kSegNoPlace) term[place] = x[u][c];
+          }
+        }
+      }
+    }
+    const unsigned listed = list_count[tile];
+    for (unsigned k = threadIdx.x; k < listed; k += kSegRowsBlock) term[list_place[(size_t)t_lo + k]] = list_value[(size_t)t_lo + k];
+  }
+  __syncthreads();
+  // times the tile's stretch of `values` (a 32-bit word past the end of the array reads as zero)
+  {
+    const __amdgpu_buffer_rsrc_t value_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(values), 0, (int)(n * 4u), 0x00020000);
+    constexpr int kSteps = kSegTile / (kSegRowsBlock * kVec);
+    using RawI = int __attribute__((ext_vector_type(4)));
+    RawI w[kSteps];
+#pragma unroll
+    for (int k = 0; k < kSteps; ++k) {
+      const unsigned e = (threadIdx.x + k * kSegRowsBlock) * kVec;
+      w[k] = __builtin_amdgcn_raw_buffer_load_b128(value_buf, t_lo + e < n ? (int)((t_lo + e) * 4u) : (int)0xfffffff0u, 0, 0x2);
+    }
+#pragma unroll
+    for (int k = 0; k < kSteps; ++k) {
+      const unsigned e = (threadIdx.x + k * kSegRowsBlock) * kVec;
+      TV g = *reinterpret_cast<const TV *>(&term[e]);
+#pragma unroll
+      for (int c = 0; c < kVec; ++c) g[c] = F::apply(a.p[0], from_bits<T>(w[k][c]), g[c]);
+      *reinterpret_cast<TV *>(&term[e]) = g;
+    }
+  }
+  __syncthreads();
+  // Rows, four lanes each.  The tile's own rows are those that start in it; the row that reaches into it
+  // from before (if there is one) comes first.  A row that lies in the tile whole is stored; of a row
+  // that began before, the part in this tile is the tile's head; of the tile's last row, when it goes
+  // on, the part in this tile is the tile's tail.
+  const unsigned row_lo = bounds[0], row_hi = bounds[1];
+  const bool reaches_in = row_lo > 0u && start[min(row_lo, rows)] > t_lo;      // start[rows] is the number of elements
+  const unsigned r_first = row_lo - (reaches_in ? 1u : 0u);
+  const unsigned ql = threadIdx.x & 3u;
+  for (unsigned r0 = r_first; r0 < row_hi; r0 += kSegRowsBlock / 4) {           // the same for the whole workgroup
+    const unsigned r = r0 + threadIdx.x / 4u;
+    const bool have = r < row_hi;
+    unsigned lo = 0u, hi = 0u;
+    if (have) { lo = start[r]; hi = start[r + 1u]; }
+    const unsigned from = max(lo, t_lo), to = min(hi, t_hi);
+    T acc = Op::identity();
+    for (unsigned k = from + ql; k < to; k += 4u) acc = Op::apply(acc, term[k - t_lo]);
+    acc = Op::apply(acc, dpp_move<0xB1>(Op::identity(), acc));    // quad_perm [1,0,3,2]
+    acc = Op::apply(acc, dpp_move<0x4E>(Op::identity(), acc));    // quad_perm [2,3,0,1]
+    if (have && ql == 0u) {
+      if (lo < t_lo) head[tile] = acc;
+      else if (hi > t_hi) tail[tile] = acc;
+      else y[r] = acc;
+    }
+  }
+}
+
+template <class Op>
+__global__ __launch_bounds__(kBlock) void seg_join_kernel(const KArgs a, const unsigned *first_row, const typename Op::T *head,
+                                                          const typename Op::T *tail, unsigned tiles) {
+  using T = typename Op::T;
+  const unsigned *start = reinterpret_cast<const unsigned *>(a.in[kMaxIn - 1]);
+  T *y = static_cast<T *>(a.out[0]);
+  const unsigned n = (unsigned)a.n;
+  const unsigned t = blockIdx.x * kBlock + threadIdx.x;
+  if (t + 1u >= tiles) return;                                // the last tile's rows end with the array
+  const unsigned row_lo = first_row[t], row_hi = first_row[t + 1u];
+  if (row_hi == row_lo) return;                               // no row starts in this tile
+  const unsigned r = row_hi - 1u, end = start[r + 1u];
+  if (end <= (t + 1u) * kSegTile) return;                     // its last row ends in it
+  T s = tail[t];
+  for (unsigned t2 = t + 1u; t2 < tiles; ++t2) {
+    s = Op::apply(s, head[t2]);
+    if (end <= min((t2 + 1u) * (unsigned)kSegTile, n)) break;
+  }
+  y[r] = s;
+}
+
 // ------------------------------------------------------------------ single-pass scan / compaction
 // Exclusive (+) scan of the int32 stream EX in one pass over the data (section
 // 2: a scan inside a cluster must be a single pass; the chained scan is one of

@@ -7,6 +7,7 @@
 #include "registry.hpp"
 
 #include <algorithm>
+#include <cmath>
 #include <string>
 #include <tuple>
 #include <utility>
@@ -137,12 +138,13 @@ template <class Op, class E> hipError_t launch_fold_binned(const KArgs &a, const
 // The table in kFineBins ranges of equal length (a multiple of four elements, so that every range
 // starts on a 128-bit boundary) and the multiplication that stands for the division by that length.
 // With 2^k >= limit * range and magic = floor(2^k / range) + 1, umulhi(j, magic) >> (k - 32) is
-// j / range for every j < limit; the check below walks the range boundaries, where a wrong quotient
-// would show first, and an empty FineCut (bins == 0) says that this table is not to be cut this way.
-inline FineCut fine_cut(size_t elems) {
+// j / range for every j < limit; the check below walks the range boundaries inside the table, where a
+// wrong quotient would show first, and an empty FineCut (bins == 0) says that this table is not to be
+// cut this way.
+inline FineCut fine_cut(size_t elems, unsigned max_bins = kFineBins) {
   const FineCut none = {0, 0, 0, 0};
-  if (elems == 0 || elems > (size_t)kFineIndexLimit) return none;
-  const unsigned range = (unsigned)(((elems + kFineBins - 1) / kFineBins + 3) / 4 * 4);
+  if (elems == 0 || elems > (size_t)kFineIndexLimit || max_bins == 0) return none;
+  const unsigned range = (unsigned)(((elems + max_bins - 1) / max_bins + 3) / 4 * 4);
   if (range > (unsigned)kFineSlice) return none;
   unsigned log2_up = 0;
   while ((1u << log2_up) < range) ++log2_up;
@@ -152,7 +154,7 @@ inline FineCut fine_cut(size_t elems) {
   if (magic >> 32) return none;
   const FineCut cut = {range, (unsigned)((elems + range - 1) / range), (unsigned)magic, k - 32};
   auto quotient = [&](unsigned j) { return (unsigned)(((unsigned long long)j * cut.magic) >> 32) >> cut.shift; };
-  for (unsigned q = 1; (unsigned long long)q * range <= kFineIndexLimit; ++q) {
+  for (unsigned q = 1; q <= cut.bins; ++q) {                  // indices past the table are undefined and clamped by the kernels
     const unsigned at = q * range;
     if (quotient(at - 1) != q - 1 || (at < kFineIndexLimit && quotient(at) != q)) return none;
   }
@@ -185,6 +187,84 @@ template <class Op, class E> hipError_t launch_fold_fine(const KArgs &a, const L
   if (e != hipSuccess) return e;
   return launch_k(&fold_fine_kernel<Op, E>, std::min(cut.bins, units), c.stream, (int)kFineBlock, a, c.ctl, c.partials,
                   static_cast<const unsigned *>(slots), tiles, cut, elems, first);
+}
+
+// ---- segmented fold over a gathered table, sorted through LDS: tables of more than one L2 and at most 2^24 elements ----
+// Ranges as long as LDS takes (so that a slot per range and tile is long and its slack small); a slot holds
+// the mean of a uniform spread plus four standard deviations, as far as the tile's slots fit their LDS image.
+inline SegPlan seg_plan(size_t elems, long long n) {
+  SegPlan p = {{0, 0, 0, 0}, 0, 0};
+  if (elems == 0 || n <= 0) return p;
+  const unsigned want = (unsigned)std::min<size_t>((elems + kFineSlice - 1) / kFineSlice, kSegMaxBins);
+  p.cut = fine_cut(elems, want);
+  if (p.cut.bins == 0 || p.cut.bins > (unsigned)kSegMaxBins) { p.cut.bins = 0; return p; }
+  const double mean = (double)kSegTile / p.cut.bins;
+  unsigned cap = ((unsigned)(mean + 4.0 * std::sqrt(mean)) + 8 + 7) / 8 * 8;
+  cap = std::min(cap, (unsigned)kSegImageWords / p.cut.bins / 8 * 8);
+  p.cap = std::max(cap, 8u);
+  p.tiles = (unsigned)(((size_t)n + kSegTile - 1) / kSegTile);
+  return p;
+}
+// the pieces of the workspace, each on a 256-byte boundary
+struct SegSpace { size_t offsets, places, gathered, list_place, list_value, list_count, first_row, head, tail, total; };
+inline SegSpace seg_space(const SegPlan &p) {
+  auto up = [](size_t b) { return (b + 255) / 256 * 256; };
+  const size_t entries = (size_t)p.cut.bins * p.tiles * p.cap, positions = (size_t)p.tiles * kSegTile;
+  SegSpace s;
+  size_t at = 0;
+  s.offsets = at;    at += up(entries * 2);
+  s.places = at;     at += up(entries * 2);
+  s.gathered = at;   at += up(entries * 4);
+  s.list_place = at; at += up(positions * 2);
+  s.list_value = at; at += up(positions * 4);
+  s.list_count = at; at += up((size_t)p.tiles * 4);
+  s.first_row = at;  at += up((size_t)p.tiles * 4);
+  s.head = at;       at += up((size_t)p.tiles * 4);
+  s.tail = at;       at += up((size_t)p.tiles * 4);
+  s.total = at;
+  return s;
+}
+template <int KT> bool foldseg_sorted_accept(const KArgs &a) {
+  const size_t table = blocked_table_bytes<KT>(a);
+  // from two million elements on, for tables that no L2 holds; positions and byte offsets into a range's
+  // slots are 32-bit numbers
+  if ((a.flags & kSinglePass) || a.n < (1 << 21) || a.n > (1 << 28) || a.aux <= 0 || table <= kL2Bytes) return false;
+  return seg_plan(table / 4, a.n).cut.bins != 0;
+}
+template <int KT> size_t foldseg_sorted_workspace(const KArgs &a) {
+  const SegPlan p = seg_plan(blocked_table_bytes<KT>(a) / 4, a.n);
+  return p.cut.bins != 0 ? seg_space(p).total : 0;
+}
+template <class Op, class F, int KV, int KI, int KT>
+hipError_t launch_foldseg_sorted(const KArgs &a, const LaunchCtx &c) {
+  using T = typename Op::T;
+  const unsigned elems = (unsigned)(blocked_table_bytes<KT>(a) / 4);
+  const SegPlan p = seg_plan(elems, a.n);
+  if (!c.workspace || p.cut.bins == 0) return hipErrorInvalidValue;
+  const SegSpace s = seg_space(p);
+  char *w = static_cast<char *>(c.workspace);
+  unsigned short *offsets = reinterpret_cast<unsigned short *>(w + s.offsets), *places = reinterpret_cast<unsigned short *>(w + s.places);
+  T *gathered = reinterpret_cast<T *>(w + s.gathered);
+  unsigned short *list_place = reinterpret_cast<unsigned short *>(w + s.list_place);
+  T *list_value = reinterpret_cast<T *>(w + s.list_value);
+  unsigned *list_count = reinterpret_cast<unsigned *>(w + s.list_count), *first_row = reinterpret_cast<unsigned *>(w + s.first_row);
+  T *head = reinterpret_cast<T *>(w + s.head), *tail = reinterpret_cast<T *>(w + s.tail);
+  const int cus = device_compute_units();
+  const unsigned units = (unsigned)(cus > 0 ? cus : 256);
+  hipError_t e = launch_k(&seg_bin_kernel<T, KI, KT>, std::min(p.tiles, units), c.stream, (int)kSegBlock, a, offsets, places,
+                          list_place, list_value, list_count, p, elems);
+  if (e != hipSuccess) return e;
+  // a table range is read into LDS by every workgroup that works on it: two workgroups per compute unit in all
+  const unsigned parts = std::max(1u, (2 * units + p.cut.bins - 1) / p.cut.bins);
+  e = launch_k(&seg_gather_kernel<T, KT>, p.cut.bins * parts, c.stream, (int)kSegBlock, a, static_cast<const unsigned short *>(offsets),
+               gathered, p, elems, parts);
+  if (e != hipSuccess) return e;
+  e = launch_k(&seg_rows_kernel<Op, F, KV>, p.tiles, c.stream, (int)kSegRowsBlock, a, static_cast<const unsigned short *>(places),
+               static_cast<const T *>(gathered), static_cast<const unsigned short *>(list_place), static_cast<const T *>(list_value),
+               static_cast<const unsigned *>(list_count), first_row, head, tail, p);
+  if (e != hipSuccess) return e;
+  return launch_k(&seg_join_kernel<Op>, (p.tiles + kBlock - 1) / kBlock, c.stream, a, static_cast<const unsigned *>(first_row),
+                  static_cast<const T *>(head), static_cast<const T *>(tail), p.tiles);
 }
 
 template <class EX, class EV, int Mode, bool Reverse = false> hipError_t launch_scan(const KArgs &a, const LaunchCtx &c) {

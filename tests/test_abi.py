@@ -336,7 +336,7 @@ def test_check_reports_and_clears_a_wait_that_gave_up():
 def test_single_pass_flag_selects_the_kernel_that_keeps_position_order():
     # host only: the matcher's choice for the two gather pipelines at their benchmark sizes
     from workloads import single_pass
-    for cfg, variant in ((2, "binned"), (3, "column-blocked")):
+    for cfg, variant in ((2, "binned"), (3, "sorted through LDS")):
         w = build(cfg)
         default = fc.fc_plan(w.graph, "bytes")
         assert variant in fc.fc_cluster_kernel(w.graph, default, 0)

@@ -250,6 +250,54 @@ def test_spmv_column_blocked(rows, ncols, mean_len):
     run_all_modes(3, w, env)
 
 
+@pytest.mark.parametrize("shape", ["uniform", "crowded", "long rows", "empty ends", "one column", "many ranges"])
+def test_spmv_sorted_through_lds(shape):
+    # from two million elements on, over a table that no L2 holds, the segmented fold sorts its elements by
+    # table range, gathers from LDS and puts the values back in place (four kernels, everything between
+    # them in scratch).  Columns spread evenly, columns that crowd into few ranges or one (slots overflow:
+    # those elements go through the tiles' lists), rows longer than several tiles, rows that end exactly
+    # on a tile boundary, runs of empty rows at both ends and around tile boundaries, a table that is cut
+    # into many short ranges, element counts off the tile and off the 128-bit group.
+    rng = np.random.default_rng(len(shape) * 1000 + 7)
+    rows, ncols = 190001, 1500007
+    lengths = rng.poisson(16.0, size=rows).astype(np.int64)
+    if shape == "long rows":
+        lengths[rng.integers(0, rows, size=6)] = 40000
+        lengths[:1024] = 16                                   # row 1024 starts on a tile boundary ...
+        lengths[1024] = 16384 * 3
+        lengths[1025:1035] = 0                                # ... ends on one, and empty rows follow
+    elif shape == "empty ends":
+        lengths[:5000] = 0
+        lengths[-7000:] = 0
+        lengths[60000:90000] = 0
+        lengths[30000:30100] = 2000
+    elif shape == "many ranges":
+        ncols = (1 << 24) - 3
+    w = C.spmv(lengths=lengths, seed=11, ncols=ncols)
+    nnz = w.inputs["col"].shape[0]
+    assert nnz >= 1 << 21
+    if shape == "crowded":
+        w.inputs["col"] = np.where(rng.random(nnz) < 0.9, rng.integers(0, 3000, size=nnz), rng.integers(0, ncols, size=nnz)).astype(np.int32)
+    elif shape == "one column":
+        w.inputs["col"] = np.full(nnz, ncols - 1, dtype=np.int32)
+    env = evaluate(w.graph, w.inputs)
+    g, part = plan(w.graph, False)
+    prog = device_program(g, w.inputs, part)
+    assert "sorted through LDS" in prog.kernels()[0], prog.kernels()
+    for k in range(2):                                        # the scratch arrays are rewritten launch after launch
+        if k:
+            w.inputs["vals"] = rng.uniform(-1.0, 1.0, size=nnz).astype(F32)
+            w.inputs["x"] = rng.uniform(-1.0, 1.0, size=ncols).astype(F32)
+            w.inputs["col"] = np.ascontiguousarray(w.inputs["col"][::-1])
+            for name in ("vals", "x", "col"):
+                prog.upload(name, w.inputs[name])
+            env = evaluate(w.graph, w.inputs)
+        prog.run()
+        compare(3, w, env, prog, w.graph.outputs(), "sorted")
+        assert prog.control_words()[1] == 0
+    run_all_modes(3, w, env)
+
+
 @pytest.mark.parametrize("table,m,spread", [(2200003, 2200003, "permutation"), (3000000, (1 << 21) + 4099, "uniform"),
                                             (2000001, (1 << 21) + 8197, "skewed"), (1 << 22, (1 << 21) + 2, "one"),
                                             (3000017, (1 << 21) + 77, "middle")])
