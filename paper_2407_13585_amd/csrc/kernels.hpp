@@ -1309,12 +1309,13 @@ __global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, 
 //  1. seg_bin_kernel sorts every tile of kSegTile positions by table range, as bin_fine_kernel
 //     does (an LDS counter per wave and range, the tile's slots built in LDS as they go to memory),
 //     and keeps two 16-bit numbers per element, in two arrays: the offset inside the range and the
-//     position inside the tile.  An element that finds its slot full (indices that crowd into few
-//     ranges) is gathered on the spot and put on the tile's list of (position, value) pairs.
+//     position inside the tile (offsets slot after slot for every range, positions tile after tile).
+//     An element that finds its slot full (about one in a thousand of evenly spread indices; most
+//     of indices that crowd into few ranges) goes onto the tile's list of (position, index) pairs.
 //  2. seg_gather_kernel: a workgroup reads a table range into LDS and turns a stretch of the
 //     range's offsets into values, slot for slot (the slots of a range lie one behind the other).
-//  3. seg_rows_kernel: a workgroup per tile puts the tile's values (one slot per range, then the
-//     list) back at their positions in LDS, multiplies by the tile's stretch of `values`, and adds
+//  3. seg_rows_kernel: a workgroup per tile puts the tile's values (one slot per range, then those
+//     of the list, gathered from memory) back at their positions in LDS, multiplies by the tile's stretch of `values`, and adds
 //     up the rows, four lanes a row.  A row belongs to the tile it starts in; the part of a row
 //     that lies in another tile than its own, and the part of a tile's last row when the row goes
 //     on, are kept per tile,
@@ -1322,7 +1323,7 @@ __global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, 
 //
 // Every element has one place at every stage and every sum a fixed order: the same bits on every
 // launch.  Bytes per element: 4 + 4 (first kernel), 2 + 4 (second), 4 + 2 + 4 (third), times the
-// slots' slack (a slot holds the mean of a uniform spread plus four standard deviations).
+// slots' slack (a slot holds the mean of a uniform spread plus two standard deviations).
 constexpr int kSegBlock = 1024;                        // threads per workgroup of the first two kernels
 constexpr int kSegWaves = kSegBlock / kWave;
 constexpr int kSegTile = 16384;                        // positions per tile: 14-bit positions, a tile of values is 64 KiB of LDS
@@ -1330,6 +1331,7 @@ constexpr int kSegVecs = kSegTile / (kSegBlock * kVec);      // 128-bit reads pe
 constexpr int kSegImageWords = 24576;                  // words of a tile's slots in LDS at most (96 KiB)
 constexpr int kSegMaxBins = 512;
 constexpr int kSegRowsBlock = 512;                     // threads per workgroup of the third kernel: two workgroups per compute unit
+constexpr int kSegRowsStaged = 2048;                   // row starts of a tile kept in LDS (a tile of 16-element rows has 1024)
 constexpr unsigned kSegNoPlace = 0xffffu;              // the position of a slot's place that holds no element
 constexpr unsigned kSegNothing = kFineNone | (kSegNoPlace << 16);
 static_assert(kSegVecs * kSegBlock * kVec == kSegTile && kSegTile <= (int)kSegNoPlace, "whole reads; positions are 16-bit numbers");
@@ -1341,9 +1343,9 @@ struct SegPlan {
   unsigned tiles;
 };
 
-template <class T, int KI, int KT>
+template <int KI>
 __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsigned short *offsets, unsigned short *places,
-                                                            unsigned short *list_place, T *list_value, unsigned *list_count,
+                                                            unsigned short *list_place, unsigned *list_index, unsigned *list_count,
                                                             const SegPlan plan, unsigned elems) {
   using Raw = int __attribute__((ext_vector_type(4)));
   using Chunk = unsigned __attribute__((ext_vector_type(4)));
@@ -1352,7 +1354,6 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
   __shared__ unsigned listed;                               // elements on the tile's list so far
   unsigned *entry = reinterpret_cast<unsigned *>(image);
   const int *index = static_cast<const int *>(a.in[KI]);
-  const T *table = static_cast<const T *>(a.in[KT]);
   const FineCut cut = plan.cut;
   const unsigned cap = plan.cap, tiles = plan.tiles, bins = cut.bins;
   const unsigned n = (unsigned)a.n;
@@ -1369,8 +1370,20 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
   Raw v[kSegVecs];
 #pragma unroll
   for (int u = 0; u < kSegVecs; ++u) v[u] = fetch_group(blockIdx.x, u);
+  auto clear_counters = [&]() {                             // a wave its own, of the ranges there are
+    for (unsigned b = (unsigned)lane_id(); b < bins; b += kWave) cursor[wave][b] = 0u;
+  };
+  // where the groups of eight entries that this thread copies out lie in a range's run of slots: worked out once
+  constexpr int kCopies = kSegImageWords / 8 / kSegBlock;
+  static_assert(kCopies * kSegBlock * 8 == kSegImageWords, "whole steps");
+  unsigned copy_to[kCopies];                                // b * tiles * cap + part, without the tile's share
+#pragma unroll
+  for (int k = 0; k < kCopies; ++k) {
+    const unsigned q = threadIdx.x + k * kSegBlock, b = q * 8u / cap, part = q * 8u - b * cap;
+    copy_to[k] = b * tiles * cap + part;
+  }
   // between tiles the counters are zero, every place of the image holds nothing and the list is empty
-  for (unsigned k = threadIdx.x; k < kSegWaves * kSegMaxBins; k += kSegBlock) (&cursor[0][0])[k] = 0u;
+  clear_counters();
   for (unsigned q = threadIdx.x; q < words / 4u; q += kSegBlock) image[q] = nothing;
   if (threadIdx.x == 0) listed = 0u;
   __syncthreads();
@@ -1380,13 +1393,14 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
     // rank of every element among the wave's elements of its range (range << 16 | rank is kept).  An index
     // outside the table (undefined anyway) gets the last range, so that everything stays inside LDS.
     unsigned where[kSegVecs][kVec];
+    const unsigned here = n - base;                         // positions of this tile that exist (or more)
 #pragma unroll
     for (int u = 0; u < kSegVecs; ++u) {
 #pragma unroll
       for (int c = 0; c < kVec; ++c) {
         const unsigned b = min(__umulhi((unsigned)v[u][c], cut.magic) >> cut.shift, bins - 1u);
         where[u][c] = b << 16;
-        if (base + first + u * (kSegBlock * kVec) + c < n)
+        if (first + u * (kSegBlock * kVec) + c < here)
           where[u][c] |= __hip_atomic_fetch_add(&cursor[wave][b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
       }
     }
@@ -1402,24 +1416,23 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
       }
     }
     __syncthreads();
-    // every element to its place in the image, or gathered here and onto the list; as a group is done
+    // every element to its place in the image, or with its index onto the list; as a group is done
     // with, the same group of the workgroup's next tile is asked for
 #pragma unroll
     for (int u = 0; u < kSegVecs; ++u) {
 #pragma unroll
       for (int c = 0; c < kVec; ++c) {
         const unsigned at = first + u * (kSegBlock * kVec) + c;
-        if (base + at < n) {
+        if (at < here) {
           const unsigned b = where[u][c] >> 16;
           const unsigned offset = min((unsigned)v[u][c] - b * cut.range, cut.range - 1u);
           const unsigned place = cursor[wave][b] + (where[u][c] & 0xffffu);
           if (place < cap) {
             entry[b * cap + place] = offset | (at << 16);
           } else {
-            const T x = table[min((unsigned)v[u][c], elems - 1u)];
             const unsigned k = atomicAdd(&listed, 1u);
             list_place[(size_t)base + k] = (unsigned short)at;
-            list_value[(size_t)base + k] = x;
+            list_index[(size_t)base + k] = min((unsigned)v[u][c], elems - 1u);
           }
         }
       }
@@ -1428,25 +1441,28 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
     __syncthreads();
     // the image goes to the tile's slots, eight entries a thread and step (128 bits of offsets, 128 bits
     // of positions), and is emptied on the way
-    for (unsigned q = threadIdx.x; q < words / 8u; q += kSegBlock) {
-      const Chunk lo = image[2u * q], hi = image[2u * q + 1u];
-      image[2u * q] = nothing;
-      image[2u * q + 1u] = nothing;
-      const unsigned b = q * 8u / cap, part = q * 8u - b * cap;
-      const size_t at = ((size_t)b * tiles + tile) * cap + part;
-      Chunk o, p;
-      o[0] = (lo[0] & 0xffffu) | (lo[1] << 16);
-      o[1] = (lo[2] & 0xffffu) | (lo[3] << 16);
-      o[2] = (hi[0] & 0xffffu) | (hi[1] << 16);
-      o[3] = (hi[2] & 0xffffu) | (hi[3] << 16);
-      p[0] = (lo[0] >> 16) | (lo[1] & 0xffff0000u);
-      p[1] = (lo[2] >> 16) | (lo[3] & 0xffff0000u);
-      p[2] = (hi[0] >> 16) | (hi[1] & 0xffff0000u);
-      p[3] = (hi[2] >> 16) | (hi[3] & 0xffff0000u);
-      *reinterpret_cast<Chunk *>(offsets + at) = o;
-      *reinterpret_cast<Chunk *>(places + at) = p;
+#pragma unroll
+    for (int k = 0; k < kCopies; ++k) {
+      const unsigned q = threadIdx.x + k * kSegBlock;
+      if (q < words / 8u) {
+        const Chunk lo = image[2u * q], hi = image[2u * q + 1u];
+        image[2u * q] = nothing;
+        image[2u * q + 1u] = nothing;
+        const size_t at = (size_t)copy_to[k] + (size_t)tile * cap;
+        Chunk o, p;
+        o[0] = (lo[0] & 0xffffu) | (lo[1] << 16);
+        o[1] = (lo[2] & 0xffffu) | (lo[3] << 16);
+        o[2] = (hi[0] & 0xffffu) | (hi[1] << 16);
+        o[3] = (hi[2] & 0xffffu) | (hi[3] << 16);
+        p[0] = (lo[0] >> 16) | (lo[1] & 0xffff0000u);
+        p[1] = (lo[2] >> 16) | (lo[3] & 0xffff0000u);
+        p[2] = (hi[0] >> 16) | (hi[1] & 0xffff0000u);
+        p[3] = (hi[2] >> 16) | (hi[3] & 0xffff0000u);
+        *reinterpret_cast<Chunk *>(offsets + at) = o;
+        *reinterpret_cast<Chunk *>(places + (size_t)tile * words + q * 8u) = p;
+      }
     }
-    for (unsigned k = threadIdx.x; k < kSegWaves * kSegMaxBins; k += kSegBlock) (&cursor[0][0])[k] = 0u;
+    clear_counters();
     if (threadIdx.x == 0) {
       list_count[tile] = listed;
       listed = 0u;
@@ -1484,37 +1500,49 @@ __global__ __launch_bounds__(kSegBlock) void seg_gather_kernel(const KArgs a, co
     if (threadIdx.x == 0) slice[kFineNone] = T();
   }
   __syncthreads();
-  // the range's slots lie one behind the other: a stream of 128-bit groups of eight offsets, of which this
-  // workgroup takes the stretch `part`
-  const unsigned groups = plan.tiles * (plan.cap / 8u);
+  // The range's slots lie one behind the other: a stream of groups of four offsets (64 bits in, 128 bits
+  // of values out, both without gaps from lane to lane), of which this workgroup takes the stretch
+  // `part`.  The reads of the next batch are under way while a batch is worked on.
+  const unsigned groups = plan.tiles * (plan.cap / 4u);
   const unsigned per = (groups + parts - 1u) / parts;
   const unsigned g_lo = part * per, g_hi = min(g_lo + per, groups);
   const size_t start = (size_t)b * plan.tiles * plan.cap;
   const __amdgpu_buffer_rsrc_t offset_buf =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned short *>(offsets + start), 0, (int)(groups * 16u), 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned short *>(offsets + start), 0, (int)(groups * 8u), 0x00020000);
   T *out = gathered + start;
-  constexpr int kInFlight = 4;
-  for (unsigned g0 = g_lo + threadIdx.x; g0 < g_hi; g0 += kSegBlock * kInFlight) {
-    Raw w[kInFlight];
+  constexpr int kInFlight = 8;
+  using Pair = unsigned __attribute__((ext_vector_type(2)));
+  auto fetch = [&](unsigned g0, Pair (&w)[kInFlight]) {       // a group past the stretch reads as zeros without a memory access
 #pragma unroll
     for (int u = 0; u < kInFlight; ++u) {
       const unsigned g = g0 + u * kSegBlock;
-      w[u] = __builtin_bit_cast(Raw, __builtin_amdgcn_raw_buffer_load_b128(offset_buf, g < g_hi ? (int)(g * 16u) : (int)0xfffffff0u, 0, kStream));
+      w[u] = __builtin_bit_cast(Pair, __builtin_amdgcn_raw_buffer_load_b64(offset_buf, g < g_hi ? (int)(g * 8u) : (int)0xfffffff0u, 0, kStream));
     }
+  };
+  auto work = [&](unsigned g0, const Pair (&w)[kInFlight]) {
 #pragma unroll
     for (int u = 0; u < kInFlight; ++u) {
       const unsigned g = g0 + u * kSegBlock;
       if (g < g_hi) {
-        TV x0, x1;
+        TV x;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          x0[k] = slice[(w[u][k / 2] >> (16 * (k & 1))) & 0xffffu];
-          x1[k] = slice[(w[u][2 + k / 2] >> (16 * (k & 1))) & 0xffffu];
-        }
-        *reinterpret_cast<TV *>(out + (size_t)g * 8u) = x0;
-        *reinterpret_cast<TV *>(out + (size_t)g * 8u + 4u) = x1;
+        for (int k = 0; k < 4; ++k) x[k] = slice[(w[u][k / 2] >> (16 * (k & 1))) & 0xffffu];
+        *reinterpret_cast<TV *>(out + (size_t)g * 4u) = x;
       }
     }
+  };
+  constexpr unsigned kStep = kSegBlock * kInFlight;
+  Pair w0[kInFlight], w1[kInFlight];
+  unsigned g0 = g_lo + threadIdx.x;
+  fetch(g0, w0);
+  while (g0 - threadIdx.x < g_hi) {                           // the same for the whole workgroup
+    fetch(g0 + kStep, w1);
+    work(g0, w0);
+    g0 += kStep;
+    if (!(g0 - threadIdx.x < g_hi)) break;
+    fetch(g0 + kStep, w0);
+    work(g0, w1);
+    g0 += kStep;
   }
 }
 
@@ -1540,45 +1568,69 @@ __device__ __forceinline__ unsigned wave_rows_below(const unsigned *start, unsig
   return lo;
 }
 
-template <class Op, class F, int KV>
+template <class Op, class F, int KV, int KT>
 __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, const unsigned short *places, const typename Op::T *gathered,
-                                                                 const unsigned short *list_place, const typename Op::T *list_value,
+                                                                 const unsigned short *list_place, const unsigned *list_index,
                                                                  const unsigned *list_count, unsigned *first_row,
                                                                  typename Op::T *head, typename Op::T *tail, const SegPlan plan) {
   using T = typename Op::T;
   using TV = T __attribute__((ext_vector_type(4)));
   using Pair = unsigned __attribute__((ext_vector_type(2)));
+  using RawI = int __attribute__((ext_vector_type(4)));
   __shared__ T term[kSegTile];                                // the tile's gathered values, then its terms, by position
-  __shared__ unsigned bounds[2];                              // the first row that starts in the tile, and in the next
+  __shared__ unsigned row_at[kSegRowsStaged + 1];             // where the tile's first kSegRowsStaged rows start, and the row after them
+  __shared__ unsigned bounds[3];                              // first row that starts in the tile; in the next tile; first row with elements here
   const unsigned *start = reinterpret_cast<const unsigned *>(a.in[kMaxIn - 1]);
   const T *values = static_cast<const T *>(a.in[KV]);
+  const T *table = static_cast<const T *>(a.in[KT]);
   T *y = static_cast<T *>(a.out[0]);
   const unsigned rows = (unsigned)a.aux, n = (unsigned)a.n;
   const unsigned tile = blockIdx.x, tiles = plan.tiles, cap = plan.cap, bins = plan.cut.bins;
   const unsigned t_lo = tile * kSegTile, t_hi = min(t_lo + (unsigned)kSegTile, n);
+  // the tile's stretch of `values` is asked for first and used last (a 32-bit word past the end of the array reads as zero)
+  constexpr int kSteps = kSegTile / (kSegRowsBlock * kVec);
+  RawI factor[kSteps];
+  {
+    const __amdgpu_buffer_rsrc_t value_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(values), 0, (int)(n * 4u), 0x00020000);
+#pragma unroll
+    for (int k = 0; k < kSteps; ++k) {
+      const unsigned e = (threadIdx.x + k * kSegRowsBlock) * kVec;
+      factor[k] = __builtin_amdgcn_raw_buffer_load_b128(value_buf, t_lo + e < n ? (int)((t_lo + e) * 4u) : (int)0xfffffff0u, 0, 0x2);
+    }
+  }
   // two waves look up the rows of the tile while the others begin with the values
   if (wave_id() == 0) {
     const unsigned r = wave_rows_below(start, rows, t_lo);
-    if (lane_id() == 0) { bounds[0] = r; first_row[tile] = r; }
+    // the row before reaches into the tile if it ends behind the tile's first position (start[rows] is the number of elements)
+    const bool reaches_in = r > 0u && start[r] > t_lo;
+    if (lane_id() == 0) { bounds[0] = r; bounds[2] = r - (reaches_in ? 1u : 0u); first_row[tile] = r; }
   } else if (wave_id() == 1) {
     const unsigned r = tile + 1u < tiles ? wave_rows_below(start, rows, t_hi) : rows;     // the last tile takes the empty rows at the end
     if (lane_id() == 0) bounds[1] = r;
   }
-  // the values back to their positions: four entries a thread and step, several steps under way
+  // The values back to their positions: four entries a thread and step, the reads of the next steps under
+  // way while those of the last ones are put in place.  Range and place of a step are carried along from
+  // step to step, not divided out.
   {
-    const unsigned quads_per_slot = cap / 4u, quads = bins * quads_per_slot;
+    const unsigned per_slot = cap / 4u, quads = bins * per_slot;
     constexpr int kAtOnce = 4;
-    for (unsigned q0 = threadIdx.x; q0 < quads; q0 += kSegRowsBlock * kAtOnce) {
-      TV x[kAtOnce];
-      Pair p[kAtOnce];
+    const unsigned step_slot = (unsigned)kSegRowsBlock / per_slot, step_part = (unsigned)kSegRowsBlock - step_slot * per_slot;
+    unsigned q = threadIdx.x;                                 // the step that is asked for next
+    unsigned b = q / per_slot, part = q - b * per_slot;
+    auto fetch = [&](TV (&x)[kAtOnce], Pair (&p)[kAtOnce]) {
 #pragma unroll
       for (int u = 0; u < kAtOnce; ++u) {
-        const unsigned q = min(q0 + u * kSegRowsBlock, quads - 1u);
-        const unsigned b = q / quads_per_slot, part = q - b * quads_per_slot;
-        const size_t at = ((size_t)b * tiles + tile) * cap + part * 4u;
+        const unsigned bb = min(b, bins - 1u);                // a step past the last one reads what the last range holds and is not used
+        const size_t at = ((size_t)bb * tiles + tile) * cap + part * 4u;
         x[u] = __builtin_nontemporal_load(reinterpret_cast<const TV *>(gathered + at));
-        p[u] = __builtin_nontemporal_load(reinterpret_cast<const Pair *>(places + at));
+        p[u] = __builtin_nontemporal_load(reinterpret_cast<const Pair *>(places + (size_t)tile * (bins * cap) + (size_t)min(q, quads - 1u) * 4u));
+        q += kSegRowsBlock;
+        b += step_slot;
+        part += step_part;
+        if (part >= per_slot) { part -= per_slot; ++b; }
       }
+    };
+    auto put = [&](unsigned q0, const TV (&x)[kAtOnce], const Pair (&p)[kAtOnce]) {
 #pragma unroll
       for (int u = 0; u < kAtOnce; ++u) {
         if (q0 + u * kSegRowsBlock < quads) {
@@ -1589,45 +1641,65 @@ __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, 
           }
         }
       }
+    };
+    constexpr unsigned kStep = kSegRowsBlock * kAtOnce;
+    TV x0[kAtOnce], x1[kAtOnce];
+    Pair p0[kAtOnce], p1[kAtOnce];
+    unsigned q0 = threadIdx.x;                                // the first step of the batch that is put in place next
+    fetch(x0, p0);
+    while (q0 - threadIdx.x < quads) {                        // the same for the whole workgroup
+      fetch(x1, p1);
+      put(q0, x0, p0);
+      q0 += kStep;
+      if (!(q0 - threadIdx.x < quads)) break;
+      fetch(x0, p0);
+      put(q0, x1, p1);
+      q0 += kStep;
     }
     const unsigned listed = list_count[tile];
-    for (unsigned k = threadIdx.x; k < listed; k += kSegRowsBlock) term[list_place[(size_t)t_lo + k]] = list_value[(size_t)t_lo + k];
+    for (unsigned k = threadIdx.x; k < listed; k += kSegRowsBlock) term[list_place[(size_t)t_lo + k]] = table[list_index[(size_t)t_lo + k]];
   }
   __syncthreads();
-  // times the tile's stretch of `values` (a 32-bit word past the end of the array reads as zero)
+  // Rows: the tile's own are those that start in it; the row that reaches into it from before (if there
+  // is one) comes first.  Where the first kSegRowsStaged of them start goes to LDS while the values are
+  // multiplied in.
+  const unsigned row_hi = bounds[1], r_first = bounds[2];
+  const unsigned staged = min(row_hi - r_first, (unsigned)kSegRowsStaged);
   {
-    const __amdgpu_buffer_rsrc_t value_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(values), 0, (int)(n * 4u), 0x00020000);
-    constexpr int kSteps = kSegTile / (kSegRowsBlock * kVec);
-    using RawI = int __attribute__((ext_vector_type(4)));
-    RawI w[kSteps];
+    constexpr int kLoads = kSegRowsStaged / kSegRowsBlock + 1;
+    unsigned at[kLoads];
 #pragma unroll
-    for (int k = 0; k < kSteps; ++k) {
-      const unsigned e = (threadIdx.x + k * kSegRowsBlock) * kVec;
-      w[k] = __builtin_amdgcn_raw_buffer_load_b128(value_buf, t_lo + e < n ? (int)((t_lo + e) * 4u) : (int)0xfffffff0u, 0, 0x2);
+    for (int k = 0; k < kLoads; ++k) {
+      const unsigned i = threadIdx.x + k * kSegRowsBlock;
+      at[k] = i <= staged ? start[r_first + i] : 0u;          // r_first + staged <= rows: start has that entry
     }
 #pragma unroll
     for (int k = 0; k < kSteps; ++k) {
       const unsigned e = (threadIdx.x + k * kSegRowsBlock) * kVec;
       TV g = *reinterpret_cast<const TV *>(&term[e]);
 #pragma unroll
-      for (int c = 0; c < kVec; ++c) g[c] = F::apply(a.p[0], from_bits<T>(w[k][c]), g[c]);
+      for (int c = 0; c < kVec; ++c) g[c] = F::apply(a.p[0], from_bits<T>(factor[k][c]), g[c]);
       *reinterpret_cast<TV *>(&term[e]) = g;
+    }
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+      const unsigned i = threadIdx.x + k * kSegRowsBlock;
+      if (i <= staged) row_at[i] = at[k];
     }
   }
   __syncthreads();
-  // Rows, four lanes each.  The tile's own rows are those that start in it; the row that reaches into it
-  // from before (if there is one) comes first.  A row that lies in the tile whole is stored; of a row
-  // that began before, the part in this tile is the tile's head; of the tile's last row, when it goes
-  // on, the part in this tile is the tile's tail.
-  const unsigned row_lo = bounds[0], row_hi = bounds[1];
-  const bool reaches_in = row_lo > 0u && start[min(row_lo, rows)] > t_lo;      // start[rows] is the number of elements
-  const unsigned r_first = row_lo - (reaches_in ? 1u : 0u);
+  // Four lanes a row.  A row that lies in the tile whole is stored; of a row that began before, the part
+  // in this tile is the tile's head; of the tile's last row, when it goes on, the part in this tile is
+  // the tile's tail.
   const unsigned ql = threadIdx.x & 3u;
   for (unsigned r0 = r_first; r0 < row_hi; r0 += kSegRowsBlock / 4) {           // the same for the whole workgroup
-    const unsigned r = r0 + threadIdx.x / 4u;
+    const unsigned r = r0 + threadIdx.x / 4u, i = r - r_first;
     const bool have = r < row_hi;
     unsigned lo = 0u, hi = 0u;
-    if (have) { lo = start[r]; hi = start[r + 1u]; }
+    if (have) {
+      lo = i < staged ? row_at[i] : start[r];
+      hi = i < staged ? row_at[i + 1u] : start[r + 1u];
+    }
     const unsigned from = max(lo, t_lo), to = min(hi, t_hi);
     T acc = Op::identity();
     for (unsigned k = from + ql; k < to; k += 4u) acc = Op::apply(acc, term[k - t_lo]);

@@ -191,7 +191,9 @@ template <class Op, class E> hipError_t launch_fold_fine(const KArgs &a, const L
 
 // ---- segmented fold over a gathered table, sorted through LDS: tables of more than one L2 and at most 2^24 elements ----
 // Ranges as long as LDS takes (so that a slot per range and tile is long and its slack small); a slot holds
-// the mean of a uniform spread plus four standard deviations, as far as the tile's slots fit their LDS image.
+// the mean of a uniform spread plus two standard deviations, as far as the tile's slots fit their LDS image:
+// every entry of a slot is written and read whether in use or not, while the element in a thousand that
+// finds its slot full costs a gather from memory and six bytes on the tile's list.
 inline SegPlan seg_plan(size_t elems, long long n) {
   SegPlan p = {{0, 0, 0, 0}, 0, 0};
   if (elems == 0 || n <= 0) return p;
@@ -199,14 +201,16 @@ inline SegPlan seg_plan(size_t elems, long long n) {
   p.cut = fine_cut(elems, want);
   if (p.cut.bins == 0 || p.cut.bins > (unsigned)kSegMaxBins) { p.cut.bins = 0; return p; }
   const double mean = (double)kSegTile / p.cut.bins;
-  unsigned cap = ((unsigned)(mean + 4.0 * std::sqrt(mean)) + 8 + 7) / 8 * 8;
+  // whole 128-byte lines of values per slot where that costs little (long slots), whole 128-bit groups anyway
+  const unsigned grain = mean >= 96.0 ? 32u : 8u;
+  unsigned cap = ((unsigned)(mean + 2.0 * std::sqrt(mean)) + grain - 1) / grain * grain;
   cap = std::min(cap, (unsigned)kSegImageWords / p.cut.bins / 8 * 8);
   p.cap = std::max(cap, 8u);
   p.tiles = (unsigned)(((size_t)n + kSegTile - 1) / kSegTile);
   return p;
 }
 // the pieces of the workspace, each on a 256-byte boundary
-struct SegSpace { size_t offsets, places, gathered, list_place, list_value, list_count, first_row, head, tail, total; };
+struct SegSpace { size_t offsets, places, gathered, list_place, list_index, list_count, first_row, head, tail, total; };
 inline SegSpace seg_space(const SegPlan &p) {
   auto up = [](size_t b) { return (b + 255) / 256 * 256; };
   const size_t entries = (size_t)p.cut.bins * p.tiles * p.cap, positions = (size_t)p.tiles * kSegTile;
@@ -216,7 +220,7 @@ inline SegSpace seg_space(const SegPlan &p) {
   s.places = at;     at += up(entries * 2);
   s.gathered = at;   at += up(entries * 4);
   s.list_place = at; at += up(positions * 2);
-  s.list_value = at; at += up(positions * 4);
+  s.list_index = at; at += up(positions * 4);
   s.list_count = at; at += up((size_t)p.tiles * 4);
   s.first_row = at;  at += up((size_t)p.tiles * 4);
   s.head = at;       at += up((size_t)p.tiles * 4);
@@ -246,21 +250,21 @@ hipError_t launch_foldseg_sorted(const KArgs &a, const LaunchCtx &c) {
   unsigned short *offsets = reinterpret_cast<unsigned short *>(w + s.offsets), *places = reinterpret_cast<unsigned short *>(w + s.places);
   T *gathered = reinterpret_cast<T *>(w + s.gathered);
   unsigned short *list_place = reinterpret_cast<unsigned short *>(w + s.list_place);
-  T *list_value = reinterpret_cast<T *>(w + s.list_value);
+  unsigned *list_index = reinterpret_cast<unsigned *>(w + s.list_index);
   unsigned *list_count = reinterpret_cast<unsigned *>(w + s.list_count), *first_row = reinterpret_cast<unsigned *>(w + s.first_row);
   T *head = reinterpret_cast<T *>(w + s.head), *tail = reinterpret_cast<T *>(w + s.tail);
   const int cus = device_compute_units();
   const unsigned units = (unsigned)(cus > 0 ? cus : 256);
-  hipError_t e = launch_k(&seg_bin_kernel<T, KI, KT>, std::min(p.tiles, units), c.stream, (int)kSegBlock, a, offsets, places,
-                          list_place, list_value, list_count, p, elems);
+  hipError_t e = launch_k(&seg_bin_kernel<KI>, std::min(p.tiles, units), c.stream, (int)kSegBlock, a, offsets, places,
+                          list_place, list_index, list_count, p, elems);
   if (e != hipSuccess) return e;
   // a table range is read into LDS by every workgroup that works on it: two workgroups per compute unit in all
   const unsigned parts = std::max(1u, (2 * units + p.cut.bins - 1) / p.cut.bins);
   e = launch_k(&seg_gather_kernel<T, KT>, p.cut.bins * parts, c.stream, (int)kSegBlock, a, static_cast<const unsigned short *>(offsets),
                gathered, p, elems, parts);
   if (e != hipSuccess) return e;
-  e = launch_k(&seg_rows_kernel<Op, F, KV>, p.tiles, c.stream, (int)kSegRowsBlock, a, static_cast<const unsigned short *>(places),
-               static_cast<const T *>(gathered), static_cast<const unsigned short *>(list_place), static_cast<const T *>(list_value),
+  e = launch_k(&seg_rows_kernel<Op, F, KV, KT>, p.tiles, c.stream, (int)kSegRowsBlock, a, static_cast<const unsigned short *>(places),
+               static_cast<const T *>(gathered), static_cast<const unsigned short *>(list_place), static_cast<const unsigned *>(list_index),
                static_cast<const unsigned *>(list_count), first_row, head, tail, p);
   if (e != hipSuccess) return e;
   return launch_k(&seg_join_kernel<Op>, (p.tiles + kBlock - 1) / kBlock, c.stream, a, static_cast<const unsigned *>(first_row),
