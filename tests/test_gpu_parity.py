@@ -252,14 +252,14 @@ def test_spmv_column_blocked(rows, ncols, mean_len):
 
 @pytest.mark.parametrize("shape", ["uniform", "crowded", "long rows", "empty ends", "one column", "many ranges"])
 def test_spmv_sorted_through_lds(shape):
-    # from two million elements on, over a table that no L2 holds, the segmented fold sorts its elements by
+    # from four million elements on, over a table that no L2 holds, the segmented fold sorts its elements by
     # table range, gathers from LDS and puts the values back in place (four kernels, everything between
     # them in scratch).  Columns spread evenly, columns that crowd into few ranges or one (slots overflow:
     # those elements go through the tiles' lists), rows longer than several tiles, rows that end exactly
     # on a tile boundary, runs of empty rows at both ends and around tile boundaries, a table that is cut
     # into many short ranges, element counts off the tile and off the 128-bit group.
     rng = np.random.default_rng(len(shape) * 1000 + 7)
-    rows, ncols = 190001, 1500007
+    rows, ncols = 300001, 1500007
     lengths = rng.poisson(16.0, size=rows).astype(np.int64)
     if shape == "long rows":
         lengths[rng.integers(0, rows, size=6)] = 40000
@@ -275,7 +275,7 @@ def test_spmv_sorted_through_lds(shape):
         ncols = (1 << 24) - 3
     w = C.spmv(lengths=lengths, seed=11, ncols=ncols)
     nnz = w.inputs["col"].shape[0]
-    assert nnz >= 1 << 21
+    assert nnz >= 1 << 22
     if shape == "crowded":
         w.inputs["col"] = np.where(rng.random(nnz) < 0.9, rng.integers(0, 3000, size=nnz), rng.integers(0, ncols, size=nnz)).astype(np.int32)
     elif shape == "one column":
