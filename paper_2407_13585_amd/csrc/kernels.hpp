@@ -1471,9 +1471,31 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
   }
 }
 
+// The number of rows r in [0, rows) with start[r] < target, start ascending: all lanes of a wave take
+// part, sixty-four probes a step.
+__device__ __forceinline__ unsigned wave_rows_below(const unsigned *start, unsigned rows, unsigned target) {
+  unsigned lo = 0, len = rows;
+  const unsigned lane = (unsigned)lane_id();
+  while (len != 0u) {                                         // the same for the whole wave
+    const unsigned stride = (len + kWave - 1u) / kWave;
+    const unsigned probe = lo + (lane + 1u) * stride - 1u;    // the last row of this lane's stretch
+    const bool inside = probe < lo + len;
+    const bool below = inside && start[probe] < target;
+    const unsigned k = (unsigned)__builtin_popcountll(__builtin_amdgcn_ballot_w64(below));
+    // stretches 0 .. k-1 lie below the target; the first row at or above it is in stretch k, whose last
+    // row is known not to be below if that row exists
+    const unsigned next = lo + k * stride;
+    const unsigned left = lo + len > next ? lo + len - next : 0u;
+    const bool last_known = k < (unsigned)kWave && next + stride - 1u < lo + len;
+    len = last_known ? stride - 1u : min(left, stride);
+    lo = next;
+  }
+  return lo;
+}
+
 template <class T, int KT>
 __global__ __launch_bounds__(kSegBlock) void seg_gather_kernel(const KArgs a, const unsigned short *offsets, T *gathered,
-                                                               const SegPlan plan, unsigned elems, unsigned parts) {
+                                                               unsigned *first_row, const SegPlan plan, unsigned elems, unsigned parts) {
   using Raw = unsigned __attribute__((ext_vector_type(4)));
   using RawI = int __attribute__((ext_vector_type(4)));
   using TV = T __attribute__((ext_vector_type(4)));
@@ -1491,6 +1513,16 @@ __global__ __launch_bounds__(kSegBlock) void seg_gather_kernel(const KArgs a, co
 #pragma unroll
     for (int u = 0; u < kAhead; ++u)
       v[u] = __builtin_amdgcn_raw_buffer_load_b128(range_buf, (int)((threadIdx.x + u * kSegBlock) * (kVec * 4u)), 0, 0);
+    // On the side, for the third kernel: the first row that starts in a tile, for every tile, a wave a tile
+    // (the waves of this launch share the tiles out); the lookups run while the table range is on its way.
+    {
+      const unsigned *row_start = reinterpret_cast<const unsigned *>(a.in[kMaxIn - 1]);
+      const unsigned rows = (unsigned)a.aux;
+      for (unsigned t = blockIdx.x * kSegWaves + (unsigned)wave_id(); t < plan.tiles; t += gridDim.x * kSegWaves) {
+        const unsigned r = wave_rows_below(row_start, rows, t * kSegTile);
+        if (lane_id() == 0) first_row[t] = r;
+      }
+    }
 #pragma unroll
     for (int u = 0; u < kAhead; ++u) {
       const unsigned i = (threadIdx.x + u * kSegBlock) * kVec;
@@ -1546,32 +1578,10 @@ __global__ __launch_bounds__(kSegBlock) void seg_gather_kernel(const KArgs a, co
   }
 }
 
-// The number of rows r in [0, rows) with start[r] < target, start ascending: all lanes of a wave take
-// part, sixty-four probes a step.
-__device__ __forceinline__ unsigned wave_rows_below(const unsigned *start, unsigned rows, unsigned target) {
-  unsigned lo = 0, len = rows;
-  const unsigned lane = (unsigned)lane_id();
-  while (len != 0u) {                                         // the same for the whole wave
-    const unsigned stride = (len + kWave - 1u) / kWave;
-    const unsigned probe = lo + (lane + 1u) * stride - 1u;    // the last row of this lane's stretch
-    const bool inside = probe < lo + len;
-    const bool below = inside && start[probe] < target;
-    const unsigned k = (unsigned)__builtin_popcountll(__builtin_amdgcn_ballot_w64(below));
-    // stretches 0 .. k-1 lie below the target; the first row at or above it is in stretch k, whose last
-    // row is known not to be below if that row exists
-    const unsigned next = lo + k * stride;
-    const unsigned left = lo + len > next ? lo + len - next : 0u;
-    const bool last_known = k < (unsigned)kWave && next + stride - 1u < lo + len;
-    len = last_known ? stride - 1u : min(left, stride);
-    lo = next;
-  }
-  return lo;
-}
-
 template <class Op, class F, int KV, int KT>
 __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, const unsigned short *places, const typename Op::T *gathered,
                                                                  const unsigned short *list_place, const unsigned *list_index,
-                                                                 const unsigned *list_count, unsigned *first_row,
+                                                                 const unsigned *list_count, const unsigned *first_row,
                                                                  typename Op::T *head, typename Op::T *tail, const SegPlan plan) {
   using T = typename Op::T;
   using TV = T __attribute__((ext_vector_type(4)));
@@ -1579,7 +1589,6 @@ __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, 
   using RawI = int __attribute__((ext_vector_type(4)));
   __shared__ T term[kSegTile];                                // the tile's gathered values, then its terms, by position
   __shared__ unsigned row_at[kSegRowsStaged + 1];             // where the tile's first kSegRowsStaged rows start, and the row after them
-  __shared__ unsigned bounds[3];                              // first row that starts in the tile; in the next tile; first row with elements here
   const unsigned *start = reinterpret_cast<const unsigned *>(a.in[kMaxIn - 1]);
   const T *values = static_cast<const T *>(a.in[KV]);
   const T *table = static_cast<const T *>(a.in[KT]);
@@ -1598,16 +1607,11 @@ __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, 
       factor[k] = __builtin_amdgcn_raw_buffer_load_b128(value_buf, t_lo + e < n ? (int)((t_lo + e) * 4u) : (int)0xfffffff0u, 0, 0x2);
     }
   }
-  // two waves look up the rows of the tile while the others begin with the values
-  if (wave_id() == 0) {
-    const unsigned r = wave_rows_below(start, rows, t_lo);
-    // the row before reaches into the tile if it ends behind the tile's first position (start[rows] is the number of elements)
-    const bool reaches_in = r > 0u && start[r] > t_lo;
-    if (lane_id() == 0) { bounds[0] = r; bounds[2] = r - (reaches_in ? 1u : 0u); first_row[tile] = r; }
-  } else if (wave_id() == 1) {
-    const unsigned r = tile + 1u < tiles ? wave_rows_below(start, rows, t_hi) : rows;     // the last tile takes the empty rows at the end
-    if (lane_id() == 0) bounds[1] = r;
-  }
+  // the first row that starts in this tile and in the next (the last tile takes the empty rows at the end);
+  // the row before reaches into the tile if it ends behind the tile's first position (start[rows] is the
+  // number of elements)
+  const unsigned row_lo = first_row[tile], row_hi = tile + 1u < tiles ? first_row[tile + 1u] : rows;
+  const unsigned r_first = row_lo - (row_lo > 0u && start[row_lo] > t_lo ? 1u : 0u);
   // The values back to their positions: four entries a thread and step, the reads of the next steps under
   // way while those of the last ones are put in place.  Range and place of a step are carried along from
   // step to step, not divided out.
@@ -1617,13 +1621,18 @@ __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, 
     const unsigned step_slot = (unsigned)kSegRowsBlock / per_slot, step_part = (unsigned)kSegRowsBlock - step_slot * per_slot;
     unsigned q = threadIdx.x;                                 // the step that is asked for next
     unsigned b = q / per_slot, part = q - b * per_slot;
+    // raw buffer views (a launch's slots stay below 2^31 bytes): a step past the last one reads zeros and is not used
+    const __amdgpu_buffer_rsrc_t value_view = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<T *>(gathered), 0, (int)(bins * tiles * cap * 4u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t place_view = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned short *>(places + (size_t)tile * (bins * cap)), 0, (int)(bins * cap * 2u), 0x00020000);
     auto fetch = [&](TV (&x)[kAtOnce], Pair (&p)[kAtOnce]) {
 #pragma unroll
       for (int u = 0; u < kAtOnce; ++u) {
-        const unsigned bb = min(b, bins - 1u);                // a step past the last one reads what the last range holds and is not used
-        const size_t at = ((size_t)bb * tiles + tile) * cap + part * 4u;
-        x[u] = __builtin_nontemporal_load(reinterpret_cast<const TV *>(gathered + at));
-        p[u] = __builtin_nontemporal_load(reinterpret_cast<const Pair *>(places + (size_t)tile * (bins * cap) + (size_t)min(q, quads - 1u) * 4u));
+        const bool real = q < quads;
+        x[u] = __builtin_bit_cast(TV, __builtin_amdgcn_raw_buffer_load_b128(
+            value_view, real ? (int)((b * tiles * cap + part * 4u) * 4u) : (int)0xfffffff0u, (int)(tile * cap * 4u), 0x2));
+        p[u] = __builtin_bit_cast(Pair, __builtin_amdgcn_raw_buffer_load_b64(place_view, real ? (int)(q * 8u) : (int)0xfffffff0u, 0, 0x2));
         q += kSegRowsBlock;
         b += step_slot;
         part += step_part;
@@ -1663,7 +1672,6 @@ __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, 
   // Rows: the tile's own are those that start in it; the row that reaches into it from before (if there
   // is one) comes first.  Where the first kSegRowsStaged of them start goes to LDS while the values are
   // multiplied in.
-  const unsigned row_hi = bounds[1], r_first = bounds[2];
   const unsigned staged = min(row_hi - r_first, (unsigned)kSegRowsStaged);
   {
     constexpr int kLoads = kSegRowsStaged / kSegRowsBlock + 1;
@@ -1701,8 +1709,18 @@ __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, 
       hi = i < staged ? row_at[i + 1u] : start[r + 1u];
     }
     const unsigned from = max(lo, t_lo), to = min(hi, t_hi);
+    // a lane takes every fourth term of its row, the first kRowAhead of them read together
+    constexpr int kRowAhead = 8;
+    T first_terms[kRowAhead];
+#pragma unroll
+    for (int j = 0; j < kRowAhead; ++j) {
+      const unsigned k = from + ql + 4u * j;
+      first_terms[j] = k < to ? term[k - t_lo] : Op::identity();
+    }
     T acc = Op::identity();
-    for (unsigned k = from + ql; k < to; k += 4u) acc = Op::apply(acc, term[k - t_lo]);
+#pragma unroll
+    for (int j = 0; j < kRowAhead; ++j) acc = Op::apply(acc, first_terms[j]);
+    for (unsigned k = from + ql + 4u * kRowAhead; k < to; k += 4u) acc = Op::apply(acc, term[k - t_lo]);
     acc = Op::apply(acc, dpp_move<0xB1>(Op::identity(), acc));    // quad_perm [1,0,3,2]
     acc = Op::apply(acc, dpp_move<0x4E>(Op::identity(), acc));    // quad_perm [2,3,0,1]
     if (have && ql == 0u) {

@@ -263,11 +263,11 @@ hipError_t launch_foldseg_sorted(const KArgs &a, const LaunchCtx &c) {
   // a table range is read into LDS by every workgroup that works on it: two workgroups per compute unit in all
   const unsigned parts = std::max(1u, (2 * units + p.cut.bins - 1) / p.cut.bins);
   e = launch_k(&seg_gather_kernel<T, KT>, p.cut.bins * parts, c.stream, (int)kSegBlock, a, static_cast<const unsigned short *>(offsets),
-               gathered, p, elems, parts);
+               gathered, first_row, p, elems, parts);
   if (e != hipSuccess) return e;
   e = launch_k(&seg_rows_kernel<Op, F, KV, KT>, p.tiles, c.stream, (int)kSegRowsBlock, a, static_cast<const unsigned short *>(places),
                static_cast<const T *>(gathered), static_cast<const unsigned short *>(list_place), static_cast<const unsigned *>(list_index),
-               static_cast<const unsigned *>(list_count), first_row, head, tail, p);
+               static_cast<const unsigned *>(list_count), static_cast<const unsigned *>(first_row), head, tail, p);
   if (e != hipSuccess) return e;
   return launch_k(&seg_join_kernel<Op>, (p.tiles + kBlock - 1) / kBlock, c.stream, a, static_cast<const unsigned *>(first_row),
                   static_cast<const T *>(head), static_cast<const T *>(tail), p.tiles);
