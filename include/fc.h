@@ -103,8 +103,9 @@ typedef enum fc_fn {
                                   every gather issued at the position that asks for it (section 2: a fold inside a
                                   cluster is one stage of a parallel reduction).  Without the flag the library may, for
                                   a gathered table larger than the L2 of an XCD, run a kernel that visits the positions
-                                  in another order (indices sorted by table range in a first kernel; the streams of
-                                  a segmented fold read once per column range), which is faster and, the reducers
+                                  in another order and in more than one kernel (elements sorted by table range in a
+                                  first kernel and gathered from on-chip memory; for small inputs the streams of a
+                                  segmented fold read once per column range), which is faster and, the reducers
                                   being commutative, gives the same result up to rounding */
 
 typedef struct fc_node {
