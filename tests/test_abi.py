@@ -208,6 +208,39 @@ def test_workspace_of_the_column_blocked_segmented_fold_is_part_of_scratch():
     assert fc.fc_scratch_bytes(g2, part2) == need - 32 * rows
 
 
+def test_workspace_of_the_sorted_segmented_fold_is_part_of_scratch():
+    # graph only, no data: from four million elements on, over a table that no L2 holds (up to 2^24 elements),
+    # an SpMV-shaped cluster sorts its elements through LDS; the sorted offsets and positions (2 + 2 bytes), the
+    # gathered values (4 bytes), all with the slots' slack, and room for every element on its tile's overflow
+    # list (6 bytes) live in scratch.  The static scratch buffer is too small for it and says so.
+    def program(rows, ncols, nnz):
+        g = Graph()
+        g.add("x", "input", "f32", (ncols,))
+        g.add("col", "input", "i32", (nnz,))
+        g.add("vals", "input", "f32", (nnz,))
+        g.add("off", "input", "i32", (rows + 1,))
+        g.add("g", "gather", "f32", (nnz,), args=("col", "x"))
+        g.add("p", "map", "f32", (nnz,), fn="mul2", args=("vals", "g"))
+        g.add("y", "foldseg", "f32", (rows,), fn="add", args=("p", "off"), output=True)
+        return g
+    nnz = (1 << 22) + 5
+    fake = (0x10000000, 1 << 30)
+    for ncols in (1 << 22, 1500007, (1 << 24) - 3):
+        g = program(300000, ncols, nnz)
+        part = fc.fc_plan(g, "bytes")
+        assert part.n_clusters == 1 and "sorted through LDS" in fc.fc_cluster_kernel(g, part, 0)
+        need = fc.fc_scratch_bytes(g, part) - B.FC_SCRATCH_CONTROL_BYTES
+        assert 14 * nnz <= need <= 19 * nnz, (ncols, need / nnz)
+        bufs = {n.name: fake for n in g.nodes if n.kind == "input" or n.output}
+        expect("FC_E_SCRATCH", fc.fc_run_fused, g, part, bufs, (0x10000000, B.FC_SCRATCH_CONTROL_BYTES + 13 * nnz))
+        expect("FC_E_LIMIT", fc.fc_run_fused_static, g, part, bufs)
+    # fewer elements, a table beyond 2^24 elements, or the single-pass flag: other kernels
+    from workloads import single_pass
+    for g in (program(100000, 1 << 22, (1 << 22) - 1), program(300000, (1 << 24) + 1, nnz), single_pass(program(300000, 1 << 22, nnz))):
+        part = fc.fc_plan(g, "bytes")
+        assert "sorted through LDS" not in fc.fc_cluster_kernel(g, part, 0)
+
+
 def test_workspace_of_the_fold_over_sorted_gather_indices_is_part_of_scratch():
     # graph only, no data: a fold over a gather from a 16 MiB table takes the kernel pair that sorts
     # the indices by table range first; the sorted indices live in scratch
