@@ -260,8 +260,9 @@ hipError_t launch_foldseg_sorted(const KArgs &a, const LaunchCtx &c) {
   hipError_t e = launch_k(&seg_bin_kernel<KI>, std::min(p.tiles, units), c.stream, (int)kSegBlock, a, offsets, places,
                           list_place, list_index, list_count, p, elems);
   if (e != hipSuccess) return e;
-  // a table range is read into LDS by every workgroup that works on it: two workgroups per compute unit in all
-  const unsigned parts = std::max(1u, (2 * units + p.cut.bins - 1) / p.cut.bins);
+  // a table range is read into LDS by every workgroup that works on it: one workgroup per compute unit in all
+  // (they fill its LDS; with two rounds of workgroups the second round's range reads stood in the open: 106 us against 102)
+  const unsigned parts = std::max(1u, (units + p.cut.bins - 1) / p.cut.bins);
   e = launch_k(&seg_gather_kernel<T, KT>, p.cut.bins * parts, c.stream, (int)kSegBlock, a, static_cast<const unsigned short *>(offsets),
                gathered, first_row, p, elems, parts);
   if (e != hipSuccess) return e;
