@@ -420,6 +420,13 @@ def main() -> int:
             + (f"  materialise p {arm_ms[c]['materialise_p'] * 1e3:8.1f} us ({arm_ms[c]['materialise_p'] / gpu_ms[c]:.2f}x)" if "materialise_p" in arm_ms[c] else ""))
     dom = max(cfgs, key=lambda c: gpu_ms[c])
     achieved = work[dom].lb_bytes / (gpu_ms[dom] * 1e-3) / 1e9
+    # the same sum with every cluster that has a single-pass form run in that form (gathers in position order, one
+    # kernel, nothing sorted): what the step costs when each cluster is the one pass the paper describes
+    sp_ms = {c: arm_ms[c].get("single_pass", gpu_ms[c]) for c in cfgs}
+    single_pass_sum = sum(sp_ms.values()) if any("single_pass" in arm_ms[c] for c in cfgs) else None
+    if single_pass_sum is not None:
+        log(f"all pipelines: {sum(gpu_ms.values()) * 1e3:.1f} us with the default kernels ({lb_total / (sum(gpu_ms.values()) * 1e-3) / 1e9:.0f} GB/s), "
+            f"{single_pass_sum * 1e3:.1f} us with the gather clusters as single passes ({lb_total / (single_pass_sum * 1e-3) / 1e9:.0f} GB/s)")
     out = {
         "metric": "fused pipeline GB/s (fused-traffic lower bound / time)",
         "value": round(lb_total / (ms_per_step * 1e-3) / 1e9, 2),
@@ -432,6 +439,11 @@ def main() -> int:
                    "all five benchmark pipelines, fused: " + ", ".join(work[c].name for c in cfgs)},
         "gpu_sum_kernel_ms": round(sum(gpu_ms.values()), 5),
         "frac_hbm_peak": round(lb_total / (sum(gpu_ms.values()) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "single_pass_clusters": None if single_pass_sum is None else {
+            "gpu_sum_kernel_ms": round(single_pass_sum, 5), "GB/s": round(lb_total / (single_pass_sum * 1e-3) / 1e9, 1),
+            "note": "the sum of the per-pipeline times with the gather pipelines' clusters run as single passes "
+                    "(FC_NODE_SINGLE_PASS: one kernel, gathers in position order); `value` uses the default kernels, "
+                    "which sort the gathered positions by table range first"},
         "copy_ceiling_GBs": round(copy_gbs, 1),
         "verified_against_oracle": verified,
         "per_config": per,
