@@ -1696,37 +1696,50 @@ __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, 
     }
   }
   __syncthreads();
-  // Four lanes a row.  A row that lies in the tile whole is stored; of a row that began before, the part
-  // in this tile is the tile's head; of the tile's last row, when it goes on, the part in this tile is
-  // the tile's tail.
+  // Four lanes a row, kRowsAtOnce rows a lane and step: their starts are read from LDS together, then the
+  // first kRowAhead terms a lane takes of each (every fourth of the row), so that a step is two round trips
+  // to LDS and not two per row.  A row that lies in the tile whole is stored; of a row that began before,
+  // the part in this tile is the tile's head; of the tile's last row, when it goes on, the part in this
+  // tile is the tile's tail.
   const unsigned ql = threadIdx.x & 3u;
-  for (unsigned r0 = r_first; r0 < row_hi; r0 += kSegRowsBlock / 4) {           // the same for the whole workgroup
-    const unsigned r = r0 + threadIdx.x / 4u, i = r - r_first;
-    const bool have = r < row_hi;
-    unsigned lo = 0u, hi = 0u;
-    if (have) {
-      lo = i < staged ? row_at[i] : start[r];
-      hi = i < staged ? row_at[i + 1u] : start[r + 1u];
-    }
-    const unsigned from = max(lo, t_lo), to = min(hi, t_hi);
-    // a lane takes every fourth term of its row, the first kRowAhead of them read together
-    constexpr int kRowAhead = 8;
-    T first_terms[kRowAhead];
+  constexpr int kRowsAtOnce = 4, kRowAhead = 6;
+  constexpr unsigned kRowsPerStep = kSegRowsBlock / 4;
+  for (unsigned r0 = r_first; r0 < row_hi; r0 += kRowsPerStep * kRowsAtOnce) {  // the same for the whole workgroup
+    unsigned lo[kRowsAtOnce], hi[kRowsAtOnce];
 #pragma unroll
-    for (int j = 0; j < kRowAhead; ++j) {
-      const unsigned k = from + ql + 4u * j;
-      first_terms[j] = k < to ? term[k - t_lo] : Op::identity();
+    for (int m = 0; m < kRowsAtOnce; ++m) {
+      const unsigned r = r0 + m * kRowsPerStep + threadIdx.x / 4u, i = r - r_first;
+      lo[m] = hi[m] = 0u;
+      if (r < row_hi) {
+        lo[m] = i < staged ? row_at[i] : start[r];
+        hi[m] = i < staged ? row_at[i + 1u] : start[r + 1u];
+      }
     }
-    T acc = Op::identity();
+    T first_terms[kRowsAtOnce][kRowAhead];
 #pragma unroll
-    for (int j = 0; j < kRowAhead; ++j) acc = Op::apply(acc, first_terms[j]);
-    for (unsigned k = from + ql + 4u * kRowAhead; k < to; k += 4u) acc = Op::apply(acc, term[k - t_lo]);
-    acc = Op::apply(acc, dpp_move<0xB1>(Op::identity(), acc));    // quad_perm [1,0,3,2]
-    acc = Op::apply(acc, dpp_move<0x4E>(Op::identity(), acc));    // quad_perm [2,3,0,1]
-    if (have && ql == 0u) {
-      if (lo < t_lo) head[tile] = acc;
-      else if (hi > t_hi) tail[tile] = acc;
-      else y[r] = acc;
+    for (int m = 0; m < kRowsAtOnce; ++m) {
+      const unsigned from = max(lo[m], t_lo), to = min(hi[m], t_hi);
+#pragma unroll
+      for (int j = 0; j < kRowAhead; ++j) {
+        const unsigned k = from + ql + 4u * j;
+        first_terms[m][j] = k < to ? term[k - t_lo] : Op::identity();
+      }
+    }
+#pragma unroll
+    for (int m = 0; m < kRowsAtOnce; ++m) {
+      const unsigned r = r0 + m * kRowsPerStep + threadIdx.x / 4u;
+      const unsigned from = max(lo[m], t_lo), to = min(hi[m], t_hi);
+      T acc = Op::identity();
+#pragma unroll
+      for (int j = 0; j < kRowAhead; ++j) acc = Op::apply(acc, first_terms[m][j]);
+      for (unsigned k = from + ql + 4u * kRowAhead; k < to; k += 4u) acc = Op::apply(acc, term[k - t_lo]);
+      acc = Op::apply(acc, dpp_move<0xB1>(Op::identity(), acc));    // quad_perm [1,0,3,2]
+      acc = Op::apply(acc, dpp_move<0x4E>(Op::identity(), acc));    // quad_perm [2,3,0,1]
+      if (r < row_hi && ql == 0u) {
+        if (lo[m] < t_lo) head[tile] = acc;
+        else if (hi[m] > t_hi) tail[tile] = acc;
+        else y[r] = acc;
+      }
     }
   }
 }
