@@ -907,12 +907,14 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
     __syncthreads();
     // inside a range's slot the waves in order: thread t < kFineBins turns the counts of range t into first places
     if (threadIdx.x < (unsigned)kFineBins) {
+      unsigned count[kFineWaves];                             // all read before any is written: one round trip to LDS, not sixteen
+#pragma unroll
+      for (int w = 0; w < kFineWaves; ++w) count[w] = cursor[w][threadIdx.x];
       unsigned run = 0;
 #pragma unroll
       for (int w = 0; w < kFineWaves; ++w) {
-        const unsigned c = cursor[w][threadIdx.x];
         cursor[w][threadIdx.x] = run;
-        run += c;
+        run += count[w];
       }
     }
     __syncthreads();
@@ -1407,12 +1409,14 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
     __syncthreads();
     // inside a range's slot the waves in order: thread t < bins turns the counts of range t into first places
     if (threadIdx.x < bins) {
+      unsigned count[kSegWaves];                              // all read before any is written: one round trip to LDS, not sixteen
+#pragma unroll
+      for (int w = 0; w < kSegWaves; ++w) count[w] = cursor[w][threadIdx.x];
       unsigned run = 0;
 #pragma unroll
       for (int w = 0; w < kSegWaves; ++w) {
-        const unsigned c = cursor[w][threadIdx.x];
         cursor[w][threadIdx.x] = run;
-        run += c;
+        run += count[w];
       }
     }
     __syncthreads();
