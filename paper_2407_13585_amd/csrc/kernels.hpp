@@ -1312,20 +1312,20 @@ __global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, 
 //     does (an LDS counter per wave and range, the tile's slots built in LDS as they go to memory),
 //     and keeps two 16-bit numbers per element, in two arrays: the offset inside the range and the
 //     position inside the tile (offsets slot after slot for every range, positions tile after tile).
-//     An element that finds its slot full (about one in a thousand of evenly spread indices; most
+//     An element that finds its slot full (a few in a thousand of evenly spread indices; most
 //     of indices that crowd into few ranges) goes onto the tile's list of (position, index) pairs.
 //  2. seg_gather_kernel: a workgroup reads a table range into LDS and turns a stretch of the
 //     range's offsets into values, slot for slot (the slots of a range lie one behind the other).
 //  3. seg_rows_kernel: a workgroup per tile puts the tile's values (one slot per range, then those
-//     of the list, gathered from memory) back at their positions in LDS, multiplies by the tile's stretch of `values`, and adds
-//     up the rows, four lanes a row.  A row belongs to the tile it starts in; the part of a row
+//     of the list, gathered from memory) back at their positions in LDS, multiplies by the tile's
+//     stretch of `values`, and adds up the rows, four lanes a row.  A row belongs to the tile it starts in; the part of a row
 //     that lies in another tile than its own, and the part of a tile's last row when the row goes
 //     on, are kept per tile,
 //  4. and seg_join_kernel adds those up, tile after tile, for the rows that cross a tile boundary.
 //
 // Every element has one place at every stage and every sum a fixed order: the same bits on every
 // launch.  Bytes per element: 4 + 4 (first kernel), 2 + 4 (second), 4 + 2 + 4 (third), times the
-// slots' slack (a slot holds the mean of a uniform spread plus two standard deviations).
+// slots' slack (a slot holds little more than the mean of a uniform spread: what overflows is listed).
 constexpr int kSegBlock = 1024;                        // threads per workgroup of the first two kernels
 constexpr int kSegWaves = kSegBlock / kWave;
 constexpr int kSegTile = 16384;                        // positions per tile: 14-bit positions, a tile of values is 64 KiB of LDS
@@ -1335,7 +1335,10 @@ constexpr int kSegMaxBins = 512;
 constexpr int kSegRowsBlock = 512;                     // threads per workgroup of the third kernel: two workgroups per compute unit
 constexpr int kSegRowsStaged = 2048;                   // row starts of a tile kept in LDS (a tile of 16-element rows has 1024)
 constexpr unsigned kSegNoPlace = 0xffffu;              // the position of a slot's place that holds no element
-constexpr unsigned kSegNothing = kFineNone | (kSegNoPlace << 16);
+constexpr int kSegSlice = 36864;                       // elements of a table range at most: 144 KiB of LDS in the second kernel
+constexpr unsigned kSegNone = kSegSlice;               // the offset of a slot's place that holds no element
+constexpr unsigned kSegNothing = kSegNone | (kSegNoPlace << 16);
+static_assert(kSegNone < 65536u, "offsets are 16-bit numbers");
 static_assert(kSegVecs * kSegBlock * kVec == kSegTile && kSegTile <= (int)kSegNoPlace, "whole reads; positions are 16-bit numbers");
 
 // Where the pieces lie in the workspace (element counts; every array starts on a 256-byte boundary).
@@ -1354,6 +1357,7 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
   __shared__ unsigned cursor[kSegWaves][kSegMaxBins];       // per (wave, range): the count, then the wave's first place in the slot
   __shared__ Chunk image[kSegImageWords / 4];               // the tile's slots: offset | position << 16 per element
   __shared__ unsigned listed;                               // elements on the tile's list so far
+  __shared__ unsigned list_wait[kSegWaves][kWave][2];       // per wave: (position, index) of elements that wait to go onto the list together
   unsigned *entry = reinterpret_cast<unsigned *>(image);
   const int *index = static_cast<const int *>(a.in[KI]);
   const FineCut cut = plan.cut;
@@ -1390,6 +1394,7 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
   if (threadIdx.x == 0) listed = 0u;
   __syncthreads();
   for (unsigned tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    if (threadIdx.x == 0) listed = 0u;                      // read last before the barrier that ended the tile before, added to after the next two
     const unsigned first = threadIdx.x * kVec;              // this thread's first position in the tile, group 0
     const unsigned base = tile * kSegTile;
     // rank of every element among the wave's elements of its range (range << 16 | rank is kept).  An index
@@ -1420,28 +1425,47 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
       }
     }
     __syncthreads();
-    // every element to its place in the image, or with its index onto the list; as a group is done
-    // with, the same group of the workgroup's next tile is asked for
+    // Every element to its place in the image, or with its index onto the list: a wave collects such
+    // elements in LDS (places from a ballot, no atomic in the way) and appends them to the tile's list sixty-
+    // four at a time at most, reserving the places with one atomic.  As a group is done with, the same
+    // group of the workgroup's next tile is asked for.
+    unsigned waiting = 0;                                     // elements in this wave's part of list_wait: the same in all lanes
+    auto append = [&]() {                                     // the whole wave, converged
+      unsigned at_list = 0;
+      if (lane_id() == 0) at_list = atomicAdd(&listed, waiting);
+      at_list = (unsigned)__builtin_amdgcn_readfirstlane((int)at_list);
+      if ((unsigned)lane_id() < waiting) {
+        list_place[(size_t)base + at_list + (unsigned)lane_id()] = (unsigned short)list_wait[wave][lane_id()][0];
+        list_index[(size_t)base + at_list + (unsigned)lane_id()] = list_wait[wave][lane_id()][1];
+      }
+      waiting = 0;
+    };
 #pragma unroll
     for (int u = 0; u < kSegVecs; ++u) {
 #pragma unroll
       for (int c = 0; c < kVec; ++c) {
         const unsigned at = first + u * (kSegBlock * kVec) + c;
-        if (at < here) {
-          const unsigned b = where[u][c] >> 16;
-          const unsigned offset = min((unsigned)v[u][c] - b * cut.range, cut.range - 1u);
-          const unsigned place = cursor[wave][b] + (where[u][c] & 0xffffu);
-          if (place < cap) {
-            entry[b * cap + place] = offset | (at << 16);
-          } else {
-            const unsigned k = atomicAdd(&listed, 1u);
-            list_place[(size_t)base + k] = (unsigned short)at;
-            list_index[(size_t)base + k] = min((unsigned)v[u][c], elems - 1u);
+        const unsigned b = where[u][c] >> 16;
+        const unsigned offset = min((unsigned)v[u][c] - b * cut.range, cut.range - 1u);
+        const unsigned place = cursor[wave][b] + (where[u][c] & 0xffffu);
+        const bool real = at < here;
+        if (real && place < cap) entry[b * cap + place] = offset | (at << 16);
+        const bool over = real && place >= cap;
+        const unsigned long long overs = __builtin_amdgcn_ballot_w64(over);
+        if (overs != 0ull) {                                  // the same for the whole wave
+          const unsigned more = (unsigned)__builtin_popcountll(overs);
+          if (waiting + more > (unsigned)kWave) append();
+          if (over) {
+            const unsigned k = waiting + __builtin_amdgcn_mbcnt_hi((unsigned)(overs >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)overs, 0u));
+            list_wait[wave][k][0] = at;
+            list_wait[wave][k][1] = min((unsigned)v[u][c], elems - 1u);
           }
+          waiting += more;
         }
       }
       v[u] = fetch_group(tile + gridDim.x, u);
     }
+    if (waiting != 0u) append();
     __syncthreads();
     // the image goes to the tile's slots, eight entries a thread and step (128 bits of offsets, 128 bits
     // of positions), and is emptied on the way
@@ -1467,10 +1491,7 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
       }
     }
     clear_counters();
-    if (threadIdx.x == 0) {
-      list_count[tile] = listed;
-      listed = 0u;
-    }
+    if (threadIdx.x == 0) list_count[tile] = listed;          // settled before the barrier above
     __syncthreads();
   }
 }
@@ -1505,14 +1526,15 @@ __global__ __launch_bounds__(kSegBlock) void seg_gather_kernel(const KArgs a, co
   using TV = T __attribute__((ext_vector_type(4)));
   constexpr int kStream = 0x2;                                // cache policy of the buffer loads: nt
   static_assert(sizeof(T) == 4, "table elements are 32-bit words");
-  __shared__ T slice[kFineSlice + kVec];                      // the range of the table, then an element for the places that hold nothing
+  __shared__ T slice[kSegSlice + kVec];                       // the range of the table, then an element for the places that hold nothing
   const T *table = static_cast<const T *>(a.in[KT]);
   const FineCut cut = plan.cut;
   const unsigned b = blockIdx.x / parts, part = blockIdx.x - b * parts;      // the grid is bins * parts workgroups
   const unsigned lo = b * cut.range, len = min(cut.range, elems - lo), len4 = len & ~3u;
   {
     const __amdgpu_buffer_rsrc_t range_buf = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(table + lo), 0, (int)(len4 * 4u), 0x00020000);
-    constexpr int kAhead = kFineSlice / (kSegBlock * kVec);
+    constexpr int kAhead = kSegSlice / (kSegBlock * kVec);
+    static_assert(kAhead * kSegBlock * kVec == kSegSlice, "whole reads");
     RawI v[kAhead];
 #pragma unroll
     for (int u = 0; u < kAhead; ++u)
@@ -1533,7 +1555,7 @@ __global__ __launch_bounds__(kSegBlock) void seg_gather_kernel(const KArgs a, co
       if (i < len4) *reinterpret_cast<RawI *>(&slice[i]) = v[u];
     }
     if (threadIdx.x < len - len4) slice[len4 + threadIdx.x] = table[lo + len4 + threadIdx.x];
-    if (threadIdx.x == 0) slice[kFineNone] = T();
+    if (threadIdx.x == 0) slice[kSegNone] = T();
   }
   __syncthreads();
   // The range's slots lie one behind the other: a stream of groups of four offsets (64 bits in, 128 bits
@@ -1611,6 +1633,16 @@ __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, 
       factor[k] = __builtin_amdgcn_raw_buffer_load_b128(value_buf, t_lo + e < n ? (int)((t_lo + e) * 4u) : (int)0xfffffff0u, 0, 0x2);
     }
   }
+  // The elements on the tile's list (those that found their slot full) are asked for now as well, a thread
+  // an element: count, then position and index, then the table element -- three round trips in a row that
+  // are over by the time the slots have been put in place.
+  const unsigned listed = list_count[tile];
+  unsigned listed_place = 0;
+  T listed_value = T();
+  if (threadIdx.x < listed) {
+    listed_place = list_place[(size_t)t_lo + threadIdx.x];
+    listed_value = table[list_index[(size_t)t_lo + threadIdx.x]];
+  }
   // the first row that starts in this tile and in the next (the last tile takes the empty rows at the end);
   // the row before reaches into the tile if it ends behind the tile's first position (start[rows] is the
   // number of elements)
@@ -1669,8 +1701,9 @@ __global__ __launch_bounds__(kSegRowsBlock) void seg_rows_kernel(const KArgs a, 
       put(q0, x1, p1);
       q0 += kStep;
     }
-    const unsigned listed = list_count[tile];
-    for (unsigned k = threadIdx.x; k < listed; k += kSegRowsBlock) term[list_place[(size_t)t_lo + k]] = table[list_index[(size_t)t_lo + k]];
+    if (threadIdx.x < listed) term[listed_place] = listed_value;
+    for (unsigned k = threadIdx.x + kSegRowsBlock; k < listed; k += kSegRowsBlock)
+      term[list_place[(size_t)t_lo + k]] = table[list_index[(size_t)t_lo + k]];
   }
   __syncthreads();
   // Rows: the tile's own are those that start in it; the row that reaches into it from before (if there

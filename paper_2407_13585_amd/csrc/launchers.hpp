@@ -141,11 +141,11 @@ template <class Op, class E> hipError_t launch_fold_binned(const KArgs &a, const
 // j / range for every j < limit; the check below walks the range boundaries inside the table, where a
 // wrong quotient would show first, and an empty FineCut (bins == 0) says that this table is not to be
 // cut this way.
-inline FineCut fine_cut(size_t elems, unsigned max_bins = kFineBins) {
+inline FineCut fine_cut(size_t elems, unsigned max_bins = kFineBins, unsigned max_range = kFineSlice) {
   const FineCut none = {0, 0, 0, 0};
   if (elems == 0 || elems > (size_t)kFineIndexLimit || max_bins == 0) return none;
   const unsigned range = (unsigned)(((elems + max_bins - 1) / max_bins + 3) / 4 * 4);
-  if (range > (unsigned)kFineSlice) return none;
+  if (range > max_range) return none;
   unsigned log2_up = 0;
   while ((1u << log2_up) < range) ++log2_up;
   const unsigned k = 24 + log2_up;
@@ -191,19 +191,20 @@ template <class Op, class E> hipError_t launch_fold_fine(const KArgs &a, const L
 
 // ---- segmented fold over a gathered table, sorted through LDS: tables of more than one L2 and at most 2^24 elements ----
 // Ranges as long as LDS takes (so that a slot per range and tile is long and its slack small); a slot holds
-// the mean of a uniform spread plus two standard deviations, as far as the tile's slots fit their LDS image:
-// every entry of a slot is written and read whether in use or not, while the element in a thousand that
-// finds its slot full costs a gather from memory and six bytes on the tile's list.
+// the mean of a uniform spread plus one and a quarter standard deviations (rounded up to whole lines), as far
+// as the tile's slots fit their LDS image: every entry of a slot is written and read whether in use or not,
+// while the few elements in a thousand that find their slot full cost a gather from memory and six bytes on
+// the tile's list each.
 inline SegPlan seg_plan(size_t elems, long long n) {
   SegPlan p = {{0, 0, 0, 0}, 0, 0};
   if (elems == 0 || n <= 0) return p;
-  const unsigned want = (unsigned)std::min<size_t>((elems + kFineSlice - 1) / kFineSlice, kSegMaxBins);
-  p.cut = fine_cut(elems, want);
+  const unsigned want = (unsigned)std::min<size_t>((elems + kSegSlice - 1) / kSegSlice, kSegMaxBins);
+  p.cut = fine_cut(elems, want, kSegSlice);
   if (p.cut.bins == 0 || p.cut.bins > (unsigned)kSegMaxBins) { p.cut.bins = 0; return p; }
   const double mean = (double)kSegTile / p.cut.bins;
   // whole 128-byte lines of values per slot where that costs little (long slots), whole 128-bit groups anyway
   const unsigned grain = mean >= 96.0 ? 32u : 8u;
-  unsigned cap = ((unsigned)(mean + 2.0 * std::sqrt(mean)) + grain - 1) / grain * grain;
+  unsigned cap = ((unsigned)(mean + 1.25 * std::sqrt(mean)) + grain - 1) / grain * grain;
   cap = std::min(cap, (unsigned)kSegImageWords / p.cut.bins / 8 * 8);
   p.cap = std::max(cap, 8u);
   p.tiles = (unsigned)(((size_t)n + kSegTile - 1) / kSegTile);
@@ -260,9 +261,16 @@ hipError_t launch_foldseg_sorted(const KArgs &a, const LaunchCtx &c) {
   hipError_t e = launch_k(&seg_bin_kernel<KI>, std::min(p.tiles, units), c.stream, (int)kSegBlock, a, offsets, places,
                           list_place, list_index, list_count, p, elems);
   if (e != hipSuccess) return e;
-  // a table range is read into LDS by every workgroup that works on it: one workgroup per compute unit in all
-  // (they fill its LDS; with two rounds of workgroups the second round's range reads stood in the open: 106 us against 102)
-  const unsigned parts = std::max(1u, (units + p.cut.bins - 1) / p.cut.bins);
+  // A table range is read into LDS by every workgroup that works on it, and a workgroup fills the LDS of a compute
+  // unit: as few parts per range as give whole rounds of workgroups, or nearly (128 ranges in two parts each on 256
+  // units: 102 us; in four parts, two rounds: 106 us; 114 ranges in three parts, a round and a third: 110 us)
+  unsigned parts = 1;
+  {
+    // rounds of workgroups times the share of the work a workgroup takes, for one to eight parts per range
+    auto cost = [&](unsigned q) { return (double)((p.cut.bins * q + units - 1) / units) / (p.cut.bins * q); };
+    for (unsigned q = 2; q <= 8; ++q)
+      if (cost(q) < cost(parts) * 0.999) parts = q;
+  }
   e = launch_k(&seg_gather_kernel<T, KT>, p.cut.bins * parts, c.stream, (int)kSegBlock, a, static_cast<const unsigned short *>(offsets),
                gathered, first_row, p, elems, parts);
   if (e != hipSuccess) return e;
