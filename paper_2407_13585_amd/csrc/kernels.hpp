@@ -1318,9 +1318,9 @@ __global__ __launch_bounds__(kBlock) void foldseg_blocked_kernel(const KArgs a, 
 //     range's offsets into values, slot for slot (the slots of a range lie one behind the other).
 //  3. seg_rows_kernel: a workgroup per tile puts the tile's values (one slot per range, then those
 //     of the list, gathered from memory) back at their positions in LDS, multiplies by the tile's
-//     stretch of `values`, and adds up the rows, four lanes a row.  A row belongs to the tile it starts in; the part of a row
-//     that lies in another tile than its own, and the part of a tile's last row when the row goes
-//     on, are kept per tile,
+//     stretch of `values`, and adds up the rows, four lanes a row.  A row belongs to the tile it
+//     starts in; the part of a row that lies in another tile than its own, and the part of a
+//     tile's last row when the row goes on, are kept per tile,
 //  4. and seg_join_kernel adds those up, tile after tile, for the rows that cross a tile boundary.
 //
 // Every element has one place at every stage and every sum a fixed order: the same bits on every
@@ -1341,7 +1341,7 @@ constexpr unsigned kSegNothing = kSegNone | (kSegNoPlace << 16);
 static_assert(kSegNone < 65536u, "offsets are 16-bit numbers");
 static_assert(kSegVecs * kSegBlock * kVec == kSegTile && kSegTile <= (int)kSegNoPlace, "whole reads; positions are 16-bit numbers");
 
-// Where the pieces lie in the workspace (element counts; every array starts on a 256-byte boundary).
+// How a launch is cut: the table into ranges, the elements into tiles, a slot per (range, tile).
 struct SegPlan {
   FineCut cut;
   unsigned cap;        // entries per slot, a multiple of eight
@@ -1394,7 +1394,7 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
   if (threadIdx.x == 0) listed = 0u;
   __syncthreads();
   for (unsigned tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    if (threadIdx.x == 0) listed = 0u;                      // read last before the barrier that ended the tile before, added to after the next two
+    if (threadIdx.x == 0) listed = 0u;                      // read last before the barrier that ended the tile before; added to after the next two
     const unsigned first = threadIdx.x * kVec;              // this thread's first position in the tile, group 0
     const unsigned base = tile * kSegTile;
     // rank of every element among the wave's elements of its range (range << 16 | rank is kept).  An index
