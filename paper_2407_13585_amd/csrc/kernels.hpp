@@ -886,7 +886,10 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
 #pragma unroll
   for (int u = 0; u < kFineVecs; ++u) v[u] = fetch_group(blockIdx.x, u);
   // between tiles the counters are zero and every place of the image holds kFineNone
-  for (unsigned k = threadIdx.x; k < kFineWaves * kFineBins; k += kFineBlock) (&cursor[0][0])[k] = 0u;
+  auto clear_counters = [&]() {                             // a wave its own
+    for (unsigned b = (unsigned)lane_id(); b < (unsigned)kFineBins; b += kWave) cursor[wave][b] = 0u;
+  };
+  clear_counters();
   for (unsigned q = threadIdx.x; q < kChunks; q += kFineBlock) image[q] = nothing;
   __syncthreads();
   for (unsigned tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
@@ -970,8 +973,10 @@ __global__ __launch_bounds__(kFineBlock) void bin_fine_kernel(const KArgs a, Con
                                                (int)(tile * (kFineSlotWords * 4u)), 0);
       }
     }
-    for (unsigned k = threadIdx.x; k < kFineWaves * kFineBins; k += kFineBlock) (&cursor[0][0])[k] = 0u;
-    __syncthreads();
+    // No barrier here.  A wave goes on to rank the next tile in its own counters, which it clears itself;
+    // the counts are not looked at by others, and the image not written to again, before the barriers that
+    // follow the ranking, which no wave passes before all are done with this tile.
+    clear_counters();
   }
   if (blockIdx.x == 0 && threadIdx.x < n - n4) acc = Op::apply(acc, E::template eval<0>(a, (int)(n4 + threadIdx.x)));
   // one partial per workgroup; the second kernel combines them with its own
@@ -1490,9 +1495,11 @@ __global__ __launch_bounds__(kSegBlock) void seg_bin_kernel(const KArgs a, unsig
         *reinterpret_cast<Chunk *>(places + (size_t)tile * words + q * 8u) = p;
       }
     }
+    // No barrier here.  A wave goes on to rank the next tile in its own counters, which it clears itself;
+    // the counts are not looked at by others, and the image and the list not written to again, before the
+    // barriers that follow the ranking, which no wave passes before all are done with this tile.
     clear_counters();
     if (threadIdx.x == 0) list_count[tile] = listed;          // settled before the barrier above
-    __syncthreads();
   }
 }
 
