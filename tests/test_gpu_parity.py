@@ -295,6 +295,9 @@ def test_spmv_sorted_through_lds(shape):
         prog.run()
         compare(3, w, env, prog, w.graph.outputs(), "sorted")
         assert prog.control_words()[1] == 0
+        first = prog.fetch("y").copy()
+        prog.run()                                            # every sum has a fixed order: the same bits again
+        P.assert_bit_exact(prog.fetch("y"), first, "sorted: second launch")
     run_all_modes(3, w, env)
 
 
@@ -334,6 +337,9 @@ def test_perm_gather_binned(table, m, spread):
         prog.run()
         compare(2, w, env, prog, w.graph.outputs(), "binned")
         assert prog.control_words()[1] == 0
+        first = prog.fetch("r").copy()
+        prog.run()                                            # every sum has a fixed order: the same bits again
+        P.assert_bit_exact(prog.fetch("r"), first, "binned: second launch")
     run_all_modes(2, w, env)
 
 
